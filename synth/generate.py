@@ -1,0 +1,179 @@
+"""Seeded generators for every input the local-update SGD path consumes.
+
+The recipes follow the workloads named for this build (Gaussian-mixture
+classification sets, CIFAR-shaped uniform images with a class offset, flat
+parameter vectors for the averaging stress).  They stand in for the CIFAR-10 /
+CIFAR-100 image sets of the paper's Sec. 5.1 ("Platform" / "Datasets"): same
+feature count (32*32*3 = 3072), same sample count (50 000) and class count, but
+no item of those sets is reproduced.
+
+Everything is drawn from numpy's counter-based Philox generator keyed by the
+caller's seed, so a (seed, recipe) pair always gives the same bytes.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+
+
+def _rng(seed: int, stream: int) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[int(seed) & (2**64 - 1), int(stream)]))
+
+
+def bf16_representable(a: np.ndarray) -> np.ndarray:
+    """Round an fp32 array to the nearest bfloat16 value (ties to even) and
+    return it as fp32.  Used only to *define* datasets whose features are stored
+    in bf16; it is data preparation, not part of the method."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    u = a.view(np.uint32).astype(np.uint64)
+    bias = ((u >> 16) & 1) + 0x7FFF
+    r = ((u + bias) >> 16) << 16
+    return r.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+def gaussian_mixture(seed: int, n: int, d: int, n_classes: int, mean_sd: float,
+                     noise_sd: float = 1.0) -> Tuple[np.ndarray, np.ndarray]:
+    """n points in R^d: label uniform over classes, x = mean[label] + noise.
+    Class means ~ N(0, mean_sd^2 I), noise ~ N(0, noise_sd^2 I)."""
+    g = _rng(seed, 1)
+    means = (g.standard_normal((n_classes, d)) * mean_sd).astype(np.float32)
+    labels = g.integers(0, n_classes, size=n, dtype=np.int64).astype(np.int32)
+    x = g.standard_normal((n, d), dtype=np.float32)
+    if noise_sd != 1.0:
+        x *= np.float32(noise_sd)
+    x += means[labels]
+    return x, labels
+
+
+def image_like(seed: int, n: int, d: int, n_classes: int, offset_sd: float = 0.1
+               ) -> Tuple[np.ndarray, np.ndarray]:
+    """CIFAR-shaped stand-in: pixels U[0,1) plus a per-class, per-feature mean
+    offset drawn once from offset_sd * N(0,1)."""
+    g = _rng(seed, 2)
+    offs = (g.standard_normal((n_classes, d)) * offset_sd).astype(np.float32)
+    labels = g.integers(0, n_classes, size=n, dtype=np.int64).astype(np.int32)
+    x = g.random((n, d), dtype=np.float32)
+    x += offs[labels]
+    return x, labels
+
+
+def param_count(dims: List[int]) -> int:
+    """P for an MLP with layer widths dims = [d_0, ..., d_L], biases included."""
+    return int(sum(dims[l] * dims[l + 1] + dims[l + 1] for l in range(len(dims) - 1)))
+
+
+def init_params(seed: int, dims: List[int], zero: bool = False) -> np.ndarray:
+    """Initial point x_1 as one flat fp32 vector.  Layout per layer l = 1..L:
+    W_l stored row-major as [d_{l-1}, d_l], then b_l [d_l].  Weights are
+    He-initialised, N(0, 2/fan_in); biases are zero.  zero=True gives x_1 = 0."""
+    p = param_count(dims)
+    x = np.zeros(p, dtype=np.float32)
+    if zero:
+        return x
+    g = _rng(seed, 3)
+    off = 0
+    for l in range(len(dims) - 1):
+        fan_in, fan_out = dims[l], dims[l + 1]
+        w = g.standard_normal(fan_in * fan_out, dtype=np.float32)
+        w *= np.float32(np.sqrt(2.0 / fan_in))
+        x[off:off + fan_in * fan_out] = w
+        off += fan_in * fan_out + fan_out
+    return x
+
+
+def flat_stress(seed: int, m: int, p: int, x_sd: float = 0.1, g_sd: float = 1e-3
+                ) -> Tuple[np.ndarray, np.ndarray]:
+    """Averaging / update stress inputs: X[m,p] ~ N(0, x_sd^2) (variance 0.01
+    by default) and explicit gradients G[m,p] ~ N(0, g_sd^2)."""
+    g = _rng(seed, 4)
+    x = g.standard_normal((m, p), dtype=np.float32) * np.float32(x_sd)
+    grad = g.standard_normal((m, p), dtype=np.float32) * np.float32(g_sd)
+    return x, grad
+
+
+def quad_problem(seed: int, m: int, p: int, common_a: bool = False
+                 ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Constants of the diagonal quadratic test objective: worker i minimises
+    0.5 * sum_p a[i,p] (x_p - c[i,p])^2.  Returns (a[m,p] in [0.5, 2), c[m,p],
+    x1[p]).  common_a=True gives every worker the same curvature."""
+    g = _rng(seed, 5)
+    a = (0.5 + 1.5 * g.random((m, p), dtype=np.float32)).astype(np.float32)
+    if common_a:
+        a[:] = a[0]
+    c = g.standard_normal((m, p), dtype=np.float32)
+    x1 = g.standard_normal(p, dtype=np.float32)
+    return a, c, x1
+
+
+@dataclass
+class Workload:
+    """One named configuration: model shape, optimiser scalars, schedule and the
+    generated inputs."""
+    name: str
+    dims: List[int]
+    m: int
+    B: int
+    N: int
+    n_classes: int
+    lr: float
+    beta: float
+    wd: float
+    bf16: bool
+    E: int
+    K: int
+    tau0: int
+    adaptive: bool
+    interval: int
+    seed: int
+    data: Optional[np.ndarray] = None
+    labels: Optional[np.ndarray] = None
+    x1: Optional[np.ndarray] = None
+    extra: Dict[str, object] = field(default_factory=dict)
+
+    @property
+    def P(self) -> int:
+        return param_count(self.dims)
+
+
+# The named configurations.  K / interval for cfg4 are not fixed by the task
+# statement; the values here (K=2000, I=200) are this build's choice.
+CONFIGS: Dict[str, dict] = {
+    "cfg1": dict(dims=[64, 10], m=4, B=32, N=20000, n_classes=10, lr=0.05, beta=0.0, wd=0.0,
+                 bf16=False, E=20000, K=200, tau0=4, adaptive=False, interval=0,
+                 data="mixture", mean_sd=2.0, zero_init=True),
+    "cfg2": dict(dims=[784, 256, 10], m=8, B=64, N=60000, n_classes=10, lr=0.1, beta=0.9, wd=0.0,
+                 bf16=False, E=8192, K=2000, tau0=5, adaptive=False, interval=0,
+                 data="mixture", mean_sd=1.0, zero_init=False),
+    "cfg3": dict(dims=[3072, 1024, 1024, 10], m=16, B=128, N=50000, n_classes=10, lr=0.05,
+                 beta=0.9, wd=0.0, bf16=True, E=8192, K=10000, tau0=20, adaptive=True,
+                 interval=500, data="image", zero_init=False),
+    "cfg4": dict(dims=[3072, 2048, 2048, 2048, 10], m=64, B=32, N=50000, n_classes=10, lr=0.02,
+                 beta=0.9, wd=0.0, bf16=True, E=8192, K=2000, tau0=10, adaptive=True,
+                 interval=200, data="image", zero_init=False),
+}
+
+
+def make_workload(name: str, seed: int = 20181008, **override) -> Workload:
+    """Build a Workload with its inputs.  Keyword overrides replace any recipe
+    field (e.g. N=2000 for a quick test, m=2, dims=[...])."""
+    spec = dict(CONFIGS[name])
+    spec.update(override)
+    kind = spec.pop("data")
+    mean_sd = spec.pop("mean_sd", 1.0)
+    zero_init = spec.pop("zero_init", False)
+    dims = list(spec["dims"])
+    n, ncls = int(spec["N"]), int(spec["n_classes"])
+    if kind == "mixture":
+        data, labels = gaussian_mixture(seed, n, dims[0], ncls, mean_sd)
+    elif kind == "image":
+        data, labels = image_like(seed, n, dims[0], ncls)
+    else:
+        raise ValueError(kind)
+    if spec["bf16"]:
+        # features of the bf16 configurations are *defined* as bf16 values
+        data = bf16_representable(data)
+    x1 = init_params(seed, dims, zero=zero_init)
+    spec["E"] = min(int(spec["E"]), n)
+    return Workload(name=name, seed=seed, data=data, labels=labels, x1=x1, **spec)
