@@ -1,0 +1,196 @@
+/*
+ * localcomm -- local-update SGD (periodic-averaging SGD, PASGD) with the
+ * AdaComm communication-period controller, for one AMD MI355X (gfx950).
+ *
+ * Method: Wang & Joshi, "Adaptive Communication Strategies to Achieve the Best
+ * Error-Runtime Trade-off in Local-Update SGD".  The m workers of the paper are
+ * m model replicas held on one GPU as the rows of X[m, P]; a local SGD step is a
+ * set of per-replica matrix products followed by a fused update; the averaging
+ * step is a reduce over the m rows written back to every row.
+ *
+ * Conventions
+ *   - Every function is extern "C", takes plain pointers and sizes, never throws
+ *     and never aborts.  Unless stated otherwise it returns LC_OK (0) or a
+ *     negative lc_status; lc_strerror() names it.
+ *   - "device" pointers are HIP device memory owned by the caller (for example
+ *     torch tensors); the library never frees or reallocates them.  "host"
+ *     pointers are ordinary host memory.  The handle owns only host metadata.
+ *   - All device work is enqueued on the stream given to lc_attach() and is
+ *     asynchronous unless the function says it synchronises.
+ *   - Parameter layout inside one replica row (P floats, fp32): for each layer
+ *     l = 1..L the weight matrix W_l stored row-major as [d_{l-1}, d_l] followed
+ *     by the bias b_l [d_l].  Rows of X and V are separated by
+ *     lc_row_stride(P) floats (P rounded up to a multiple of 64, so that every
+ *     row starts on a 256-byte boundary); the padding must be zero and stays zero.
+ */
+#ifndef LOCALCOMM_H
+#define LOCALCOMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LC_MAX_LAYERS 8
+
+typedef enum {
+    LC_OK = 0,
+    LC_ERR_ARG = -1,        /* invalid argument (null pointer, size, range) */
+    LC_ERR_MODEL = -2,      /* inconsistent model description or P != P(model) */
+    LC_ERR_STATE = -3,      /* call out of order (e.g. not attached) */
+    LC_ERR_ALIGN = -4,      /* a device pointer is not 256-byte aligned */
+    LC_ERR_WORKSPACE = -5,  /* scratch buffer too small */
+    LC_ERR_HIP = -6,        /* a HIP call failed; lc_last_hip_error() has the code */
+    LC_ERR_NONFINITE = -7,  /* the evaluated loss is not finite */
+    LC_ERR_UNSUPPORTED = -8 /* shape outside what the kernels handle */
+} lc_status;
+
+typedef enum { LC_KIND_QUAD = 0, LC_KIND_MLP = 1 } lc_kind;
+typedef enum { LC_GEMM_FP32 = 0, LC_GEMM_BF16 = 1 } lc_gemm_dtype;
+
+/* Model and optimiser description.
+ *   LC_KIND_MLP : ReLU multi-layer perceptron with softmax cross-entropy loss;
+ *                 n_layers = L weight layers, dims[0..L]; n_layers = 1 is
+ *                 softmax regression.
+ *   LC_KIND_QUAD: test objective; worker i minimises 0.5 sum_p a[i,p] (x_p -
+ *                 c[i,p])^2 with the exact gradient (no sampling); dims[0] = P.
+ *   gemm        : LC_GEMM_BF16 rounds activations, deltas and the weight operand
+ *                 of every matrix product to bfloat16 (accumulation fp32, master
+ *                 weights and momentum fp32); the dataset is then bf16 too. */
+typedef struct {
+    int32_t kind;                     /* lc_kind */
+    int32_t n_layers;
+    int32_t dims[LC_MAX_LAYERS + 1];
+    int32_t B;                        /* mini-batch size per worker, 1..128 */
+    int64_t N;                        /* dataset size */
+    int32_t E;                        /* lc_loss() uses the first E samples, E <= N */
+    float lr;                         /* learning rate eta */
+    float beta;                       /* momentum factor, 0 = plain SGD */
+    float wd;                         /* weight decay added to the gradient */
+    int32_t gemm;                     /* lc_gemm_dtype */
+} lc_model;
+
+typedef struct lc_handle lc_handle;
+
+/* Human-readable name of a status code (static string). */
+const char* lc_strerror(int status);
+/* Raw hipError_t of the last failing HIP call on this handle (0 if none). */
+int lc_last_hip_error(const lc_handle* h);
+
+/* P(model): parameters of one replica, biases included (Sec. 2: x in R^d).
+ * Negative lc_status if the description is invalid. */
+int64_t lc_param_count(const lc_model* model);
+/* Distance in floats between consecutive rows of X and of V. */
+int64_t lc_row_stride(int64_t P);
+
+/* Create a run of m workers with P parameters each (Sec. 2, PASGD: "m worker
+ * nodes ... all workers start at the same initial point").  seed keys the
+ * mini-batch index stream: sample b of worker i at local iteration k is
+ *   idx = mix(mix(mix(seed + G (k+1)) + G (i+1)) + G (b+1)) mod N,
+ * mix = SplitMix64 output function, G = 0x9E3779B97F4A7C15 (sampling with
+ * replacement from the whole set, an independent stream per worker).
+ * The iteration counter starts at k = 0.  No device memory is touched.
+ * Errors: LC_ERR_ARG (m < 1, null), LC_ERR_MODEL (P != lc_param_count, bad dims,
+ * B outside 1..128, E > N). */
+int lc_init(int m, int64_t P, const lc_model* model, uint64_t seed, lc_handle** out);
+void lc_destroy(lc_handle* h);
+
+/* Bytes of device scratch lc_attach() needs for this run. */
+size_t lc_workspace_bytes(const lc_handle* h);
+
+/* Bind caller-owned device memory and the stream.
+ *   X, V     : device, fp32 [m, lc_row_stride(P)], 256-byte aligned.  X holds the
+ *              models, V the per-worker momentum buffers (Sec. 5.3: each worker
+ *              keeps its own buffer).  Contents are taken as they are.
+ *   scratch  : device, >= lc_workspace_bytes(), 256-byte aligned; zeroed here.
+ *   data     : device, the dataset [N, d_0] row-major; fp32 for LC_GEMM_FP32,
+ *              bfloat16 for LC_GEMM_BF16.  NULL for LC_KIND_QUAD.
+ *   labels   : device, int32 [N], values in [0, d_L).  NULL for LC_KIND_QUAD.
+ *   stream   : a hipStream_t (NULL = the default stream).
+ * Synchronises the stream once.  Errors: LC_ERR_ARG, LC_ERR_ALIGN,
+ * LC_ERR_WORKSPACE, LC_ERR_HIP. */
+int lc_attach(lc_handle* h, void* X, void* V, void* scratch, size_t scratch_bytes,
+              const void* data, const int32_t* labels, void* stream);
+
+/* LC_KIND_QUAD only: curvatures a and centres c, device fp32 [m, lc_row_stride(P)]. */
+int lc_attach_quad(lc_handle* h, const float* a, const float* c);
+
+/* tau local iterations on every worker, no communication (Sec. 2, the
+ * "otherwise" branch of the PASGD update rule): sample a mini-batch, forward,
+ * softmax cross-entropy, backward, x <- x - lr v with v <- beta v + g.
+ * The iteration counter advances by tau.  Asynchronous.
+ * Errors: LC_ERR_ARG (tau < 1), LC_ERR_STATE, LC_ERR_HIP. */
+int lc_local_steps(lc_handle* h, int tau);
+
+/* The averaging step (Sec. 2, the "k mod tau = 0" branch): every row of X is
+ * replaced by the mean of all rows, X <- X J with J = 11^T/m (Appendix).  V is
+ * not touched.  Afterwards all rows are bit-identical; calling it twice changes
+ * nothing more.  Asynchronous. */
+int lc_average(lc_handle* h);
+
+/* Training loss of the averaged model F(x_bar) on the first E samples (the
+ * quantity the basic update rule of Sec. 4.2 reads).  Always evaluated with
+ * fp32 operands.  Does not modify X or V.  Synchronises the stream; *out is a
+ * host double.  Errors: LC_ERR_NONFINITE (and *out is still written). */
+int lc_loss(lc_handle* h, double* out);
+
+/* AdaComm basic update rule (Sec. 4.2): tau_l = ceil( sqrt(F_l / F_0) * tau_0 ),
+ * not below 1.  Pure host function, evaluated in IEEE double in exactly this
+ * order: ratio = Fl / F0; root = sqrt(ratio); prod = root * tau0; ceil(prod).
+ * Returns tau_l >= 1, or LC_ERR_ARG for F0 <= 0, Fl < 0, a non-finite input,
+ * tau0 < 1, or a result that does not fit an int. */
+int adacomm_next_tau(double F0, double Fl, int tau0);
+
+/* Whole schedule on the host side of the library: K iterations as periods of
+ * tau local steps each followed by lc_average(), the last period truncated.
+ * adaptive != 0: F_0 = lc_loss() at entry; at the first averaging step at or
+ * after every multiple of `interval` iterations (the paper's wall-clock interval
+ * T_0 of Sec. 4, counted in iterations) F_l = lc_loss() and tau for the
+ * following periods is adacomm_next_tau(F_0, F_l, tau0).
+ *   sched_k, sched_tau : host arrays of capacity cap receiving the decisions
+ *                        (iteration, tau), the first being (k at entry, tau0)
+ *   n_sched            : host, number of decisions made (may exceed cap)
+ *   rounds             : host, number of averaging steps performed
+ * Synchronises before returning. */
+int lc_run(lc_handle* h, int64_t K, int tau0, int adaptive, int64_t interval,
+           int64_t* sched_k, int32_t* sched_tau, int cap, int32_t* n_sched, int64_t* rounds);
+
+/* One (momentum-)SGD update of every worker from explicit gradients G (device,
+ * fp32 [m, lc_row_stride(P)], 256-byte aligned): g <- G + wd x; v <- beta v + g;
+ * x <- x - lr v (mini-batch SGD update of Sec. 2).  The iteration counter is
+ * unchanged.  Asynchronous. */
+int lc_set_grad(lc_handle* h, const void* G);
+int lc_update_from_grad(lc_handle* h);
+
+/* Fused form of lc_update_from_grad() followed by lc_average() for the fully
+ * synchronous case tau = 1 (Sec. 2, special case): one pass over X, V and G. */
+int lc_update_from_grad_and_average(lc_handle* h);
+
+/* State access for tests and checkpoints.  X_host / V_host are host fp32 [m, P]
+ * (dense, no row padding); either may be NULL.  Both calls synchronise. */
+int lc_get_state(lc_handle* h, float* X_host, float* V_host, int64_t* k);
+int lc_set_state(lc_handle* h, const float* X_host, const float* V_host, int64_t k);
+
+int lc_set_lr(lc_handle* h, float lr);
+
+/* Mini-batch loss of every worker at its last local step: host float [m].
+ * Synchronises. */
+int lc_get_local_losses(lc_handle* h, float* losses_host);
+/* Dataset indices drawn at the last local step: host int32 [m, B].  Synchronises. */
+int lc_get_last_indices(lc_handle* h, int32_t* idx_host);
+
+/* Per-kernel timing for measurement: while enabled, every launch of the named
+ * kernel class is bracketed by HIP events on the run's stream.
+ * lc_timing_read() synchronises and returns the number of launches and their
+ * summed duration since lc_timing_begin().  which: 0 = backward+update kernel,
+ * 1 = forward kernel, 2 = averaging kernel, 3 = update-from-gradient kernel,
+ * 4 = fused update+average kernel. */
+int lc_timing_begin(lc_handle* h, int which);
+int lc_timing_read(lc_handle* h, int64_t* launches, double* total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

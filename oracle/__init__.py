@@ -55,6 +55,8 @@ def lib() -> C.CDLL:
     L.orc_param_count.argtypes = [mp]
     L.orc_mlp_loss_grad.restype = C.c_float
     L.orc_mlp_loss_grad.argtypes = [mp, fp, fp, ip, lp, fp]
+    L.orc_mlp_preactivations.restype = None
+    L.orc_mlp_preactivations.argtypes = [mp, fp, fp, lp, fp]
     L.orc_sgd_update.restype = None
     L.orc_sgd_update.argtypes = [C.c_int64, fp, fp, fp, C.c_float, C.c_float, C.c_float]
     L.orc_next_tau.restype = C.c_int
@@ -142,6 +144,22 @@ def mlp_loss_grad(md: OrcModel, x: np.ndarray, data: np.ndarray, labels: np.ndar
     loss = lib().orc_mlp_loss_grad(C.byref(md), _f(x), _f(data), labels.ctypes.data_as(C.POINTER(C.c_int32)),
                                    ix.ctypes.data_as(C.POINTER(C.c_int64)), _f(g) if want_grad else None)
     return float(loss), g
+
+
+def mlp_preactivations(md: OrcModel, x: np.ndarray, data: np.ndarray, idx: Sequence[int]) -> List[np.ndarray]:
+    """Pre-ReLU values of the hidden layers, one [B, d_l] array per hidden layer."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    data = np.ascontiguousarray(data, dtype=np.float32)
+    ix = np.ascontiguousarray(idx, dtype=np.int64)
+    hidden = [md.dims[l] for l in range(1, md.n_layers)]
+    z = np.zeros((md.B, max(1, sum(hidden))), np.float32)
+    if hidden:
+        lib().orc_mlp_preactivations(C.byref(md), _f(x), _f(data), ix.ctypes.data_as(C.POINTER(C.c_int64)), _f(z))
+    out, o = [], 0
+    for d in hidden:
+        out.append(z[:, o:o + d].copy())
+        o += d
+    return out
 
 
 def sgd_update(x: np.ndarray, v: np.ndarray, g: np.ndarray, lr: float, beta: float, wd: float) -> None:

@@ -70,9 +70,10 @@ int64_t orc_param_count(const orc_model* md) {
  *   x    : master parameters (biases are read from here)
  *   act  : act[l] points at the sample's d_l activations; act[0] is the input
  * Hidden layers apply ReLU; act[L] receives the logits.  q != 0 rounds every
- * hidden activation to bf16 when it is produced. */
+ * hidden activation to bf16 when it is produced.  zpre (optional) receives the
+ * values before the ReLU. */
 static void forward_sample(const orc_model* md, const float* w_op, const float* x,
-                           float* const* act, double* acc, int q) {
+                           float* const* act, double* acc, int q, float* const* zpre) {
     int64_t off = 0;
     for (int l = 1; l <= md->n_layers; ++l) {
         const int din = md->dims[l - 1], dout = md->dims[l];
@@ -86,6 +87,7 @@ static void forward_sample(const orc_model* md, const float* w_op, const float* 
         }
         for (int c = 0; c < dout; ++c) {
             float z = (float)(acc[c] + (double)bias[c]);
+            if (zpre && zpre[l]) zpre[l][c] = z;
             if (l < md->n_layers) {
                 z = z > 0.0f ? z : 0.0f;
                 if (q) z = orc_bf16_round(z);
@@ -154,7 +156,7 @@ float orc_mlp_loss_grad(const orc_model* md, const float* x, const float* data,
         for (int j = 0; j < md->dims[0]; ++j) A[0][(int64_t)b * md->dims[0] + j] = q ? orc_bf16_round(row[j]) : row[j];
         float* act[ORC_MAX_LAYERS + 1];
         for (int l = 0; l <= L; ++l) act[l] = A[l] + (int64_t)b * md->dims[l];
-        forward_sample(md, w_op, x, act, acc, q);
+        forward_sample(md, w_op, x, act, acc, q, NULL);
         const int y = labels[idx[b]];
         loss_sum += softmax_nll(act[L], C, y, p);
         /* dZ_L = (p - onehot) / B : gradient of the batch-mean loss */
@@ -215,6 +217,42 @@ float orc_mlp_loss_grad(const orc_model* md, const float* x, const float* data,
     free(p);
     free(w_op);
     return loss;
+}
+
+void orc_mlp_preactivations(const orc_model* md, const float* x, const float* data,
+                             const int64_t* idx, float* zout) {
+    const int L = md->n_layers, B = md->B, q = md->bf16;
+    const int64_t P = orc_param_count(md);
+    const int dmax = max_dim(md);
+    int hidden = 0;
+    for (int l = 1; l < L; ++l) hidden += md->dims[l];
+    float* w_op = (float*)malloc(sizeof(float) * (size_t)P);
+    memcpy(w_op, x, sizeof(float) * (size_t)P);
+    if (q) {
+        int64_t off = 0;
+        for (int l = 1; l <= L; ++l) {
+            const int64_t nw = (int64_t)md->dims[l - 1] * md->dims[l];
+            for (int64_t j = 0; j < nw; ++j) w_op[off + j] = orc_bf16_round(w_op[off + j]);
+            off += nw + md->dims[l];
+        }
+    }
+    double* acc = (double*)malloc(sizeof(double) * (size_t)dmax);
+    float* buf[ORC_MAX_LAYERS + 1];
+    for (int l = 0; l <= L; ++l) buf[l] = (float*)malloc(sizeof(float) * (size_t)md->dims[l]);
+    for (int b = 0; b < B; ++b) {
+        const float* row = data + idx[b] * (int64_t)md->dims[0];
+        for (int j = 0; j < md->dims[0]; ++j) buf[0][j] = q ? orc_bf16_round(row[j]) : row[j];
+        float* zp[ORC_MAX_LAYERS + 1];
+        int o = 0;
+        for (int l = 0; l <= L; ++l) {
+            zp[l] = (l >= 1 && l < L) ? zout + (int64_t)b * hidden + o : NULL;
+            if (l >= 1 && l < L) o += md->dims[l];
+        }
+        forward_sample(md, w_op, x, buf, acc, q, zp);
+    }
+    for (int l = 0; l <= L; ++l) free(buf[l]);
+    free(acc);
+    free(w_op);
 }
 
 void orc_sgd_update(int64_t P, float* x, float* v, const float* g, float lr, float beta, float wd) {
@@ -384,7 +422,7 @@ double orc_loss(orc_state* s) {
                 float* act[ORC_MAX_LAYERS + 1];
                 act[0] = (float*)(s->data + (int64_t)e * md->dims[0]); /* read only */
                 for (int l = 1; l <= L; ++l) act[l] = buf[l];
-                forward_sample(md, xbar, xbar, act, acc, 0);
+                forward_sample(md, xbar, xbar, act, acc, 0, NULL);
                 per[e] = softmax_nll(act[L], C, s->labels[e], NULL);
             }
             for (int l = 1; l <= L; ++l) free(buf[l]);

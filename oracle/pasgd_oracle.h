@@ -70,6 +70,12 @@ int64_t orc_param_count(const orc_model* md);
 float orc_mlp_loss_grad(const orc_model* md, const float* x, const float* data,
                         const int32_t* labels, const int64_t* idx, float* grad);
 
+/* Values Z_l before the ReLU of every hidden layer l = 1..L-1 for the samples
+ * idx[0..B): zout is [B][d_1 + ... + d_{L-1}].  Lets a test see which ReLU gates
+ * sit so close to zero that accumulation order decides them. */
+void orc_mlp_preactivations(const orc_model* md, const float* x, const float* data,
+                             const int64_t* idx, float* zout);
+
 /* One (momentum-)SGD update  g += wd x;  v = beta v + g;  x = x - lr v
  * (mini-batch SGD update rule of Sec. 2; per-worker buffer of Sec. 5.3). */
 void orc_sgd_update(int64_t P, float* x, float* v, const float* g, float lr, float beta, float wd);

@@ -1,0 +1,489 @@
+// Host side of liblocalcomm: the C ABI declared in include/localcomm.h.
+// Argument checking, workspace carving, kernel sequencing, the AdaComm
+// controller and the schedule driver live here; all arithmetic of the method
+// on parameters runs in the kernels.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "lc_internal.h"
+
+using namespace lc;
+
+#define LC_HIP(h, call)                             \
+    do {                                            \
+        hipError_t e__ = (call);                    \
+        if (e__ != hipSuccess) {                    \
+            (h)->last_hip = static_cast<int>(e__);  \
+            return LC_ERR_HIP;                      \
+        }                                           \
+    } while (0)
+
+namespace lc {
+
+void timing_start(lc_handle* h, int which) {
+    if (h->timing_which != which) return;
+    if (h->ev_used + 2 > h->ev_pool.size()) {
+        for (int i = 0; i < 256; ++i) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return;
+            h->ev_pool.push_back(e);
+        }
+    }
+    (void)hipEventRecord(h->ev_pool[h->ev_used], h->stream);
+}
+
+void timing_stop(lc_handle* h, int which) {
+    if (h->timing_which != which) return;
+    if (h->ev_used + 2 > h->ev_pool.size()) return;
+    (void)hipEventRecord(h->ev_pool[h->ev_used + 1], h->stream);
+    h->ev_used += 2;
+}
+
+}  // namespace lc
+
+namespace {
+
+bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+
+int padded_batch(int B) { return B <= 32 ? 32 : (B <= 64 ? 64 : 128); }
+
+int model_ok(const lc_model* md) {
+    if (!md) return LC_ERR_ARG;
+    if (md->kind == LC_KIND_QUAD) return md->dims[0] >= 1 ? LC_OK : LC_ERR_MODEL;
+    if (md->kind != LC_KIND_MLP) return LC_ERR_MODEL;
+    if (md->n_layers < 1 || md->n_layers > LC_MAX_LAYERS) return LC_ERR_MODEL;
+    for (int l = 0; l <= md->n_layers; ++l)
+        if (md->dims[l] < 1) return LC_ERR_MODEL;
+    if (md->dims[md->n_layers] > 1024) return LC_ERR_UNSUPPORTED;  // classes per sample handled by one thread
+    if (md->B < 1 || md->B > 128) return LC_ERR_MODEL;
+    if (md->N < 1 || md->N > 2147483647LL) return LC_ERR_MODEL;
+    if (md->E < 1 || md->E > md->N) return LC_ERR_MODEL;
+    if (md->gemm != LC_GEMM_FP32 && md->gemm != LC_GEMM_BF16) return LC_ERR_MODEL;
+    return LC_OK;
+}
+
+// Carves the scratch buffer.  With base == nullptr only the size is computed.
+struct Carver {
+    char* base;
+    size_t off;
+    void* take(size_t bytes) {
+        off = static_cast<size_t>(round_up(static_cast<int64_t>(off), 256));
+        void* p = base ? base + off : nullptr;
+        off += bytes;
+        return p;
+    }
+};
+
+size_t carve(lc_handle* h, char* base) {
+    Carver c{base, 0};
+    h->xbar = static_cast<float*>(c.take(sizeof(float) * static_cast<size_t>(h->Ps)));
+    if (h->md.kind == LC_KIND_QUAD) {
+        h->n_partial = static_cast<int>((h->P + 255) / 256);
+        h->partial = static_cast<double*>(c.take(sizeof(double) * static_cast<size_t>(h->n_partial)));
+        return static_cast<size_t>(round_up(static_cast<int64_t>(c.off), 256));
+    }
+    const int L = h->L;
+    const size_t ot = h->md.gemm == LC_GEMM_BF16 ? 2 : 4;
+    for (int pass = 0; pass < 2; ++pass) {
+        ActSet& S = pass == 0 ? h->train : h->eval;
+        const bool eval = pass == 1;
+        const size_t es = eval ? 4 : ot;
+        if (eval) {  // evaluation: chunks of 128 samples, at most 64 chunks per pass
+            S.B = S.Bp = 128;
+            const int chunks = (h->md.E + 127) / 128;
+            S.G = chunks < 64 ? chunks : 64;
+        } else {
+            S.G = h->m;
+            S.B = h->md.B;
+            S.Bp = padded_batch(h->md.B);
+        }
+        for (int l = 0; l <= L; ++l) {
+            const size_t dp = static_cast<size_t>(l == 0 ? h->layer[1].dp_in : h->layer[l].dp_out);
+            const size_t n = static_cast<size_t>(S.G) * S.Bp * dp;
+            S.a_bm[l] = c.take(n * (l == L ? 4 : es));
+            S.a_fm[l] = (!eval && l < L) ? c.take(n * es) : nullptr;
+            S.dz_bm[l] = (!eval && l >= 1) ? c.take(n * es) : nullptr;
+            S.dz_fm[l] = (!eval && l >= 1) ? c.take(n * es) : nullptr;
+        }
+        S.labels = static_cast<int32_t*>(c.take(sizeof(int32_t) * static_cast<size_t>(S.G) * S.Bp));
+        S.idx = static_cast<int32_t*>(c.take(sizeof(int32_t) * static_cast<size_t>(S.G) * S.Bp));
+        const int per_pass = S.G * S.B;
+        const int passes = eval ? (h->md.E + per_pass - 1) / per_pass : 1;
+        S.loss = static_cast<float*>(c.take(sizeof(float) * static_cast<size_t>(S.G) * passes));
+    }
+    h->n_partial = 0;
+    h->partial = nullptr;
+    return static_cast<size_t>(round_up(static_cast<int64_t>(c.off), 256));
+}
+
+int require_attached(const lc_handle* h) {
+    if (!h) return LC_ERR_ARG;
+    if (!h->attached) return LC_ERR_STATE;
+    return LC_OK;
+}
+
+// the quadratic objective also needs its constants before it can step or be evaluated
+int require_objective(const lc_handle* h) {
+    const int rc = require_attached(h);
+    if (rc != LC_OK) return rc;
+    if (h->md.kind == LC_KIND_QUAD && (!h->qa || !h->qc)) return LC_ERR_STATE;
+    return LC_OK;
+}
+
+int one_local_step(lc_handle* h) {
+    if (h->md.kind == LC_KIND_QUAD) {
+        LC_HIP(h, launch_quad_step(h));
+    } else {
+        LC_HIP(h, launch_gather(h, false, h->k));
+        for (int l = 1; l <= h->L; ++l) LC_HIP(h, launch_forward(h, false, l));
+        LC_HIP(h, launch_softmax(h, false, 0));
+        // layer L first: dZ_{l-1} is produced from W_l before W_l is overwritten
+        // inside the same kernel, and kernels run in stream order
+        for (int l = h->L; l >= 1; --l) LC_HIP(h, launch_backward(h, l));
+    }
+    h->k += 1;
+    return LC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lc_strerror(int status) {
+    switch (status) {
+        case LC_OK: return "ok";
+        case LC_ERR_ARG: return "invalid argument";
+        case LC_ERR_MODEL: return "inconsistent model description";
+        case LC_ERR_STATE: return "call out of order (not attached?)";
+        case LC_ERR_ALIGN: return "device pointer not 256-byte aligned";
+        case LC_ERR_WORKSPACE: return "scratch buffer too small";
+        case LC_ERR_HIP: return "HIP call failed";
+        case LC_ERR_NONFINITE: return "loss is not finite";
+        case LC_ERR_UNSUPPORTED: return "shape not supported";
+        default: return "unknown status";
+    }
+}
+
+int lc_last_hip_error(const lc_handle* h) { return h ? h->last_hip : 0; }
+
+int64_t lc_param_count(const lc_model* md) {
+    const int rc = model_ok(md);
+    if (rc != LC_OK) return rc;
+    if (md->kind == LC_KIND_QUAD) return md->dims[0];
+    int64_t p = 0;
+    for (int l = 0; l < md->n_layers; ++l) p += static_cast<int64_t>(md->dims[l]) * md->dims[l + 1] + md->dims[l + 1];
+    return p;
+}
+
+int64_t lc_row_stride(int64_t P) { return P < 1 ? LC_ERR_ARG : round_up(P, 64); }
+
+int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out) {
+    if (!out) return LC_ERR_ARG;
+    *out = nullptr;
+    if (m < 1 || m > 65535 || !md) return LC_ERR_ARG;
+    const int64_t want = lc_param_count(md);
+    if (want < 0) return static_cast<int>(want);
+    if (P != want) return LC_ERR_MODEL;
+    lc_handle* h = new (std::nothrow) lc_handle();
+    if (!h) return LC_ERR_ARG;
+    h->m = m;
+    h->P = P;
+    h->Ps = round_up(P, 64);
+    h->md = *md;
+    h->seed = seed;
+    h->k = 0;
+    h->L = md->kind == LC_KIND_MLP ? md->n_layers : 0;
+    int64_t off = 0;
+    for (int l = 1; l <= h->L; ++l) {
+        LayerGeom& g = h->layer[l];
+        g.d_in = md->dims[l - 1];
+        g.d_out = md->dims[l];
+        g.dp_in = static_cast<int>(round_up(g.d_in, 64));
+        g.dp_out = static_cast<int>(round_up(g.d_out, 64));
+        g.w_off = off;
+        g.b_off = off + static_cast<int64_t>(g.d_in) * g.d_out;
+        off = g.b_off + g.d_out;
+    }
+    h->attached = false;
+    h->X = h->V = nullptr;
+    h->G = h->qa = h->qc = nullptr;
+    h->data = nullptr;
+    h->labels = nullptr;
+    h->scratch = nullptr;
+    h->scratch_bytes = 0;
+    h->stream = nullptr;
+    h->last_hip = 0;
+    h->timing_which = kTimeNone;
+    h->ev_used = 0;
+    (void)carve(h, nullptr);
+    *out = h;
+    return LC_OK;
+}
+
+void lc_destroy(lc_handle* h) {
+    if (!h) return;
+    for (hipEvent_t e : h->ev_pool) (void)hipEventDestroy(e);
+    delete h;
+}
+
+size_t lc_workspace_bytes(const lc_handle* h) {
+    if (!h) return 0;
+    lc_handle tmp = *h;  // carve() only writes pointers; keep the caller's handle const
+    tmp.ev_pool.clear();
+    return carve(&tmp, nullptr);
+}
+
+int lc_attach(lc_handle* h, void* X, void* V, void* scratch, size_t scratch_bytes, const void* data,
+              const int32_t* labels, void* stream) {
+    if (!h || !X || !V || !scratch) return LC_ERR_ARG;
+    if (h->md.kind == LC_KIND_MLP && (!data || !labels)) return LC_ERR_ARG;
+    if (!aligned256(X) || !aligned256(V) || !aligned256(scratch) || (data && !aligned256(data))) return LC_ERR_ALIGN;
+    const size_t need = lc_workspace_bytes(h);
+    if (scratch_bytes < need) return LC_ERR_WORKSPACE;
+    h->X = static_cast<float*>(X);
+    h->V = static_cast<float*>(V);
+    h->data = data;
+    h->labels = labels;
+    h->scratch = static_cast<char*>(scratch);
+    h->scratch_bytes = scratch_bytes;
+    h->stream = static_cast<hipStream_t>(stream);
+    (void)carve(h, h->scratch);
+    LC_HIP(h, hipMemsetAsync(scratch, 0, need, h->stream));
+    LC_HIP(h, hipStreamSynchronize(h->stream));
+    h->attached = true;
+    return LC_OK;
+}
+
+int lc_attach_quad(lc_handle* h, const float* a, const float* c) {
+    if (!h || !a || !c) return LC_ERR_ARG;
+    if (h->md.kind != LC_KIND_QUAD) return LC_ERR_MODEL;
+    if (!aligned256(a) || !aligned256(c)) return LC_ERR_ALIGN;
+    h->qa = a;
+    h->qc = c;
+    return LC_OK;
+}
+
+int lc_local_steps(lc_handle* h, int tau) {
+    const int rc = require_objective(h);
+    if (rc != LC_OK) return rc;
+    if (tau < 1) return LC_ERR_ARG;
+    for (int t = 0; t < tau; ++t) {
+        const int r = one_local_step(h);
+        if (r != LC_OK) return r;
+    }
+    return LC_OK;
+}
+
+int lc_average(lc_handle* h) {
+    const int rc = require_attached(h);
+    if (rc != LC_OK) return rc;
+    LC_HIP(h, launch_average(h, h->X, h->X, nullptr));
+    return LC_OK;
+}
+
+int lc_loss(lc_handle* h, double* out) {
+    const int rc = require_objective(h);
+    if (rc != LC_OK) return rc;
+    if (!out) return LC_ERR_ARG;
+    LC_HIP(h, launch_average(h, h->X, nullptr, h->xbar));
+    double F = 0.0;
+    if (h->md.kind == LC_KIND_QUAD) {
+        int np = 0;
+        LC_HIP(h, launch_quad_loss(h, &np));
+        double* host = static_cast<double*>(malloc(sizeof(double) * static_cast<size_t>(np)));
+        if (!host) return LC_ERR_ARG;
+        hipError_t e = hipMemcpyAsync(host, h->partial, sizeof(double) * static_cast<size_t>(np), hipMemcpyDeviceToHost, h->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+        if (e != hipSuccess) {
+            free(host);
+            h->last_hip = static_cast<int>(e);
+            return LC_ERR_HIP;
+        }
+        for (int i = 0; i < np; ++i) F += host[i];
+        free(host);
+        F /= static_cast<double>(h->m);
+    } else {
+        const int per_pass = h->eval.G * h->eval.B;
+        const int E = h->md.E;
+        const int passes = (E + per_pass - 1) / per_pass;
+        const size_t n = static_cast<size_t>(h->eval.G) * passes;
+        float* host = static_cast<float*>(malloc(sizeof(float) * n));
+        if (!host) return LC_ERR_ARG;
+        hipError_t e = hipSuccess;
+        for (int p = 0; p < passes && e == hipSuccess; ++p) {
+            e = launch_gather(h, true, static_cast<int64_t>(p) * per_pass);
+            for (int l = 1; l <= h->L && e == hipSuccess; ++l) e = launch_forward(h, true, l);
+            if (e == hipSuccess) e = launch_softmax(h, true, p * h->eval.G);
+        }
+        if (e == hipSuccess) e = hipMemcpyAsync(host, h->eval.loss, sizeof(float) * n, hipMemcpyDeviceToHost, h->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+        if (e != hipSuccess) {
+            free(host);
+            h->last_hip = static_cast<int>(e);
+            return LC_ERR_HIP;
+        }
+        for (size_t g = 0; g < n; ++g) F += static_cast<double>(host[g]);
+        free(host);
+        F /= static_cast<double>(E);
+    }
+    *out = F;
+    return isfinite(F) ? LC_OK : LC_ERR_NONFINITE;
+}
+
+int adacomm_next_tau(double F0, double Fl, int tau0) {
+    if (!(F0 > 0.0) || !(Fl >= 0.0) || !isfinite(F0) || !isfinite(Fl) || tau0 < 1) return LC_ERR_ARG;
+    volatile double ratio = Fl / F0;        // volatile: each operation rounded to double, nothing fused
+    volatile double root = sqrt(ratio);
+    volatile double prod = root * static_cast<double>(tau0);
+    const double up = ceil(prod);
+    if (!(up < 2147483647.0)) return LC_ERR_ARG;
+    const int t = static_cast<int>(up);
+    return t < 1 ? 1 : t;
+}
+
+int lc_run(lc_handle* h, int64_t K, int tau0, int adaptive, int64_t interval, int64_t* sched_k,
+           int32_t* sched_tau, int cap, int32_t* n_sched, int64_t* rounds) {
+    const int rc = require_attached(h);
+    if (rc != LC_OK) return rc;
+    if (K < 0 || tau0 < 1 || cap < 0 || (cap > 0 && (!sched_k || !sched_tau)) || !n_sched || !rounds) return LC_ERR_ARG;
+    if (adaptive && interval < 1) return LC_ERR_ARG;
+    int tau = tau0, ns = 0;
+    int64_t r = 0, next_eval = h->k + interval;
+    double F0 = 0.0;
+    *n_sched = 0;
+    *rounds = 0;
+    if (adaptive) {
+        const int e = lc_loss(h, &F0);
+        if (e != LC_OK) return e;
+    }
+    if (ns < cap) {
+        sched_k[ns] = h->k;
+        sched_tau[ns] = tau;
+    }
+    ++ns;
+    const int64_t k_end = h->k + K;
+    while (h->k < k_end) {
+        const int64_t left = k_end - h->k;
+        const int t = static_cast<int64_t>(tau) < left ? tau : static_cast<int>(left);
+        int e = lc_local_steps(h, t);
+        if (e == LC_OK) e = lc_average(h);
+        if (e != LC_OK) return e;
+        ++r;
+        if (adaptive && h->k >= next_eval && h->k < k_end) {
+            double Fl = 0.0;
+            e = lc_loss(h, &Fl);
+            if (e != LC_OK) return e;
+            const int nt = adacomm_next_tau(F0, Fl, tau0);
+            if (nt < 0) return nt;
+            tau = nt;
+            if (ns < cap) {
+                sched_k[ns] = h->k;
+                sched_tau[ns] = tau;
+            }
+            ++ns;
+            while (next_eval <= h->k) next_eval += interval;
+        }
+        *n_sched = ns;
+        *rounds = r;
+    }
+    *n_sched = ns;
+    *rounds = r;
+    LC_HIP(h, hipStreamSynchronize(h->stream));
+    return LC_OK;
+}
+
+int lc_set_grad(lc_handle* h, const void* G) {
+    if (!h || !G) return LC_ERR_ARG;
+    if (!aligned256(G)) return LC_ERR_ALIGN;
+    h->G = static_cast<const float*>(G);
+    return LC_OK;
+}
+
+int lc_update_from_grad(lc_handle* h) {
+    if (!h) return LC_ERR_ARG;
+    if (!h->attached || !h->G) return LC_ERR_STATE;
+    LC_HIP(h, launch_update_from_grad(h));
+    return LC_OK;
+}
+
+int lc_update_from_grad_and_average(lc_handle* h) {
+    if (!h) return LC_ERR_ARG;
+    if (!h->attached || !h->G) return LC_ERR_STATE;
+    LC_HIP(h, launch_update_and_average(h));
+    return LC_OK;
+}
+
+int lc_get_state(lc_handle* h, float* X_host, float* V_host, int64_t* k) {
+    if (!h) return LC_ERR_ARG;
+    if (!h->attached) return LC_ERR_STATE;
+    const size_t row = sizeof(float) * static_cast<size_t>(h->P), pitch = sizeof(float) * static_cast<size_t>(h->Ps);
+    if (X_host) LC_HIP(h, hipMemcpy2DAsync(X_host, row, h->X, pitch, row, h->m, hipMemcpyDeviceToHost, h->stream));
+    if (V_host) LC_HIP(h, hipMemcpy2DAsync(V_host, row, h->V, pitch, row, h->m, hipMemcpyDeviceToHost, h->stream));
+    LC_HIP(h, hipStreamSynchronize(h->stream));
+    if (k) *k = h->k;
+    return LC_OK;
+}
+
+int lc_set_state(lc_handle* h, const float* X_host, const float* V_host, int64_t k) {
+    if (!h || k < 0) return LC_ERR_ARG;
+    if (!h->attached) return LC_ERR_STATE;
+    const size_t row = sizeof(float) * static_cast<size_t>(h->P), pitch = sizeof(float) * static_cast<size_t>(h->Ps);
+    if (X_host) LC_HIP(h, hipMemcpy2DAsync(h->X, pitch, X_host, row, row, h->m, hipMemcpyHostToDevice, h->stream));
+    if (V_host) LC_HIP(h, hipMemcpy2DAsync(h->V, pitch, V_host, row, row, h->m, hipMemcpyHostToDevice, h->stream));
+    LC_HIP(h, hipStreamSynchronize(h->stream));
+    h->k = k;
+    return LC_OK;
+}
+
+int lc_set_lr(lc_handle* h, float lr) {
+    if (!h || !(lr >= 0.f)) return LC_ERR_ARG;
+    h->md.lr = lr;
+    return LC_OK;
+}
+
+int lc_get_local_losses(lc_handle* h, float* losses_host) {
+    if (!h || !losses_host) return LC_ERR_ARG;
+    if (!h->attached) return LC_ERR_STATE;
+    if (h->md.kind != LC_KIND_MLP) return LC_ERR_UNSUPPORTED;
+    LC_HIP(h, hipMemcpyAsync(losses_host, h->train.loss, sizeof(float) * static_cast<size_t>(h->m), hipMemcpyDeviceToHost, h->stream));
+    LC_HIP(h, hipStreamSynchronize(h->stream));
+    return LC_OK;
+}
+
+int lc_get_last_indices(lc_handle* h, int32_t* idx_host) {
+    if (!h || !idx_host) return LC_ERR_ARG;
+    if (!h->attached) return LC_ERR_STATE;
+    if (h->md.kind != LC_KIND_MLP) return LC_ERR_UNSUPPORTED;
+    const size_t row = sizeof(int32_t) * static_cast<size_t>(h->train.B), pitch = sizeof(int32_t) * static_cast<size_t>(h->train.Bp);
+    LC_HIP(h, hipMemcpy2DAsync(idx_host, row, h->train.idx, pitch, row, h->m, hipMemcpyDeviceToHost, h->stream));
+    LC_HIP(h, hipStreamSynchronize(h->stream));
+    return LC_OK;
+}
+
+int lc_timing_begin(lc_handle* h, int which) {
+    if (!h || which < kTimeNone || which > kTimeUpdAvg) return LC_ERR_ARG;
+    h->timing_which = which;
+    h->ev_used = 0;
+    return LC_OK;
+}
+
+int lc_timing_read(lc_handle* h, int64_t* launches, double* total_ms) {
+    if (!h || !launches || !total_ms) return LC_ERR_ARG;
+    if (!h->attached) return LC_ERR_STATE;
+    LC_HIP(h, hipStreamSynchronize(h->stream));
+    double sum = 0.0;
+    for (size_t i = 0; i + 1 < h->ev_used; i += 2) {
+        float ms = 0.f;
+        LC_HIP(h, hipEventElapsedTime(&ms, h->ev_pool[i], h->ev_pool[i + 1]));
+        sum += static_cast<double>(ms);
+    }
+    *launches = static_cast<int64_t>(h->ev_used / 2);
+    *total_ms = sum;
+    h->ev_used = 0;
+    return LC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,98 @@
+// Internal declarations shared by the translation units of liblocalcomm.
+// Nothing here is part of the C ABI (see include/localcomm.h for that).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "localcomm.h"
+
+namespace lc {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+constexpr int kColChunk = 64;   // columns of W handled per wave and per loop trip
+constexpr int kRowsPerWave = 16;
+constexpr int kXcds = 8;
+
+inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+
+// Kernel classes for lc_timing_begin().
+enum TimedKernel { kTimeBwd = 0, kTimeFwd = 1, kTimeAvg = 2, kTimeUpd = 3, kTimeUpdAvg = 4, kTimeNone = -1 };
+
+// One layer of the per-replica MLP as the kernels see it.
+struct LayerGeom {
+    int d_in, d_out;      // logical sizes
+    int dp_in, dp_out;    // padded to a multiple of 64
+    int64_t w_off, b_off; // offsets inside a replica row (floats)
+};
+
+// Device buffers of one "activation set": either the training set (operand type
+// of the run) or the evaluation set (always fp32).
+struct ActSet {
+    int G;                 // groups (replicas, or evaluation chunks)
+    int B, Bp;             // valid rows and rows padded to a multiple of 32
+    void* a_bm[LC_MAX_LAYERS + 1];  // A_l batch-major   [G][Bp][dp_l]   (l = L: logits, fp32)
+    void* a_fm[LC_MAX_LAYERS + 1];  // A_l feature-major [G][dp_l][Bp]   (training only, l < L)
+    void* dz_bm[LC_MAX_LAYERS + 1]; // dZ_l batch-major  (training only, l >= 1)
+    void* dz_fm[LC_MAX_LAYERS + 1]; // dZ_l feature-major
+    int32_t* labels;       // [G][Bp]
+    int32_t* idx;          // [G][Bp]
+    float* loss;           // training: [G] batch means; evaluation: [passes][G] sums over valid rows
+};
+
+}  // namespace lc
+
+struct lc_handle {
+    int m;
+    int64_t P, Ps;
+    lc_model md;
+    uint64_t seed;
+    int64_t k;
+    int L;
+    lc::LayerGeom layer[LC_MAX_LAYERS + 1];  // index 1..L
+    bool attached;
+    float *X, *V;
+    const float* G;
+    const float *qa, *qc;
+    const void* data;
+    const int32_t* labels;
+    char* scratch;
+    size_t scratch_bytes;
+    hipStream_t stream;
+    lc::ActSet train, eval;
+    float* xbar;            // [Ps]
+    double* partial;        // reduction partials
+    int n_partial;
+    int last_hip;
+    // timing
+    int timing_which;
+    std::vector<hipEvent_t> ev_pool;
+    size_t ev_used;
+};
+
+namespace lc {
+
+// ---- launchers (each returns a hipError_t from hipGetLastError) --------------
+hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* out_single);
+hipError_t launch_update_from_grad(lc_handle* h);
+hipError_t launch_update_and_average(lc_handle* h);
+hipError_t launch_quad_step(lc_handle* h);
+hipError_t launch_quad_loss(lc_handle* h, int* n_partial);
+
+hipError_t launch_gather(lc_handle* h, bool eval, int64_t k_or_base);
+hipError_t launch_forward(lc_handle* h, bool eval, int l);
+hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset);
+hipError_t launch_backward(lc_handle* h, int l);
+
+// timing helpers used by the launchers
+void timing_start(lc_handle* h, int which);
+void timing_stop(lc_handle* h, int which);
+
+}  // namespace lc

@@ -1,0 +1,707 @@
+// The local SGD step of every replica (Sec. 2, mini-batch SGD inside PASGD) as
+// grouped per-replica matrix products on the gfx950 matrix cores:
+//
+//   gather   : mini-batch selection by the integer index stream + row gather
+//   forward  : Z_l = A_{l-1} W_l + b_l, A_l = ReLU(Z_l)
+//   softmax  : cross-entropy loss and dZ_L = (p - onehot) / B
+//   backward : dW_l = A_{l-1}^T dZ_l, db_l, dZ_{l-1} = (dZ_l W_l^T) .* [A_{l-1} > 0]
+//              with the momentum-SGD update applied to the dW tile while it is
+//              still in registers (the gradient never reaches memory)
+//
+// Weights are private to a replica and reused only B times per product, so the
+// step is bound by streaming W and V through HBM, not by the matrix cores.  The
+// kernels are therefore organised around the weight stream: each wavefront owns
+// a slab of W, reads it exactly once per kernel with 16-byte loads straight into
+// the MFMA operand/accumulator register layout, and activations (small, shared
+// by all wavefronts of a replica) are kept in memory in BOTH batch-major and
+// feature-major form, zero padded, so that every MFMA operand is one aligned
+// 16-byte load with no bounds checks.
+//
+// MFMA shapes: v_mfma_f32_16x16x32_bf16 (bf16 operands) and v_mfma_f32_16x16x4_f32
+// (fp32 operands).  With l = lane, an A operand lane holds row (l & 15) and a B
+// operand lane holds column (l & 15); both hold the reduction indices
+// 8 (l >> 4) .. 8 (l >> 4) + 7 of a 32-wide step (one bf16 instruction, or eight
+// fp32 instructions taking one element each; the order inside the step does not
+// matter because both operands use the same one).  The 16x16 result has row
+// 4 (l >> 4) + r in register r and column (l & 15).
+//
+// Column trick: a wavefront covers 64 columns of W as four 16-column MFMA tiles,
+// but tile t, lane column j stands for memory column c0 + 4 j + t.  A lane's four
+// tiles are then four consecutive floats of one row of W: one float4.
+#include "lc_internal.h"
+
+namespace lc {
+
+namespace {
+
+// ------------------------------------------------------------------ fragments
+
+template <typename OT>
+struct Frag;
+template <>
+struct Frag<float> {
+    float v[8];
+};
+template <>
+struct Frag<bf16_t> {
+    bf16x8 v;
+};
+
+__device__ __forceinline__ Frag<float> load8(const float* p) {
+    Frag<float> f;
+    const float4 a = *reinterpret_cast<const float4*>(p);
+    const float4 b = *reinterpret_cast<const float4*>(p + 4);
+    f.v[0] = a.x; f.v[1] = a.y; f.v[2] = a.z; f.v[3] = a.w;
+    f.v[4] = b.x; f.v[5] = b.y; f.v[6] = b.z; f.v[7] = b.w;
+    return f;
+}
+__device__ __forceinline__ Frag<bf16_t> load8(const bf16_t* p) {
+    Frag<bf16_t> f;
+    f.v = *reinterpret_cast<const bf16x8*>(p);
+    return f;
+}
+
+__device__ __forceinline__ void pack8(Frag<float>& f, const float (&x)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f.v[e] = x[e];
+}
+__device__ __forceinline__ void pack8(Frag<bf16_t>& f, const float (&x)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f.v[e] = static_cast<bf16_t>(x[e]);  // round to nearest even
+}
+
+__device__ __forceinline__ f32x4 mma8(const Frag<float>& a, const Frag<float>& b, f32x4 c) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[e], b.v[e], c, 0, 0, 0);
+    return c;
+}
+__device__ __forceinline__ f32x4 mma8(const Frag<bf16_t>& a, const Frag<bf16_t>& b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return static_cast<float>(x); }
+
+template <typename OT>
+__device__ __forceinline__ void store4(OT* p, float a, float b, float c, float d);
+template <>
+__device__ __forceinline__ void store4<float>(float* p, float a, float b, float c, float d) {
+    *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
+}
+template <>
+__device__ __forceinline__ void store4<bf16_t>(bf16_t* p, float a, float b, float c, float d) {
+    bf16x4 v;
+    v[0] = static_cast<bf16_t>(a); v[1] = static_cast<bf16_t>(b);
+    v[2] = static_cast<bf16_t>(c); v[3] = static_cast<bf16_t>(d);
+    *reinterpret_cast<bf16x4*>(p) = v;
+}
+
+// Four consecutive floats of a weight row, zero outside [0, d_out).
+__device__ __forceinline__ float4 load_w4(const float* row, int c, int d_out, bool vec) {
+    if (vec && c + 3 < d_out) return *reinterpret_cast<const float4*>(row + c);
+    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c < d_out) r.x = row[c];
+    if (c + 1 < d_out) r.y = row[c + 1];
+    if (c + 2 < d_out) r.z = row[c + 2];
+    if (c + 3 < d_out) r.w = row[c + 3];
+    return r;
+}
+__device__ __forceinline__ void store_w4(float* row, int c, int d_out, bool vec, float4 v) {
+    if (vec && c + 3 < d_out) {
+        *reinterpret_cast<float4*>(row + c) = v;
+        return;
+    }
+    if (c < d_out) row[c] = v.x;
+    if (c + 1 < d_out) row[c + 1] = v.y;
+    if (c + 2 < d_out) row[c + 2] = v.z;
+    if (c + 3 < d_out) row[c + 3] = v.w;
+}
+
+__device__ __forceinline__ void wave_sync_lds() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Workgroups are handed to the 8 XCDs round-robin.  This maps the hardware
+// block id to a logical one such that each XCD works on a contiguous range of
+// logical blocks (consecutive blocks of one replica then share that XCD's L2
+// for the replica's activations).  Returns -1 for the padding blocks.
+__device__ __forceinline__ int64_t xcd_logical_block(int64_t total) {
+    const int64_t per = (total + kXcds - 1) / kXcds;
+    const int64_t bid = blockIdx.x;
+    const int64_t logical = (bid % kXcds) * per + bid / kXcds;
+    return logical < total ? logical : -1;
+}
+
+// ----------------------------------------------------------------- index hash
+
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+__device__ __forceinline__ int64_t batch_index(uint64_t seed, int i, int64_t k, int b, int64_t N) {
+    const uint64_t gamma = 0x9E3779B97F4A7C15ULL;
+    uint64_t hsh = mix64(seed + gamma * (static_cast<uint64_t>(k) + 1));
+    hsh = mix64(hsh + gamma * (static_cast<uint64_t>(i) + 1));
+    hsh = mix64(hsh + gamma * (static_cast<uint64_t>(b) + 1));
+    return static_cast<int64_t>(hsh % static_cast<uint64_t>(N));
+}
+
+// --------------------------------------------------------------------- gather
+
+struct GatherArgs {
+    const void* data;       // [N][d0] of DT
+    const int32_t* labels;  // [N]
+    void* a_bm;             // [G][Bp][dp0] of OT
+    void* a_fm;             // [G][dp0][Bp] of OT or null
+    int32_t* lab_out;       // [G][Bp]
+    int32_t* idx_out;       // [G][Bp]
+    int d0, dp0, B, Bp;
+    int64_t N;
+    uint64_t seed;
+    int64_t k;              // training: local iteration; evaluation: first sample of the pass
+    int64_t limit;          // evaluation: samples >= limit are invalid
+    int eval;
+};
+
+// One block copies a 32-sample x 64-feature tile through LDS and writes it in
+// both layouts.  grid = (dp0/64, Bp/32, G).
+template <typename DT, typename OT>
+__global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
+    __shared__ float tile[32][65];
+    __shared__ int64_t rows[32];
+    const int g = blockIdx.z, b0 = blockIdx.y * 32, k0 = blockIdx.x * 64;
+    const int t = threadIdx.x;
+    if (t < 32) {
+        const int b = b0 + t;
+        int64_t idx = -1;
+        if (b < a.B) {
+            if (a.eval) {
+                idx = a.k + static_cast<int64_t>(g) * a.B + b;
+                if (idx >= a.limit) idx = -1;
+            } else {
+                idx = batch_index(a.seed, g, a.k, b, a.N);
+            }
+        }
+        rows[t] = idx;
+        if (blockIdx.x == 0) {
+            const int64_t o = static_cast<int64_t>(g) * a.Bp + b;
+            a.idx_out[o] = static_cast<int32_t>(idx);
+            a.lab_out[o] = idx >= 0 ? a.labels[idx] : -1;
+        }
+    }
+    __syncthreads();
+    const DT* data = static_cast<const DT*>(a.data);
+    {
+        const int r = t >> 3, seg = (t & 7) * 8;
+        const int64_t idx = rows[r];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int kk = k0 + seg + e;
+            tile[r][seg + e] = (idx >= 0 && kk < a.d0) ? to_f32(data[idx * a.d0 + kk]) : 0.f;
+        }
+    }
+    __syncthreads();
+    OT* bm = static_cast<OT*>(a.a_bm) + static_cast<int64_t>(g) * a.Bp * a.dp0;
+    {
+        const int r = t >> 3, seg = (t & 7) * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bm[static_cast<int64_t>(b0 + r) * a.dp0 + k0 + seg + e] = static_cast<OT>(tile[r][seg + e]);
+    }
+    if (a.a_fm) {
+        OT* fm = static_cast<OT*>(a.a_fm) + static_cast<int64_t>(g) * a.dp0 * a.Bp;
+        const int kk = t >> 2, seg = (t & 3) * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) fm[static_cast<int64_t>(k0 + kk) * a.Bp + b0 + seg + e] = static_cast<OT>(tile[seg + e][kk]);
+    }
+}
+
+// -------------------------------------------------------------------- forward
+
+struct FwdArgs {
+    const float* X;       // parameters; replica g at X + g * x_stride
+    int64_t x_stride;     // 0: every group uses the same parameters (evaluation)
+    int64_t w_off, b_off;
+    int d_in, d_out, dp_in, dp_out;
+    int B, Bp;
+    const void* a_in;     // [G][Bp][dp_in] of OT
+    void* out_bm;         // [G][Bp][dp_out] of OT, or fp32 logits when last
+    void* out_fm;         // [G][dp_out][Bp] of OT or null
+    int last;             // 1: no ReLU, fp32 output
+    int vec;              // weight rows may be read with 16-byte loads
+    int n_chunks;         // column chunks per group
+    int64_t total_blocks;
+};
+
+// One block = one replica x 64 output columns; its NW wavefronts split the
+// reduction over d_in and combine their partial tiles in LDS.
+template <typename OT, int MT, int NW>
+__global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
+    __shared__ float red[MT * 16][kColChunk + 4];
+    const int64_t logical = xcd_logical_block(a.total_blocks);
+    if (logical < 0) return;
+    const int g = static_cast<int>(logical / a.n_chunks);
+    const int c0 = static_cast<int>(logical % a.n_chunks) * kColChunk;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = lane & 15, q = lane >> 4;
+
+    const float* W = a.X + g * a.x_stride + a.w_off;
+    const OT* A = static_cast<const OT*>(a.a_in) + static_cast<int64_t>(g) * a.Bp * a.dp_in;
+    const bool vec = a.vec != 0;
+
+    f32x4 acc[MT][4];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int n_steps = a.dp_in / 32;
+    for (int s = wave; s < n_steps; s += NW) {
+        const int k0 = s * 32 + 8 * q;
+        float4 w[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int row = k0 + e;
+            w[e] = row < a.d_in ? load_w4(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec)
+                                : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        Frag<OT> af[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) af[mt] = load8(A + static_cast<int64_t>(16 * mt + j) * a.dp_in + k0);
+        {
+            Frag<OT> bf;
+            float x[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = w[e].x;
+            pack8(bf, x);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt][0] = mma8(af[mt], bf, acc[mt][0]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = w[e].y;
+            pack8(bf, x);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt][1] = mma8(af[mt], bf, acc[mt][1]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = w[e].z;
+            pack8(bf, x);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt][2] = mma8(af[mt], bf, acc[mt][2]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = w[e].w;
+            pack8(bf, x);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt][3] = mma8(af[mt], bf, acc[mt][3]);
+        }
+    }
+
+    // combine the wavefronts' partial tiles in a fixed order
+    for (int w = 0; w < NW; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float4* p = reinterpret_cast<float4*>(&red[16 * mt + 4 * q + r][4 * j]);
+                    float4 v = make_float4(acc[mt][0][r], acc[mt][1][r], acc[mt][2][r], acc[mt][3][r]);
+                    if (w > 0) {
+                        const float4 o = *p;
+                        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                    }
+                    *p = v;
+                }
+        }
+        __syncthreads();
+    }
+
+    // epilogue: bias, ReLU, both layouts; only valid (b, c) are written so the
+    // zero padding of the activation buffers is preserved
+    const float* bias = a.X + g * a.x_stride + a.b_off;
+    const int nthr = NW * 64;
+    if (a.last) {
+        float* out = static_cast<float*>(a.out_bm) + static_cast<int64_t>(g) * a.Bp * a.dp_out;
+        for (int e = threadIdx.x; e < MT * 16 * kColChunk; e += nthr) {
+            const int b = e / kColChunk, c = c0 + e % kColChunk;
+            if (b < a.B && c < a.d_out) out[static_cast<int64_t>(b) * a.dp_out + c] = red[b][e % kColChunk] + bias[c];
+        }
+    } else {
+        OT* obm = static_cast<OT*>(a.out_bm) + static_cast<int64_t>(g) * a.Bp * a.dp_out;
+        for (int e = threadIdx.x; e < MT * 16 * kColChunk; e += nthr) {
+            const int b = e / kColChunk, c = c0 + e % kColChunk;
+            if (b < a.B && c < a.d_out) {
+                const float z = red[b][e % kColChunk] + bias[c];
+                obm[static_cast<int64_t>(b) * a.dp_out + c] = static_cast<OT>(z > 0.f ? z : 0.f);
+            }
+        }
+        if (a.out_fm) {
+            OT* ofm = static_cast<OT*>(a.out_fm) + static_cast<int64_t>(g) * a.dp_out * a.Bp;
+            for (int e = threadIdx.x; e < MT * 16 * kColChunk; e += nthr) {
+                const int cl = e / (MT * 16), b = e % (MT * 16), c = c0 + cl;
+                if (b < a.B && c < a.d_out) {
+                    const float z = red[b][cl] + bias[c];
+                    ofm[static_cast<int64_t>(c) * a.Bp + b] = static_cast<OT>(z > 0.f ? z : 0.f);
+                }
+            }
+        }
+    }
+}
+
+// -------------------------------------------------------------------- softmax
+
+struct SoftmaxArgs {
+    const float* logits;    // [G][Bp][dpL]
+    const int32_t* labels;  // [G][Bp], -1 = no sample
+    void* dz_bm;            // [G][Bp][dpL] of OT or null (evaluation)
+    void* dz_fm;            // [G][dpL][Bp] of OT or null
+    float* loss;            // [G]
+    int C, dpL, B, Bp;
+    int eval;               // 1: loss[g] = sum over valid samples; 0: mean over B
+};
+
+// One block per group, one thread per sample.
+template <typename OT>
+__global__ __launch_bounds__(128) void softmax_kernel(SoftmaxArgs a) {
+    __shared__ float red[128];
+    const int g = blockIdx.x, b = threadIdx.x;
+    float nll = 0.f;
+    if (b < a.B) {
+        const int y = a.labels[static_cast<int64_t>(g) * a.Bp + b];
+        if (y >= 0) {
+            const float* z = a.logits + (static_cast<int64_t>(g) * a.Bp + b) * a.dpL;
+            float zmax = z[0];
+            for (int c = 1; c < a.C; ++c) zmax = fmaxf(zmax, z[c]);
+            float sum = 0.f;
+            for (int c = 0; c < a.C; ++c) sum += expf(z[c] - zmax);
+            nll = -(z[y] - zmax - logf(sum));
+            if (a.dz_bm) {
+                OT* dbm = static_cast<OT*>(a.dz_bm) + (static_cast<int64_t>(g) * a.Bp + b) * a.dpL;
+                OT* dfm = static_cast<OT*>(a.dz_fm) + static_cast<int64_t>(g) * a.dpL * a.Bp + b;
+                const float inv = 1.f / sum, invB = 1.f / static_cast<float>(a.B);
+                for (int c = 0; c < a.C; ++c) {
+                    const float p = expf(z[c] - zmax) * inv;
+                    const OT d = static_cast<OT>((p - (c == y ? 1.f : 0.f)) * invB);
+                    dbm[c] = d;
+                    dfm[static_cast<int64_t>(c) * a.Bp] = d;
+                }
+            }
+        }
+    }
+    red[b] = nll;
+    __syncthreads();
+    for (int w = 64; w > 0; w >>= 1) {
+        if (b < w) red[b] += red[b + w];
+        __syncthreads();
+    }
+    if (b == 0) a.loss[g] = a.eval ? red[0] : red[0] / static_cast<float>(a.B);
+}
+
+// ------------------------------------------------------------------- backward
+
+struct BwdArgs {
+    float* X;
+    float* V;
+    int64_t x_stride;
+    int64_t w_off, b_off;
+    int d_in, d_out, dp_in, dp_out;
+    int B, Bp;
+    const void* a_bm;    // A_{l-1} batch-major   [G][Bp][dp_in]  (unused here)
+    const void* a_fm;    // A_{l-1} feature-major [G][dp_in][Bp]
+    const void* dz_bm;   // dZ_l batch-major      [G][Bp][dp_out]
+    const void* dz_fm;   // dZ_l feature-major    [G][dp_out][Bp]
+    void* dzp_bm;        // dZ_{l-1} batch-major  [G][Bp][dp_in]  or null (layer 1)
+    void* dzp_fm;        // dZ_{l-1} feature-major[G][dp_in][Bp]
+    float lr, beta, wd;
+    int vec;
+    int n_row_blocks;    // blocks per group (64 rows each)
+    int64_t total_blocks;
+};
+
+// One wavefront owns 16 rows of W_l (and of V_l) and walks along them 64 columns
+// at a time.  Per trip it (1) loads the W and V tiles into the accumulator
+// layout, (2) forms the dW tile with MFMA over the batch, (3) parks the *old* W
+// tile in LDS, re-reads it in operand layout and accumulates its contribution
+// to dA_{l-1} (which therefore uses the weights of before the update, as the
+// chain rule requires), (4) applies v <- beta v + dW + wd w, w <- w - lr v and
+// stores both tiles.  W and V cross HBM exactly once in each direction.
+template <typename OT, int NT>
+__global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
+    constexpr int kPad = sizeof(OT) == 2 ? 8 : 4;
+    __shared__ __attribute__((aligned(16))) OT wlds[4][kRowsPerWave][kColChunk + kPad];
+    const int64_t logical = xcd_logical_block(a.total_blocks);
+    if (logical < 0) return;
+    const int g = static_cast<int>(logical / a.n_row_blocks);
+    const int rb = static_cast<int>(logical % a.n_row_blocks);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = lane & 15, q = lane >> 4;
+    const int k0 = (rb * 4 + wave) * kRowsPerWave;
+    const bool vec = a.vec != 0;
+    const bool need_da = a.dzp_bm != nullptr;
+
+    float* W = a.X + g * a.x_stride + a.w_off;
+    float* Vw = a.V + g * a.x_stride + a.w_off;
+    const OT* AT = static_cast<const OT*>(a.a_fm) + static_cast<int64_t>(g) * a.dp_in * a.Bp;
+    const OT* dZ = static_cast<const OT*>(a.dz_bm) + static_cast<int64_t>(g) * a.Bp * a.dp_out;
+    const OT* dZT = static_cast<const OT*>(a.dz_fm) + static_cast<int64_t>(g) * a.dp_out * a.Bp;
+
+    // bias: db_l = sum_b dZ_l, then the same update (first block of the replica)
+    if (rb == 0) {
+        float* bx = a.X + g * a.x_stride + a.b_off;
+        float* bv = a.V + g * a.x_stride + a.b_off;
+        for (int c = threadIdx.x; c < a.d_out; c += 256) {
+            float s = 0.f;
+            for (int b = 0; b < a.B; ++b) s += to_f32(dZT[static_cast<int64_t>(c) * a.Bp + b]);
+            const float x = bx[c];
+            const float v = a.beta * bv[c] + (s + a.wd * x);
+            bv[c] = v;
+            bx[c] = x - a.lr * v;
+        }
+    }
+    if (k0 >= a.dp_in) return;  // whole wavefront beyond the padded rows
+
+    f32x4 dacc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) dacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // this lane's A operand for the dW product: row k0 + j of A_{l-1}^T
+    const OT* at_row = AT + static_cast<int64_t>(k0 + j) * a.Bp + 8 * q;
+
+    const int n_cc = a.dp_out / kColChunk;
+    for (int cc = 0; cc < n_cc; ++cc) {
+        const int c0 = cc * kColChunk;
+        if (c0 >= a.d_out) break;
+        float4 w[4], v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = k0 + 4 * q + r;
+            if (row < a.d_in) {
+                w[r] = load_w4(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec);
+                v[r] = load_w4(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec);
+            } else {
+                w[r] = v[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+        // dW tile: sum over the batch of A^T[k][b] dZ^T[c][b]
+        f32x4 acc[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < NT / 2; ++s) {
+            const Frag<OT> af = load8(at_row + 32 * s);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const Frag<OT> bf = load8(dZT + static_cast<int64_t>(c0 + 4 * j + t) * a.Bp + 32 * s + 8 * q);
+                acc[t] = mma8(af, bf, acc[t]);
+            }
+        }
+        if (need_da) {
+            // old weights, in operand precision, to LDS in natural column order
+#pragma unroll
+            for (int r = 0; r < 4; ++r) store4<OT>(&wlds[wave][4 * q + r][4 * j], w[r].x, w[r].y, w[r].z, w[r].w);
+        }
+        // update and store
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = k0 + 4 * q + r;
+            float4 gr = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
+            v[r].x = a.beta * v[r].x + (gr.x + a.wd * w[r].x);
+            v[r].y = a.beta * v[r].y + (gr.y + a.wd * w[r].y);
+            v[r].z = a.beta * v[r].z + (gr.z + a.wd * w[r].z);
+            v[r].w = a.beta * v[r].w + (gr.w + a.wd * w[r].w);
+            w[r].x -= a.lr * v[r].x;
+            w[r].y -= a.lr * v[r].y;
+            w[r].z -= a.lr * v[r].z;
+            w[r].w -= a.lr * v[r].w;
+            if (row < a.d_in) {
+                store_w4(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, v[r]);
+                store_w4(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, w[r]);
+            }
+        }
+        if (need_da) {
+            wave_sync_lds();
+            // dA^T[k][b] += sum_c W[k][c] dZ[b][c] over this chunk's 64 columns
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const Frag<OT> wf = load8(&wlds[wave][j][32 * s + 8 * q]);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const Frag<OT> zf = load8(dZ + static_cast<int64_t>(16 * nt + j) * a.dp_out + c0 + 32 * s + 8 * q);
+                    dacc[nt] = mma8(wf, zf, dacc[nt]);
+                }
+            }
+            wave_sync_lds();
+        }
+    }
+
+    if (need_da) {
+        // dZ_{l-1} = dA .* [A_{l-1} > 0], both layouts.  Rows beyond d_in and batch
+        // entries beyond B come out as exact zeros (zero operands), which is what
+        // the padding must hold.
+        OT* pbm = static_cast<OT*>(a.dzp_bm) + static_cast<int64_t>(g) * a.Bp * a.dp_in;
+        OT* pfm = static_cast<OT*>(a.dzp_fm) + static_cast<int64_t>(g) * a.dp_in * a.Bp;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int b = 16 * nt + j;
+            float d[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = k0 + 4 * q + r;
+                const float act = to_f32(AT[static_cast<int64_t>(row) * a.Bp + b]);
+                d[r] = act > 0.f ? dacc[nt][r] : 0.f;
+                pfm[static_cast<int64_t>(row) * a.Bp + b] = static_cast<OT>(d[r]);
+            }
+            store4<OT>(pbm + static_cast<int64_t>(b) * a.dp_in + k0 + 4 * q, d[0], d[1], d[2], d[3]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ dispatch
+
+template <typename OT, int NW>
+hipError_t launch_fwd_mt(const FwdArgs& a, int mt, unsigned grid, hipStream_t s) {
+    switch (mt) {
+        case 2: hipLaunchKernelGGL((forward_kernel<OT, 2, NW>), dim3(grid), dim3(NW * 64), 0, s, a); break;
+        case 4: hipLaunchKernelGGL((forward_kernel<OT, 4, NW>), dim3(grid), dim3(NW * 64), 0, s, a); break;
+        case 8: hipLaunchKernelGGL((forward_kernel<OT, 8, NW>), dim3(grid), dim3(NW * 64), 0, s, a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+template <typename OT>
+hipError_t launch_bwd_nt(const BwdArgs& a, int nt, unsigned grid, hipStream_t s) {
+    switch (nt) {
+        case 2: hipLaunchKernelGGL((backward_kernel<OT, 2>), dim3(grid), dim3(256), 0, s, a); break;
+        case 4: hipLaunchKernelGGL((backward_kernel<OT, 4>), dim3(grid), dim3(256), 0, s, a); break;
+        case 8: hipLaunchKernelGGL((backward_kernel<OT, 8>), dim3(grid), dim3(256), 0, s, a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+inline int mt_for(int Bp) { return Bp / 16; }  // Bp is 32, 64 or 128
+
+inline unsigned xcd_grid(int64_t total) { return static_cast<unsigned>((total + kXcds - 1) / kXcds * kXcds); }
+
+}  // namespace
+
+hipError_t launch_gather(lc_handle* h, bool eval, int64_t k_or_base) {
+    const ActSet& S = eval ? h->eval : h->train;
+    const bool bf16 = h->md.gemm == LC_GEMM_BF16;
+    GatherArgs a;
+    a.data = h->data;
+    a.labels = h->labels;
+    a.a_bm = S.a_bm[0];
+    a.a_fm = S.a_fm[0];
+    a.lab_out = S.labels;
+    a.idx_out = S.idx;
+    a.d0 = h->layer[1].d_in;
+    a.dp0 = h->layer[1].dp_in;
+    a.B = S.B;
+    a.Bp = S.Bp;
+    a.N = h->md.N;
+    a.seed = h->seed;
+    a.k = k_or_base;
+    a.limit = h->md.E;
+    a.eval = eval ? 1 : 0;
+    const dim3 grid(a.dp0 / 64, a.Bp / 32, S.G);
+    if (eval) {
+        if (bf16) hipLaunchKernelGGL((gather_kernel<bf16_t, float>), grid, dim3(256), 0, h->stream, a);
+        else hipLaunchKernelGGL((gather_kernel<float, float>), grid, dim3(256), 0, h->stream, a);
+    } else {
+        if (bf16) hipLaunchKernelGGL((gather_kernel<bf16_t, bf16_t>), grid, dim3(256), 0, h->stream, a);
+        else hipLaunchKernelGGL((gather_kernel<float, float>), grid, dim3(256), 0, h->stream, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_forward(lc_handle* h, bool eval, int l) {
+    const ActSet& S = eval ? h->eval : h->train;
+    const LayerGeom& g = h->layer[l];
+    const bool bf16 = !eval && h->md.gemm == LC_GEMM_BF16;
+    FwdArgs a;
+    a.X = eval ? h->xbar : h->X;
+    a.x_stride = eval ? 0 : h->Ps;
+    a.w_off = g.w_off;
+    a.b_off = g.b_off;
+    a.d_in = g.d_in;
+    a.d_out = g.d_out;
+    a.dp_in = g.dp_in;
+    a.dp_out = g.dp_out;
+    a.B = S.B;
+    a.Bp = S.Bp;
+    a.a_in = S.a_bm[l - 1];
+    a.out_bm = S.a_bm[l];
+    a.out_fm = S.a_fm[l];
+    a.last = l == h->L ? 1 : 0;
+    a.vec = (g.d_out % 4 == 0 && g.w_off % 4 == 0) ? 1 : 0;
+    a.n_chunks = g.dp_out / kColChunk;
+    a.total_blocks = static_cast<int64_t>(S.G) * a.n_chunks;
+    const unsigned grid = xcd_grid(a.total_blocks);
+    const int mt = mt_for(S.Bp);
+    // few blocks: split the reduction over more wavefronts per block
+    const bool wide = a.total_blocks * 4 < 2048 && g.dp_in >= 512;
+    if (!eval) timing_start(h, kTimeFwd);
+    hipError_t e;
+    if (bf16) e = wide ? launch_fwd_mt<bf16_t, 8>(a, mt, grid, h->stream) : launch_fwd_mt<bf16_t, 4>(a, mt, grid, h->stream);
+    else e = wide ? launch_fwd_mt<float, 8>(a, mt, grid, h->stream) : launch_fwd_mt<float, 4>(a, mt, grid, h->stream);
+    if (!eval) timing_stop(h, kTimeFwd);
+    return e;
+}
+
+hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset) {
+    const ActSet& S = eval ? h->eval : h->train;
+    const bool bf16 = !eval && h->md.gemm == LC_GEMM_BF16;
+    SoftmaxArgs a;
+    a.logits = static_cast<const float*>(S.a_bm[h->L]);
+    a.labels = S.labels;
+    a.dz_bm = eval ? nullptr : S.dz_bm[h->L];
+    a.dz_fm = eval ? nullptr : S.dz_fm[h->L];
+    a.loss = S.loss + loss_offset;
+    a.C = h->layer[h->L].d_out;
+    a.dpL = h->layer[h->L].dp_out;
+    a.B = S.B;
+    a.Bp = S.Bp;
+    a.eval = eval ? 1 : 0;
+    if (bf16) hipLaunchKernelGGL((softmax_kernel<bf16_t>), dim3(S.G), dim3(128), 0, h->stream, a);
+    else hipLaunchKernelGGL((softmax_kernel<float>), dim3(S.G), dim3(128), 0, h->stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_backward(lc_handle* h, int l) {
+    const ActSet& S = h->train;
+    const LayerGeom& g = h->layer[l];
+    const bool bf16 = h->md.gemm == LC_GEMM_BF16;
+    BwdArgs a;
+    a.X = h->X;
+    a.V = h->V;
+    a.x_stride = h->Ps;
+    a.w_off = g.w_off;
+    a.b_off = g.b_off;
+    a.d_in = g.d_in;
+    a.d_out = g.d_out;
+    a.dp_in = g.dp_in;
+    a.dp_out = g.dp_out;
+    a.B = S.B;
+    a.Bp = S.Bp;
+    a.a_bm = S.a_bm[l - 1];
+    a.a_fm = S.a_fm[l - 1];
+    a.dz_bm = S.dz_bm[l];
+    a.dz_fm = S.dz_fm[l];
+    a.dzp_bm = l > 1 ? S.dz_bm[l - 1] : nullptr;
+    a.dzp_fm = l > 1 ? S.dz_fm[l - 1] : nullptr;
+    a.lr = h->md.lr;
+    a.beta = h->md.beta;
+    a.wd = h->md.wd;
+    a.vec = (g.d_out % 4 == 0 && g.w_off % 4 == 0) ? 1 : 0;
+    a.n_row_blocks = g.dp_in / 64;
+    a.total_blocks = static_cast<int64_t>(S.G) * a.n_row_blocks;
+    const unsigned grid = xcd_grid(a.total_blocks);
+    timing_start(h, kTimeBwd);
+    const hipError_t e = bf16 ? launch_bwd_nt<bf16_t>(a, S.Bp / 16, grid, h->stream)
+                              : launch_bwd_nt<float>(a, S.Bp / 16, grid, h->stream);
+    timing_stop(h, kTimeBwd);
+    return e;
+}
+
+}  // namespace lc

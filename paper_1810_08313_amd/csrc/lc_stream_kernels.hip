@@ -1,0 +1,194 @@
+// Bandwidth-bound kernels over the stacked models X[m, Ps]: replica averaging
+// (the communication step of PASGD, Sec. 2), the momentum-SGD update from
+// explicit gradients, their fusion for tau = 1, and the quadratic test
+// objective.  Every thread owns one 16-byte column of the [m, Ps] matrix, so
+// the reduction over the m axis happens in registers and each row is read and
+// written in fully coalesced 1 KiB wavefront segments.
+#include "lc_internal.h"
+
+namespace lc {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRowBatch = 8;  // rows whose loads are issued before any is consumed
+
+__device__ __forceinline__ float4 ld_stream(const float* p) {
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void st_stream(float* p, float4 v) {
+    __builtin_nontemporal_store(f32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<f32x4*>(p));
+}
+
+// x_bar = (1/m) sum_i x^(i), written to every row of out_rows (in place when
+// out_rows == X) and/or to the single vector out_single.  The sum is carried in
+// double: adding m floats in double is exact for any realistic spread of
+// magnitudes, so the result is the correctly rounded mean whatever the order.
+__global__ __launch_bounds__(kThreads) void average_kernel(const float* __restrict__ X, float* out_rows,
+                                                           float* out_single, int m, int64_t Ps) {
+    const int64_t col = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
+    if (col >= Ps) return;
+    double s0 = 0, s1 = 0, s2 = 0, s3 = 0;
+    for (int i0 = 0; i0 < m; i0 += kRowBatch) {
+        float4 r[kRowBatch];
+#pragma unroll
+        for (int u = 0; u < kRowBatch; ++u)
+            if (i0 + u < m) r[u] = ld_stream(X + static_cast<int64_t>(i0 + u) * Ps + col);
+#pragma unroll
+        for (int u = 0; u < kRowBatch; ++u)
+            if (i0 + u < m) {
+                s0 += static_cast<double>(r[u].x);
+                s1 += static_cast<double>(r[u].y);
+                s2 += static_cast<double>(r[u].z);
+                s3 += static_cast<double>(r[u].w);
+            }
+    }
+    const double dm = static_cast<double>(m);
+    const float4 mean = make_float4(static_cast<float>(s0 / dm), static_cast<float>(s1 / dm),
+                                    static_cast<float>(s2 / dm), static_cast<float>(s3 / dm));
+    if (out_rows)
+        for (int i = 0; i < m; ++i) st_stream(out_rows + static_cast<int64_t>(i) * Ps + col, mean);
+    if (out_single) *reinterpret_cast<float4*>(out_single + col) = mean;
+}
+
+__device__ __forceinline__ void sgd_update4(float4& x, float4& v, const float4& g, float lr, float beta, float wd) {
+    v.x = beta * v.x + (g.x + wd * x.x);
+    v.y = beta * v.y + (g.y + wd * x.y);
+    v.z = beta * v.z + (g.z + wd * x.z);
+    v.w = beta * v.w + (g.w + wd * x.w);
+    x.x -= lr * v.x;
+    x.y -= lr * v.y;
+    x.z -= lr * v.z;
+    x.w -= lr * v.w;
+}
+
+// g <- G + wd x; v <- beta v + g; x <- x - lr v over the whole [m, Ps] block.
+__global__ __launch_bounds__(kThreads) void update_kernel(float* X, float* V, const float* __restrict__ G,
+                                                          int64_t n4, float lr, float beta, float wd) {
+    const int64_t j = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (j >= n4) return;
+    float4 x = ld_stream(X + j * 4), v = ld_stream(V + j * 4);
+    const float4 g = ld_stream(G + j * 4);
+    sgd_update4(x, v, g, lr, beta, wd);
+    st_stream(V + j * 4, v);
+    st_stream(X + j * 4, x);
+}
+
+// tau = 1: the update of every worker and the averaging in one pass.
+__global__ __launch_bounds__(kThreads) void update_average_kernel(float* X, float* V, const float* __restrict__ G,
+                                                                  int m, int64_t Ps, float lr, float beta, float wd) {
+    const int64_t col = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
+    if (col >= Ps) return;
+    double s0 = 0, s1 = 0, s2 = 0, s3 = 0;
+    for (int i0 = 0; i0 < m; i0 += 4) {
+        float4 x[4], v[4], g[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i0 + u < m) {
+                const int64_t o = static_cast<int64_t>(i0 + u) * Ps + col;
+                x[u] = ld_stream(X + o);
+                v[u] = ld_stream(V + o);
+                g[u] = ld_stream(G + o);
+            }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i0 + u < m) {
+                sgd_update4(x[u], v[u], g[u], lr, beta, wd);
+                st_stream(V + static_cast<int64_t>(i0 + u) * Ps + col, v[u]);
+                s0 += static_cast<double>(x[u].x);
+                s1 += static_cast<double>(x[u].y);
+                s2 += static_cast<double>(x[u].z);
+                s3 += static_cast<double>(x[u].w);
+            }
+    }
+    const double dm = static_cast<double>(m);
+    const float4 mean = make_float4(static_cast<float>(s0 / dm), static_cast<float>(s1 / dm),
+                                    static_cast<float>(s2 / dm), static_cast<float>(s3 / dm));
+    for (int i = 0; i < m; ++i) st_stream(X + static_cast<int64_t>(i) * Ps + col, mean);
+}
+
+// Quadratic test objective: exact gradient g = a (x - c), then the same update.
+__global__ __launch_bounds__(kThreads) void quad_step_kernel(float* X, float* V, const float* __restrict__ A,
+                                                             const float* __restrict__ C, int64_t n4, float lr,
+                                                             float beta, float wd) {
+    const int64_t j = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (j >= n4) return;
+    float4 x = *reinterpret_cast<const float4*>(X + j * 4), v = *reinterpret_cast<const float4*>(V + j * 4);
+    const float4 a = *reinterpret_cast<const float4*>(A + j * 4), c = *reinterpret_cast<const float4*>(C + j * 4);
+    const float4 g = make_float4(a.x * (x.x - c.x), a.y * (x.y - c.y), a.z * (x.z - c.z), a.w * (x.w - c.w));
+    sgd_update4(x, v, g, lr, beta, wd);
+    *reinterpret_cast<float4*>(V + j * 4) = v;
+    *reinterpret_cast<float4*>(X + j * 4) = x;
+}
+
+// partial[block] = sum over the block's columns and all workers of
+// 0.5 a (xbar - c)^2, in double, in a fixed order.
+__global__ __launch_bounds__(kThreads) void quad_loss_kernel(const float* __restrict__ xbar,
+                                                             const float* __restrict__ A,
+                                                             const float* __restrict__ C, int m, int64_t P,
+                                                             int64_t Ps, double* partial) {
+    __shared__ double red[kThreads];
+    const int64_t p = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    double s = 0.0;
+    if (p < P) {
+        const double xb = static_cast<double>(xbar[p]);
+        for (int i = 0; i < m; ++i) {
+            const double d = xb - static_cast<double>(C[static_cast<int64_t>(i) * Ps + p]);
+            s += 0.5 * static_cast<double>(A[static_cast<int64_t>(i) * Ps + p]) * d * d;
+        }
+    }
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = kThreads / 2; w > 0; w >>= 1) {
+        if (threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
+}
+
+inline unsigned blocks_for(int64_t threads) { return static_cast<unsigned>((threads + kThreads - 1) / kThreads); }
+
+}  // namespace
+
+hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* out_single) {
+    if (out_rows) timing_start(h, kTimeAvg);
+    hipLaunchKernelGGL(average_kernel, dim3(blocks_for(h->Ps / 4)), dim3(kThreads), 0, h->stream, X, out_rows,
+                       out_single, h->m, h->Ps);
+    if (out_rows) timing_stop(h, kTimeAvg);
+    return hipGetLastError();
+}
+
+hipError_t launch_update_from_grad(lc_handle* h) {
+    const int64_t n4 = static_cast<int64_t>(h->m) * h->Ps / 4;
+    timing_start(h, kTimeUpd);
+    hipLaunchKernelGGL(update_kernel, dim3(blocks_for(n4)), dim3(kThreads), 0, h->stream, h->X, h->V, h->G, n4,
+                       h->md.lr, h->md.beta, h->md.wd);
+    timing_stop(h, kTimeUpd);
+    return hipGetLastError();
+}
+
+hipError_t launch_update_and_average(lc_handle* h) {
+    timing_start(h, kTimeUpdAvg);
+    hipLaunchKernelGGL(update_average_kernel, dim3(blocks_for(h->Ps / 4)), dim3(kThreads), 0, h->stream, h->X, h->V,
+                       h->G, h->m, h->Ps, h->md.lr, h->md.beta, h->md.wd);
+    timing_stop(h, kTimeUpdAvg);
+    return hipGetLastError();
+}
+
+hipError_t launch_quad_step(lc_handle* h) {
+    const int64_t n4 = static_cast<int64_t>(h->m) * h->Ps / 4;
+    hipLaunchKernelGGL(quad_step_kernel, dim3(blocks_for(n4)), dim3(kThreads), 0, h->stream, h->X, h->V, h->qa,
+                       h->qc, n4, h->md.lr, h->md.beta, h->md.wd);
+    return hipGetLastError();
+}
+
+hipError_t launch_quad_loss(lc_handle* h, int* n_partial) {
+    const unsigned nb = blocks_for(h->P);
+    *n_partial = static_cast<int>(nb);
+    hipLaunchKernelGGL(quad_loss_kernel, dim3(nb), dim3(kThreads), 0, h->stream, h->xbar, h->qa, h->qc, h->m, h->P,
+                       h->Ps, h->partial);
+    return hipGetLastError();
+}
+
+}  // namespace lc

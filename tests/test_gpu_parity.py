@@ -1,0 +1,483 @@
+"""GPU parity: the HIP path, called through the C ABI, against the oracle on the
+same seeded inputs.  Integers (index stream, tau schedule, counters) and the
+averaging step are compared bit for bit; parameters, buffers and losses within
+1e-4 relative for fp32 operands and 2e-2 for bf16 operands (relative to the
+largest magnitude of the compared block, per layer block)."""
+import ctypes as C
+import sys
+
+import numpy as np
+import pytest
+
+import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL32, TOL16 = 1e-4, 2e-2
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_1810_08313_amd as p
+    p.lib()
+    return p
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _blocks(dims):
+    """(name, slice) of every W_l and b_l inside a flat parameter vector."""
+    out, off = [], 0
+    for l in range(len(dims) - 1):
+        nw = dims[l] * dims[l + 1]
+        out.append((f"W{l + 1}", slice(off, off + nw)))
+        out.append((f"b{l + 1}", slice(off + nw, off + nw + dims[l + 1])))
+        off += nw + dims[l + 1]
+    return out
+
+
+GATE_EPS = 4e-6      # |z| below this (times the layer's rms) cannot be signed reliably in fp32
+GATE_EPS16 = 1e-3    # same, below a layer whose bf16-rounded activations feed z
+GATE_TOL = 5e-2      # blocks below a layer with such a gate see its effect diluted, not removed
+
+
+def _undecided_gates(orc, omd, x, data, idx):
+    """ReLU'(z) is a step at 0: where the oracle's pre-activation is within the
+    accumulation error of zero, the side it falls on depends on summation order
+    (double in the oracle, fp32 MFMA on the GPU) and both outcomes are valid.
+    With bf16 operands the error is larger from layer 2 on: an activation of the
+    layer below that sits on a bf16 rounding boundary may round either way
+    (2^-8 relative), which moves every z above it by about 1e-4.
+    Returns {layer: set(units)} of such gates for one worker's batch."""
+    out = {}
+    for l, z in enumerate(orc.mlp_preactivations(omd, x, data, idx), start=1):
+        rms = max(1.0, float(np.sqrt(np.mean(z.astype(np.float64) ** 2))))
+        eps = GATE_EPS16 if (omd.bf16 and l >= 2) else GATE_EPS
+        units = set(np.nonzero((np.abs(z) < eps * rms).any(axis=0))[0].tolist())
+        if units:
+            out[l] = units
+    return out
+
+
+def _assert_close(got, want, dims, tol, what, gates=None):
+    """Per block: max |got - want| / max |want| < tol.  A unit whose gate is
+    undecided (see above) is left out of its own layer's block; blocks of the
+    layers below it are held to GATE_TOL, since one flipped term in their
+    delta sums changes them at the per-cent level."""
+    gates = gates or {}
+    top = max(gates) if gates else 0
+    for name, sl in _blocks(dims):
+        layer = int(name[1:])
+        g, w = got[..., sl].astype(np.float64), want[..., sl].astype(np.float64)
+        if layer in gates:
+            keep = np.ones(dims[layer], dtype=bool)
+            keep[list(gates[layer])] = False
+            if name[0] == "W":
+                g = g.reshape(g.shape[:-1] + (dims[layer - 1], dims[layer]))[..., keep]
+                w = w.reshape(w.shape[:-1] + (dims[layer - 1], dims[layer]))[..., keep]
+            else:
+                g, w = g[..., keep], w[..., keep]
+        scale = np.abs(w).max()
+        if scale == 0.0:
+            assert np.abs(g).max() == 0.0, (what, name)
+            continue
+        err = np.abs(g - w).max() / scale
+        t = max(tol, GATE_TOL) if layer < top else tol
+        assert err < t, f"{what} {name}: rel err {err:.3e} >= {t}"
+
+
+def _problem(pkg, orc, dims, m, B, N=400, lr=0.1, beta=0.9, wd=0.0, bf16=False, seed=11, E=None, mean_sd=1.0):
+    data, labels = synth.gaussian_mixture(seed, N, dims[0], dims[-1], mean_sd=mean_sd)
+    if bf16:
+        data = synth.bf16_representable(data)
+    x1 = synth.init_params(seed, dims)
+    # non-zero biases so that the bias path matters from the first step
+    for name, sl in _blocks(dims):
+        if name.startswith("b"):
+            x1[sl] = 0.05
+    E = min(N, 300) if E is None else E
+    omd = orc.make_model(orc.KIND_MLP, dims, B=B, N=N, E=E, lr=lr, beta=beta, wd=wd, bf16=bf16)
+    gmd = pkg.make_model(pkg.KIND_MLP, dims, B=B, N=N, E=E, lr=lr, beta=beta, wd=wd, bf16=bf16)
+    ref = orc.Run(m, omd, seed, x1, data, labels)
+    run = pkg.LocalSGD(m, gmd, seed, x1, data, labels)
+    return ref, run
+
+
+SHAPES = [
+    # dims, m, B        -- ragged everywhere, one tile
+    ([50, 37, 5], 3, 5),
+    # softmax regression of the small configuration
+    ([64, 10], 4, 32),
+    # three layers, several row/column tiles with ragged tails, B not a multiple of 16
+    ([130, 70, 33, 7], 2, 48),
+    # widths that are not multiples of 4 (unaligned weight rows)
+    ([67, 129, 10], 2, 33),
+    # the 2-layer configuration's layer shapes
+    ([784, 256, 10], 8, 64),
+    # full 128-row batch tile
+    ([200, 128, 10], 3, 128),
+]
+
+
+# ------------------------------------------------------------------ integers
+
+def test_index_stream_bit_exact(pkg, orc):
+    _say("index stream")
+    dims, m, B, N = [20, 6], 5, 37, 1000
+    ref, run = _problem(pkg, orc, dims, m, B, N=N, lr=0.0)
+    for k in (0, 1, 123456789):
+        run.set_state(None, None, k)
+        run.local_steps(1)
+        got = run.last_indices()
+        want = np.array([[orc.index(11, i, k, b, N) for b in range(B)] for i in range(m)], dtype=np.int32)
+        assert np.array_equal(got, want), k
+        assert run.k == k + 1
+    run.close()
+
+
+# ------------------------------------------------------------------ averaging
+
+@pytest.mark.parametrize("m,P", [(1, 7), (3, 50), (5, 1000), (16, 70001), (64, 257), (7, 4096)])
+def test_average_bit_exact(pkg, orc, m, P):
+    _say(f"average m={m} P={P}")
+    X, _ = synth.flat_stress(m * 1000 + P, m, P)
+    X[:, ::7] *= 1000.0          # mixed magnitudes
+    Vv = (X * 0.5).astype(np.float32)
+    md_o = orc.make_model(orc.KIND_QUAD, [P])
+    ref = orc.Run(m, md_o, 0, X[0], qa=np.ones((m, P), np.float32), qc=np.zeros((m, P), np.float32))
+    ref.X[:] = X
+    ref.average()
+    run = pkg.LocalSGD(m, pkg.make_model(pkg.KIND_QUAD, [P]), 0, qa=np.ones((m, P), np.float32),
+                       qc=np.zeros((m, P), np.float32))
+    run.set_state(X, Vv, 0)
+    run.average()
+    got, gotV, _ = run.get_state()
+    assert np.array_equal(got.view(np.uint32), ref.X.view(np.uint32))
+    assert np.array_equal(gotV.view(np.uint32), Vv.view(np.uint32))       # buffers are not communicated
+    for i in range(m):
+        assert np.array_equal(got[i].view(np.uint32), got[0].view(np.uint32))
+    run.average()                                                          # J J = J
+    again, _, _ = run.get_state()
+    assert np.array_equal(again.view(np.uint32), got.view(np.uint32))
+    # the row padding stays zero
+    assert float(run.X[:, P:].abs().max().item()) == 0.0 if run.Ps > P else True
+    run.close()
+
+
+@pytest.mark.parametrize("m,P", [(3, 50), (8, 10007)])
+def test_update_from_grad_and_fused_average(pkg, orc, m, P):
+    _say(f"update_from_grad m={m} P={P}")
+    X, G = synth.flat_stress(5, m, P)
+    kw = dict(lr=0.05, beta=0.9, wd=1e-3)
+    ones, zeros = np.ones((m, P), np.float32), np.zeros((m, P), np.float32)
+    ref = orc.Run(m, orc.make_model(orc.KIND_QUAD, [P], **kw), 0, X[0], qa=ones, qc=zeros)
+    ref.X[:] = X
+    run = pkg.LocalSGD(m, pkg.make_model(pkg.KIND_QUAD, [P], **kw), 0, qa=ones, qc=zeros)
+    run.set_state(X, zeros, 0)
+    run.set_grad(G)
+    for _ in range(3):
+        ref.update_from_grad(G)
+        run.update_from_grad()
+    gx, gv, k = run.get_state()
+    assert k == 0
+    assert np.abs(gx - ref.X).max() < 1e-6 * np.abs(ref.X).max()
+    assert np.abs(gv - ref.V).max() < 1e-6 * np.abs(ref.V).max()
+    # tau = 1 fusion: update then average in one pass
+    ref.update_from_grad(G)
+    ref.average()
+    run.update_from_grad_and_average()
+    gx, gv, _ = run.get_state()
+    assert np.abs(gx - ref.X).max() < 1e-6 * np.abs(ref.X).max()
+    assert np.abs(gv - ref.V).max() < 1e-6 * np.abs(ref.V).max()
+    for i in range(m):
+        assert np.array_equal(gx[i].view(np.uint32), gx[0].view(np.uint32))
+    run.close()
+
+
+# ------------------------------------------------------------- one local step
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("dims,m,B", SHAPES)
+def test_one_local_step(pkg, orc, dims, m, B, bf16):
+    _say(f"one step dims={dims} m={m} B={B} bf16={bf16}")
+    ref, run = _problem(pkg, orc, dims, m, B, wd=1e-3, bf16=bf16)
+    x1 = ref.X[0].copy()
+    data = ref._keep[1]
+    ref.local_steps(1)
+    run.local_steps(1)
+    X, V, k = run.get_state()
+    tol = TOL16 if bf16 else TOL32
+    assert k == 1 == ref.k
+    for i in range(m):
+        gates = _undecided_gates(orc, ref.md, x1, data, [orc.index(11, i, 0, b, 400) for b in range(B)])
+        # after the first step V is the gradient (+ wd x): the sensitive comparison
+        _assert_close(V[i], ref.V[i], dims, tol, f"V[{i}]", gates)
+        _assert_close(X[i], ref.X[i], dims, tol, f"X[{i}]", gates)
+    ll = run.local_losses()
+    assert np.abs(ll - ref.last_losses).max() < tol * np.abs(ref.last_losses).max()
+    run.close()
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_round_of_local_steps_then_average(pkg, orc, bf16):
+    dims, m, B, tau = [130, 70, 33, 7], 4, 48, 5
+    _say(f"round dims={dims} bf16={bf16}")
+    ref, run = _problem(pkg, orc, dims, m, B, wd=5e-4, bf16=bf16)
+    tol = TOL16 if bf16 else TOL32
+    for r in range(2):
+        ref.local_steps(tau)
+        run.local_steps(tau)
+        X, V, _ = run.get_state()
+        _assert_close(X, ref.X, dims, tol, f"X before average {r}")
+        ref.average()
+        run.average()
+        X, V, k = run.get_state()
+        _assert_close(X, ref.X, dims, tol, f"X round {r}")
+        _assert_close(V, ref.V, dims, tol * 5, f"V round {r}")
+        for i in range(1, m):
+            assert np.array_equal(X[i].view(np.uint32), X[0].view(np.uint32))
+        assert k == ref.k == tau * (r + 1)
+    run.close()
+
+
+def test_plain_sgd_without_momentum_and_repeatability(pkg, orc):
+    dims, m, B = [64, 10], 4, 32
+    _say("plain SGD, repeatability")
+    outs = []
+    for rep in range(2):
+        ref, run = _problem(pkg, orc, dims, m, B, beta=0.0, lr=0.05)
+        run.local_steps(4)
+        run.average()
+        outs.append(run.get_state())
+        if rep == 0:
+            ref.local_steps(4)
+            ref.average()
+            _assert_close(outs[0][0], ref.X, dims, TOL32, "X")
+        run.close()
+    assert np.array_equal(outs[0][0].view(np.uint32), outs[1][0].view(np.uint32))   # bit-identical reruns
+    assert np.array_equal(outs[0][1].view(np.uint32), outs[1][1].view(np.uint32))
+
+
+# --------------------------------------------------------------- loss + driver
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_loss_of_averaged_model(pkg, orc, bf16):
+    dims, m, B = [130, 70, 33, 7], 3, 16
+    _say(f"loss bf16={bf16}")
+    # E = 300 is not a multiple of the 128-sample evaluation chunk
+    ref, run = _problem(pkg, orc, dims, m, B, bf16=bf16, E=300)
+    assert abs(run.loss() - ref.loss()) < 1e-5 * ref.loss()
+    ref.local_steps(2)
+    run.local_steps(2)
+    before = run.get_state()
+    Fg, Fr = run.loss(), ref.loss()          # workers differ here: the loss is that of their mean
+    assert abs(Fg - Fr) < (TOL16 if bf16 else TOL32) * Fr
+    after = run.get_state()
+    assert np.array_equal(before[0], after[0]) and np.array_equal(before[1], after[1])
+    run.close()
+
+
+def test_loss_many_chunks(pkg, orc):
+    dims = [40, 10]
+    _say("loss over several passes")
+    ref, run = _problem(pkg, orc, dims, 2, 8, N=9000, E=8500)   # > 64 chunks: two passes
+    assert abs(run.loss() - ref.loss()) < 1e-5 * ref.loss()
+    run.close()
+
+
+def test_cfg1_full_run(pkg, orc):
+    """The small configuration end to end: softmax regression, m=4, B=32,
+    tau=4, 200 iterations, plain SGD from zero (convex: errors do not amplify)."""
+    _say("cfg1 full run")
+    w = synth.make_workload("cfg1")
+    omd = orc.make_model(orc.KIND_MLP, w.dims, B=w.B, N=w.N, E=w.E, lr=w.lr, beta=w.beta)
+    gmd = pkg.make_model(pkg.KIND_MLP, w.dims, B=w.B, N=w.N, E=w.E, lr=w.lr, beta=w.beta)
+    ref = orc.Run(w.m, omd, w.seed, w.x1, w.data, w.labels)
+    run = pkg.LocalSGD(w.m, gmd, w.seed, w.x1, w.data, w.labels)
+    F0 = run.loss()
+    assert abs(F0 - np.log(10.0)) < 1e-6            # zero init: uniform prediction
+    s_ref, r_ref = ref.run(w.K, w.tau0)
+    s_gpu, r_gpu = run.run(w.K, w.tau0)
+    assert s_gpu == s_ref == [(0, 4)] and r_gpu == r_ref == 50
+    X, V, k = run.get_state()
+    assert k == ref.k == 200
+    _assert_close(X, ref.X, w.dims, TOL32, "X")
+    Fg, Fr = run.loss(), ref.loss()
+    assert abs(Fg - Fr) < TOL32 * Fr and Fg < 0.5 * F0
+    run.close()
+
+
+def test_adaptive_schedule_bit_exact(pkg, orc):
+    """AdaComm on a small MLP: same tau decisions, rounds and counters as the
+    oracle.  Every decision is checked to sit far enough from an integer that
+    the 1e-4 loss tolerance cannot flip the ceil."""
+    dims, m, B = [64, 32, 10], 4, 32
+    _say("adaptive schedule")
+    ref, run = _problem(pkg, orc, dims, m, B, N=2000, lr=0.05, beta=0.0, E=1024, mean_sd=2.0)
+    K, tau0, I = 120, 8, 24
+    s_ref, r_ref = ref.run(K, tau0, adaptive=True, interval=I)
+    s_gpu, r_gpu = run.run(K, tau0, adaptive=True, interval=I)
+    assert len(s_ref) >= 4 and s_ref[-1][1] < tau0      # the loss fell, so tau fell
+    assert s_gpu == s_ref and r_gpu == r_ref
+    assert run.k == ref.k == K
+    X, V, _ = run.get_state()
+    _assert_close(X, ref.X, dims, 1e-3, "X after adaptive run")
+    run.close()
+
+
+# ------------------------------------------------------------------ quadratic
+
+def test_quadratic_closed_form_and_schedule(pkg, orc):
+    _say("quadratic")
+    m, P, lr, tau, R = 4, 333, 0.2, 4, 5
+    a, c, x0 = synth.quad_problem(2, m, P)
+    run = pkg.LocalSGD(m, pkg.make_model(pkg.KIND_QUAD, [P], lr=lr), 0, x0, qa=a, qc=c)
+    for _ in range(R):
+        run.local_steps(tau)
+        run.average()
+    rho = 1.0 - lr * a.astype(np.float64)
+    alpha = (rho ** tau).mean(axis=0)
+    bt = ((1.0 - rho ** tau) * c).mean(axis=0)
+    want = alpha ** R * x0 + bt * (1.0 - alpha ** R) / (1.0 - alpha)
+    X, V, k = run.get_state()
+    assert k == tau * R
+    assert np.abs(X[0] - want).max() < 2e-5
+    xbar = X[0].astype(np.float64)
+    F = float(np.mean([0.5 * np.sum(a[i].astype(np.float64) * (xbar - c[i].astype(np.float64)) ** 2) for i in range(m)]))
+    assert abs(run.loss() - F) < 1e-9 * F
+    run.close()
+
+    # momentum + adaptive schedule against the oracle
+    kw = dict(lr=0.02, beta=0.5)
+    a, c, x0 = synth.quad_problem(8, m, P, common_a=True)
+    c = (c * 0.05).astype(np.float32)
+    ref = orc.Run(m, orc.make_model(orc.KIND_QUAD, [P], **kw), 0, x0, qa=a, qc=c)
+    run = pkg.LocalSGD(m, pkg.make_model(pkg.KIND_QUAD, [P], **kw), 0, x0, qa=a, qc=c)
+    s_ref, r_ref = ref.run(150, 12, adaptive=True, interval=20)
+    s_gpu, r_gpu = run.run(150, 12, adaptive=True, interval=20)
+    assert s_gpu == s_ref and r_gpu == r_ref and len(s_ref) > 3
+    X, V, k = run.get_state()
+    assert k == ref.k
+    assert np.abs(X - ref.X).max() < 1e-4 * np.abs(ref.X).max()
+    assert np.abs(V - ref.V).max() < 1e-4 * max(np.abs(ref.V).max(), 1e-3)
+    run.close()
+
+
+# --------------------------------------------------------------- error paths
+
+def test_attach_errors_and_bad_tau(pkg):
+    import torch
+    _say("error paths")
+    L = pkg.lib()
+    md = pkg.make_model(pkg.KIND_MLP, [8, 4, 3], B=4, N=10, E=10)
+    P = pkg.lc_param_count(md)
+    Ps = pkg.lc_row_stride(P)
+    h = C.c_void_p()
+    assert L.lc_init(2, P, C.byref(md), 1, C.byref(h)) == 0
+    ws = int(L.lc_workspace_bytes(h))
+    X = torch.zeros(2 * Ps + 64, dtype=torch.float32, device="cuda:0")
+    V = torch.zeros(2 * Ps, dtype=torch.float32, device="cuda:0")
+    S = torch.empty(ws, dtype=torch.uint8, device="cuda:0")
+    D = torch.zeros(10 * 8, dtype=torch.float32, device="cuda:0")
+    Lb = torch.zeros(10, dtype=torch.int32, device="cuda:0")
+    st = torch.cuda.current_stream().cuda_stream
+    assert L.lc_attach(h, X.data_ptr(), V.data_ptr(), S.data_ptr(), ws - 1, D.data_ptr(), Lb.data_ptr(), st) == -5
+    assert L.lc_attach(h, X.data_ptr() + 4, V.data_ptr(), S.data_ptr(), ws, D.data_ptr(), Lb.data_ptr(), st) == -4
+    assert L.lc_attach(h, X.data_ptr(), V.data_ptr(), S.data_ptr(), ws, None, Lb.data_ptr(), st) == -1
+    assert L.lc_attach(h, X.data_ptr(), V.data_ptr(), S.data_ptr(), ws, D.data_ptr(), Lb.data_ptr(), st) == 0
+    assert L.lc_local_steps(h, 0) == -1
+    assert L.lc_local_steps(h, -3) == -1
+    assert L.lc_update_from_grad(h) == -3            # no gradient buffer set
+    assert L.lc_local_steps(h, 1) == 0
+    torch.cuda.synchronize()
+    L.lc_destroy(h)
+
+
+# ------------------------------------------------------------ full-size checks
+
+@pytest.mark.parametrize("name,replicas", [("cfg3", (0, 15)), ("cfg4", (63,))])
+def test_full_size_local_step_sampled_replicas(pkg, orc, name, replicas):
+    """One local step at the full layer shapes, batch and replica count of the
+    large configurations; the oracle recomputes the sampled replicas (workers do
+    not interact inside a period)."""
+    _say(f"full-size step {name}")
+    w = synth.make_workload(name, N=4096, E=256)
+    omd = orc.make_model(orc.KIND_MLP, w.dims, B=w.B, N=w.N, E=w.E, lr=w.lr, beta=w.beta, bf16=True)
+    gmd = pkg.make_model(pkg.KIND_MLP, w.dims, B=w.B, N=w.N, E=w.E, lr=w.lr, beta=w.beta, bf16=True)
+    run = pkg.LocalSGD(w.m, gmd, w.seed, w.x1, w.data, w.labels)
+    run.local_steps(1)
+    X, V, k = run.get_state()
+    assert k == 1
+    orc.set_threads(8)
+    ref = orc.Run(w.m, omd, w.seed, w.x1, w.data, w.labels)
+    ref.local_steps(1, ids=list(replicas))
+    orc.set_threads(1)
+    for i in replicas:
+        gates = _undecided_gates(orc, omd, w.x1, w.data, [orc.index(w.seed, i, 0, b, w.N) for b in range(w.B)])
+        _say(f"  replica {i}: undecided gates per layer { {l: len(u) for l, u in gates.items()} }")
+        _assert_close(V[i], ref.V[i], w.dims, TOL16, f"V[{i}]", gates)
+        _assert_close(X[i], ref.X[i], w.dims, TOL16, f"X[{i}]", gates)
+    ll = run.local_losses()
+    for i in replicas:
+        assert abs(ll[i] - ref.last_losses[i]) < TOL16 * ref.last_losses[i]
+    # the untouched replicas of the oracle still hold x_1, the GPU's have all moved
+    assert np.abs(X - w.x1).max(axis=1).min() > 0
+    run.average()
+    Xa, _, _ = run.get_state()
+    cols = np.random.default_rng(0).choice(w.P, 4096, replace=False)
+    want = X[:, cols].astype(np.float64).mean(axis=0).astype(np.float32)
+    assert np.array_equal(Xa[0, cols].view(np.uint32), want.view(np.uint32))
+    assert all(np.array_equal(Xa[i], Xa[0]) for i in range(1, w.m))
+    run.close()
+
+
+@pytest.mark.parametrize("m,P", [(16, 25_600_000), (8, 138_000_000)])
+def test_full_size_averaging_and_update(pkg, m, P):
+    """The averaging stress sizes: sampled columns against the exact mean, all
+    rows identical, buffers untouched; then the update from explicit gradients
+    on sampled entries."""
+    import torch
+    _say(f"full-size average m={m} P={P}")
+    kw = dict(lr=0.05, beta=0.9)
+    # build without host-side [m, P] arrays: fill the device tensors directly
+    L = pkg.lib()
+    md = pkg.make_model(pkg.KIND_QUAD, [P], **kw)
+    h = C.c_void_p()
+    assert L.lc_init(m, P, C.byref(md), 0, C.byref(h)) == 0
+    Ps = pkg.lc_row_stride(P)
+    assert Ps == P
+    gen = torch.Generator(device="cuda:0").manual_seed(1234)
+    X = torch.randn((m, Ps), generator=gen, device="cuda:0") * 0.1
+    V = torch.zeros((m, Ps), device="cuda:0")
+    G = torch.randn((m, Ps), generator=gen, device="cuda:0") * 1e-3
+    ws = int(L.lc_workspace_bytes(h))
+    S = torch.empty(ws, dtype=torch.uint8, device="cuda:0")
+    st = torch.cuda.current_stream().cuda_stream
+    assert L.lc_attach(h, X.data_ptr(), V.data_ptr(), S.data_ptr(), ws, None, None, st) == 0
+    cols = torch.from_numpy(np.concatenate([np.arange(0, 2048), np.arange(P - 2048, P),
+                                            np.random.default_rng(1).choice(P, 20000, replace=False)])).to("cuda:0")
+    x0 = X[:, cols].cpu().numpy()
+    g0 = G[:, cols].cpu().numpy()
+    assert L.lc_set_grad(h, G.data_ptr()) == 0
+    assert L.lc_update_from_grad(h) == 0
+    torch.cuda.synchronize()
+    v1 = (g0.astype(np.float64))
+    x1 = x0.astype(np.float64) - kw["lr"] * v1
+    assert np.abs(V[:, cols].cpu().numpy() - v1).max() < 1e-6 * np.abs(v1).max()
+    assert np.abs(X[:, cols].cpu().numpy() - x1).max() < 1e-6 * np.abs(x1).max()
+    xs = X[:, cols].cpu().numpy()
+    Vb = V[:, cols].clone()
+    assert L.lc_average(h) == 0
+    torch.cuda.synchronize()
+    want = xs.astype(np.float64).mean(axis=0).astype(np.float32)
+    got = X[:, cols].cpu().numpy()
+    for i in range(m):
+        assert np.array_equal(got[i].view(np.uint32), want.view(np.uint32))
+    assert bool((X == X[0:1]).all().item())
+    assert bool((V[:, cols] == Vb).all().item())
+    L.lc_destroy(h)
