@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Throughput of the local-update SGD hot path on one MI355X.
+
+A "step" is one local iteration of all m replicas (mini-batch gather, forward,
+softmax cross-entropy, backward with fused momentum update), with the replica
+averaging every tau steps and, for the adaptive workloads, the loss evaluation
+and AdaComm decision every `interval` steps -- i.e. the whole schedule driver
+(lc_run) over K iterations.  Inputs are synthetic and resident in HBM before
+the timed region starts.
+
+Prints ONE JSON line: replica-steps/s for the workload, the roofline figures of
+the dominant kernel (measured with HIP events around each of its launches in a
+second pass over the same steps), and the oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+DEFAULT_STEPS = {"cfg1": 2000, "cfg2": 2000, "cfg3": 200, "cfg4": 40, "cfg5a": 50, "cfg5b": 20}
+DEFAULT_WARMUP = {"cfg1": 100, "cfg2": 100, "cfg3": 20, "cfg4": 5, "cfg5a": 5, "cfg5b": 3}
+FLAT = {"cfg5a": (16, 25_600_000), "cfg5b": (8, 138_000_000)}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="cfg2", choices=sorted(DEFAULT_STEPS))
+    ap.add_argument("--tau", type=int, default=None, help="fixed communication period (overrides the workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the averaging-stress figures")
+    return ap.parse_args()
+
+
+def sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def bench_mlp(args, pkg, synth):
+    import torch
+    name = args.workload
+    w = synth.make_workload(name)
+    tau0 = args.tau if args.tau is not None else w.tau0
+    adaptive = w.adaptive and args.tau is None
+    K = args.steps if args.steps is not None else DEFAULT_STEPS[name]
+    W = args.warmup if args.warmup is not None else DEFAULT_WARMUP[name]
+    md = pkg.make_model(pkg.KIND_MLP, w.dims, B=w.B, N=w.N, E=w.E, lr=w.lr, beta=w.beta, wd=w.wd, bf16=w.bf16)
+    run = pkg.LocalSGD(w.m, md, w.seed, w.x1, w.data, w.labels)
+    interval = w.interval if adaptive else 0
+
+    run.run(W, tau0, adaptive=False) if W > 0 else None
+    sync()
+    t0 = time.perf_counter()
+    sched, rounds = run.run(K, tau0, adaptive=adaptive, interval=interval)
+    sync()
+    sec = time.perf_counter() - t0
+
+    # second pass over the same number of steps with HIP events around every
+    # launch of the dominant kernel (backward + fused update)
+    from paper_1810_08313_amd.binding import TIME_BWD, TIME_NONE
+    K2 = min(K, 200)
+    run.timing_begin(TIME_BWD)
+    run.run(K2, tau0, adaptive=False)
+    launches, total_ms = run.timing_read()
+    run.timing_begin(TIME_NONE)
+    bytes_per_iter = 16.0 * w.m * w.P                    # read W,V + write W,V of every replica, fp32
+    per_launch_bytes = bytes_per_iter * K2 / launches
+    avg_launch_ms = total_ms / launches
+    achieved = per_launch_bytes / (avg_launch_ms * 1e-3) / 1e9
+    roof = {"bound": "hbm", "kernel": "backward_kernel (dA + dW + momentum update, all layers)",
+            "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+            "launches": launches, "avg_launch_us": round(avg_launch_ms * 1e3, 2),
+            "algorithmic_bytes_per_launch": per_launch_bytes}
+    final_loss = run.loss()
+    run.close()
+    cfg = {"workload": f"{name}: MLP {'-'.join(map(str, w.dims))}, m={w.m}, B={w.B}, "
+                       f"{'AdaComm tau0=' if adaptive else 'tau='}{tau0}"
+                       f"{', interval=%d' % interval if adaptive else ''}, lr={w.lr}, momentum={w.beta}",
+           "m": w.m, "P": w.P, "batch_per_replica": w.B, "tau0": tau0, "adaptive": adaptive,
+           "averaging_rounds": rounds, "tau_schedule": sched[:16], "final_loss": round(final_loss, 6)}
+    return dict(value=w.m * K / sec, sec=sec, K=K, W=W, roofline=roof, config=cfg,
+                dtype="bf16" if w.bf16 else "f32", workload=w, tau0=tau0)
+
+
+def bench_flat(args, pkg, name):
+    """Averaging stress: {update from explicit gradients; average} per step."""
+    import ctypes as C
+    import torch
+    from paper_1810_08313_amd.binding import TIME_AVG, TIME_NONE
+    m, P = FLAT[name]
+    K = args.steps if args.steps is not None else DEFAULT_STEPS[name]
+    W = args.warmup if args.warmup is not None else DEFAULT_WARMUP[name]
+    res = flat_measure(pkg, m, P, K, W)
+    roof = {"bound": "hbm", "kernel": "average_kernel", "achieved": round(res["avg_gbs"], 1), "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": round(res["avg_gbs"] / HBM_PEAK_GBS, 4), "traffic": None,
+            "launches": res["launches"], "avg_launch_us": round(res["avg_us"], 2),
+            "algorithmic_bytes_per_launch": 8.0 * m * P}
+    cfg = {"workload": f"{name}: flat fp32 vectors m={m}, P={P}, step = momentum-SGD update from explicit "
+                       f"gradients + replica averaging", "m": m, "P": P,
+           "update_GBps": round(res["upd_gbs"], 1), "fused_update_average_GBps": round(res["fused_gbs"], 1)}
+    return dict(value=m * K / res["sec"], sec=res["sec"], K=K, W=W, roofline=roof, config=cfg, dtype="f32",
+                workload=None, tau0=1)
+
+
+def flat_measure(pkg, m, P, K, W):
+    import ctypes as C
+    import torch
+    from paper_1810_08313_amd.binding import TIME_AVG, TIME_UPD, TIME_UPDAVG, TIME_NONE
+    L = pkg.lib()
+    md = pkg.make_model(pkg.KIND_QUAD, [P], lr=0.05, beta=0.9)
+    h = C.c_void_p()
+    assert L.lc_init(m, P, C.byref(md), 0, C.byref(h)) == 0
+    Ps = pkg.lc_row_stride(P)
+    gen = torch.Generator(device="cuda:0").manual_seed(20181008)
+    X = torch.zeros((m, Ps), device="cuda:0")
+    X[:, :P] = torch.randn((m, P), generator=gen, device="cuda:0") * 0.1
+    V = torch.zeros((m, Ps), device="cuda:0")
+    G = torch.zeros((m, Ps), device="cuda:0")
+    G[:, :P] = torch.randn((m, P), generator=gen, device="cuda:0") * 1e-3
+    ws = int(L.lc_workspace_bytes(h))
+    S = torch.empty(ws, dtype=torch.uint8, device="cuda:0")
+    assert L.lc_attach(h, X.data_ptr(), V.data_ptr(), S.data_ptr(), ws, None, None,
+                       torch.cuda.current_stream().cuda_stream) == 0
+    assert L.lc_set_grad(h, G.data_ptr()) == 0
+
+    def step():
+        assert L.lc_update_from_grad(h) == 0
+        assert L.lc_average(h) == 0
+
+    for _ in range(W):
+        step()
+    sync()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step()
+    sync()
+    sec = time.perf_counter() - t0
+
+    out = {"sec": sec}
+    n, ms = C.c_int64(0), C.c_double(0.0)
+    for which, key, nbytes in ((TIME_AVG, "avg", 8.0 * m * P), (TIME_UPD, "upd", 20.0 * m * P)):
+        L.lc_timing_begin(h, which)
+        for _ in range(K):
+            step()
+        assert L.lc_timing_read(h, C.byref(n), C.byref(ms)) == 0
+        out[key + "_gbs"] = nbytes / (ms.value / n.value * 1e-3) / 1e9
+        out[key + "_us"] = ms.value / n.value * 1e3
+        if key == "avg":
+            out["launches"] = n.value
+    L.lc_timing_begin(h, TIME_UPDAVG)
+    for _ in range(K):
+        assert L.lc_update_from_grad_and_average(h) == 0
+    assert L.lc_timing_read(h, C.byref(n), C.byref(ms)) == 0
+    out["fused_gbs"] = 20.0 * m * P / (ms.value / n.value * 1e-3) / 1e9
+    out["fused_us"] = ms.value / n.value * 1e3
+    L.lc_timing_begin(h, TIME_NONE)
+    sync()
+    L.lc_destroy(h)
+    del X, V, G, S
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline(res):
+    """The oracle as it stands on the host cores, on a bounded sample of the
+    same workload: whole periods (tau local steps + averaging) until about 10 s
+    have passed."""
+    import oracle
+    w = res["workload"]
+    if w is None:
+        return None
+    cores = min(w.m, len(os.sched_getaffinity(0)))
+    threads = oracle.set_threads(cores)
+    md = oracle.make_model(oracle.KIND_MLP, w.dims, B=w.B, N=w.N, E=w.E, lr=w.lr, beta=w.beta, wd=w.wd, bf16=w.bf16)
+    ref = oracle.Run(w.m, md, w.seed, w.x1, w.data, w.labels)
+    tau = max(1, min(res["tau0"], 5))
+    t0 = time.perf_counter()
+    steps = 0
+    while True:
+        ref.local_steps(tau)
+        ref.average()
+        steps += tau
+        el = time.perf_counter() - t0
+        if el > 10.0 or steps >= 2000:
+            break
+    oracle.set_threads(1)
+    return {"value": round(w.m * steps / el, 2), "unit": "replica-steps/s", "cores": threads, "kind": "oracle",
+            "sample": f"{steps} iterations of all {w.m} replicas in periods of {tau} local steps + averaging "
+                      f"({el:.1f} s), OpenMP over replicas"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (no collectives, no sharding); --gpus {args.gpus} is not "
+              f"supported. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU path", file=sys.stderr)
+        sys.exit(2)
+    import paper_1810_08313_amd as pkg
+    import synth
+    pkg.lib()
+    torch.cuda.set_device(0)
+
+    if args.workload in FLAT:
+        res = bench_flat(args, pkg, args.workload)
+    else:
+        res = bench_mlp(args, pkg, synth)
+
+    line = {
+        "metric": "replica-steps/sec (all m replicas); averaging HBM GB/s as fraction of peak",
+        "value": round(res["value"], 2),
+        "unit": "replica-steps/s",
+        "n_gpus": 1,
+        "steps": res["K"],
+        "warmup": res["W"],
+        "ms_per_step": round(res["sec"] / res["K"] * 1e3, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": res["dtype"],
+        "data": "synthetic",
+        "config": res["config"],
+        "roofline": res["roofline"],
+    }
+    if not args.no_extra and args.workload not in FLAT:
+        # the second half of the metric: averaging kernel at the stress sizes
+        extra = {}
+        for name, (m, P) in FLAT.items():
+            r = flat_measure(pkg, m, P, DEFAULT_STEPS[name], DEFAULT_WARMUP[name])
+            extra[name] = {"m": m, "P": P, "average_GBps": round(r["avg_gbs"], 1),
+                           "average_frac_of_peak": round(r["avg_gbs"] / HBM_PEAK_GBS, 4),
+                           "average_us": round(r["avg_us"], 1),
+                           "update_GBps": round(r["upd_gbs"], 1),
+                           "fused_update_average_GBps": round(r["fused_gbs"], 1)}
+        line["averaging"] = extra
+    line["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(res)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
