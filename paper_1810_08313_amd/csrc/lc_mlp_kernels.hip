@@ -413,85 +413,147 @@ struct BwdArgs {
     void* dzp_fm;        // dZ_{l-1} feature-major[G][dp_in][Bp]
     float lr, beta, wd;
     int vec;
-    int n_row_blocks;    // blocks per group (64 rows each)
+    int n_row_blocks;    // row blocks per group (64 rows each)
+    int col_split;       // workgroups sharing one row block's columns (1 when dA is needed)
     int64_t total_blocks;
 };
 
-// One wavefront owns 16 rows of W_l (and of V_l) and walks along them 64 columns
-// at a time.  Per trip it (1) loads the W and V tiles into the accumulator
-// layout, (2) forms the dW tile with MFMA over the batch, (3) parks the *old* W
-// tile in LDS, re-reads it in operand layout and accumulates its contribution
-// to dA_{l-1} (which therefore uses the weights of before the update, as the
-// chain rule requires), (4) applies v <- beta v + dW + wd w, w <- w - lr v and
-// stores both tiles.  W and V cross HBM exactly once in each direction.
+// One workgroup (4 wavefronts) owns 64 rows of W_l and V_l of one replica, 16
+// rows per wavefront, and walks along them 64 columns per trip.  Per trip
+//   (0) the 64-column slice of dZ_l is staged once per workgroup in LDS, in
+//       both layouts, from loads that were issued one trip ahead;
+//   (1) each wavefront holds its W and V tiles (also loaded one trip ahead,
+//       float4 per lane, straight into the MFMA accumulator layout);
+//   (2) the dW tile is formed with MFMA over the batch;
+//   (3) the *old* W tile is parked in LDS, re-read in operand layout and its
+//       contribution to dA_{l-1} accumulated (the chain rule needs the weights
+//       of before the update);
+//   (4) v <- beta v + dW + wd w, w <- w - lr v, both tiles stored.
+// W and V cross HBM exactly once in each direction; the gradient never exists
+// in memory; dA is complete when the wavefront has walked its rows, so nothing
+// is reduced across workgroups.  When dA is not needed (first layer) the
+// columns may additionally be split over several workgroups.
 template <typename OT, int NT>
 __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
     constexpr int kPad = sizeof(OT) == 2 ? 8 : 4;
+    constexpr int Bp = 16 * NT;
+    constexpr int NS = NT / 2;                 // 32-wide steps over the batch; also staging pieces per thread
+    // dZ^T slice: row (c % 4) * 16 + c / 4 holds column c0 + c, so that the 16 lanes
+    // of a B-operand read (columns 4 j + t) hit 16 consecutive LDS rows
+    __shared__ __attribute__((aligned(16))) OT dzt_lds[kColChunk][Bp + kPad];
+    __shared__ __attribute__((aligned(16))) OT dz_lds[Bp][kColChunk + kPad];
     __shared__ __attribute__((aligned(16))) OT wlds[4][kRowsPerWave][kColChunk + kPad];
+
     const int64_t logical = xcd_logical_block(a.total_blocks);
     if (logical < 0) return;
-    const int g = static_cast<int>(logical / a.n_row_blocks);
-    const int rb = static_cast<int>(logical % a.n_row_blocks);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int per_group = a.n_row_blocks * a.col_split;
+    const int g = static_cast<int>(logical / per_group);
+    const int rem = static_cast<int>(logical % per_group);
+    const int rb = rem / a.col_split, cs = rem % a.col_split;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 15, q = lane >> 4;
-    const int k0 = (rb * 4 + wave) * kRowsPerWave;
+    const int k0 = (rb * 4 + wave) * kRowsPerWave;   // < dp_in: the grid covers dp_in / 64 row blocks exactly
     const bool vec = a.vec != 0;
     const bool need_da = a.dzp_bm != nullptr;
 
     float* W = a.X + g * a.x_stride + a.w_off;
     float* Vw = a.V + g * a.x_stride + a.w_off;
-    const OT* AT = static_cast<const OT*>(a.a_fm) + static_cast<int64_t>(g) * a.dp_in * a.Bp;
-    const OT* dZ = static_cast<const OT*>(a.dz_bm) + static_cast<int64_t>(g) * a.Bp * a.dp_out;
-    const OT* dZT = static_cast<const OT*>(a.dz_fm) + static_cast<int64_t>(g) * a.dp_out * a.Bp;
+    const OT* AT = static_cast<const OT*>(a.a_fm) + static_cast<int64_t>(g) * a.dp_in * Bp;
+    const OT* dZ = static_cast<const OT*>(a.dz_bm) + static_cast<int64_t>(g) * Bp * a.dp_out;
+    const OT* dZT = static_cast<const OT*>(a.dz_fm) + static_cast<int64_t>(g) * a.dp_out * Bp;
 
-    // bias: db_l = sum_b dZ_l, then the same update (first block of the replica)
-    if (rb == 0) {
+    // bias: db_l = sum_b dZ_l, then the same update (first workgroup of the replica)
+    if (rb == 0 && cs == 0) {
         float* bx = a.X + g * a.x_stride + a.b_off;
         float* bv = a.V + g * a.x_stride + a.b_off;
-        for (int c = threadIdx.x; c < a.d_out; c += 256) {
+        for (int c = tid; c < a.d_out; c += 256) {
             float s = 0.f;
-            for (int b = 0; b < a.B; ++b) s += to_f32(dZT[static_cast<int64_t>(c) * a.Bp + b]);
+            for (int b = 0; b < a.B; ++b) s += to_f32(dZT[static_cast<int64_t>(c) * Bp + b]);
             const float x = bx[c];
             const float v = a.beta * bv[c] + (s + a.wd * x);
             bv[c] = v;
             bx[c] = x - a.lr * v;
         }
     }
-    if (k0 >= a.dp_in) return;  // whole wavefront beyond the padded rows
+
+    // column chunks of this workgroup
+    const int n_cc = (a.d_out + kColChunk - 1) / kColChunk;
+    const int cc_per = (n_cc + a.col_split - 1) / a.col_split;
+    const int cc_lo = cs * cc_per;
+    const int cc_hi = cc_lo + cc_per < n_cc ? cc_lo + cc_per : n_cc;
+    if (cc_lo >= cc_hi) return;   // uniform over the workgroup
 
     f32x4 dacc[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) dacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // this lane's A operand for the dW product: row k0 + j of A_{l-1}^T
-    const OT* at_row = AT + static_cast<int64_t>(k0 + j) * a.Bp + 8 * q;
+    // this lane's A operands for the dW product: row k0 + j of A_{l-1}^T, all batch steps
+    Frag<OT> af[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) af[s] = load8(AT + static_cast<int64_t>(k0 + j) * Bp + 32 * s + 8 * q);
 
-    const int n_cc = a.dp_out / kColChunk;
-    for (int cc = 0; cc < n_cc; ++cc) {
+    float4 w[4], v[4], wn[4], vn[4];
+    Frag<OT> st_t[NS], st_b[NS];   // staging registers for the dZ^T and dZ slices
+
+    auto issue_loads = [&](int cc, float4 (&ww)[4], float4 (&vv)[4]) {
         const int c0 = cc * kColChunk;
-        if (c0 >= a.d_out) break;
-        float4 w[4], v[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int row = k0 + 4 * q + r;
             if (row < a.d_in) {
-                w[r] = load_w4(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec);
-                v[r] = load_w4(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec);
+                ww[r] = load_w4(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec);
+                vv[r] = load_w4(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec);
             } else {
-                w[r] = v[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+                ww[r] = vv[r] = make_float4(0.f, 0.f, 0.f, 0.f);
             }
         }
+        // the dZ^T slice is one contiguous run of 64 * Bp elements
+        const OT* src_t = dZT + static_cast<int64_t>(c0) * Bp;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) st_t[s] = load8(src_t + static_cast<int64_t>(tid + 256 * s) * 8);
+        if (need_da) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const int p = tid + 256 * s;
+                st_b[s] = load8(dZ + static_cast<int64_t>(p >> 3) * a.dp_out + c0 + (p & 7) * 8);
+            }
+        }
+    };
+    auto stage_to_lds = [&]() {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const int p = tid + 256 * s;
+            const int c = p / (Bp / 8), seg = p % (Bp / 8);
+            *reinterpret_cast<Frag<OT>*>(&dzt_lds[(c & 3) * 16 + (c >> 2)][seg * 8]) = st_t[s];
+        }
+        if (need_da) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const int p = tid + 256 * s;
+                *reinterpret_cast<Frag<OT>*>(&dz_lds[p >> 3][(p & 7) * 8]) = st_b[s];
+            }
+        }
+    };
+
+    issue_loads(cc_lo, w, v);
+    stage_to_lds();
+    __syncthreads();
+
+    for (int cc = cc_lo; cc < cc_hi; ++cc) {
+        const int c0 = cc * kColChunk;
+        const bool has_next = cc + 1 < cc_hi;
+        if (has_next) issue_loads(cc + 1, wn, vn);
+
         // dW tile: sum over the batch of A^T[k][b] dZ^T[c][b]
         f32x4 acc[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < NT / 2; ++s) {
-            const Frag<OT> af = load8(at_row + 32 * s);
+        for (int s = 0; s < NS; ++s) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const Frag<OT> bf = load8(dZT + static_cast<int64_t>(c0 + 4 * j + t) * a.Bp + 32 * s + 8 * q);
-                acc[t] = mma8(af, bf, acc[t]);
+                const Frag<OT> bf = *reinterpret_cast<const Frag<OT>*>(&dzt_lds[t * 16 + j][32 * s + 8 * q]);
+                acc[t] = mma8(af[s], bf, acc[t]);
             }
         }
         if (need_da) {
@@ -503,7 +565,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int row = k0 + 4 * q + r;
-            float4 gr = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
+            const float4 gr = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
             v[r].x = a.beta * v[r].x + (gr.x + a.wd * w[r].x);
             v[r].y = a.beta * v[r].y + (gr.y + a.wd * w[r].y);
             v[r].z = a.beta * v[r].z + (gr.z + a.wd * w[r].z);
@@ -522,14 +584,23 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
             // dA^T[k][b] += sum_c W[k][c] dZ[b][c] over this chunk's 64 columns
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                const Frag<OT> wf = load8(&wlds[wave][j][32 * s + 8 * q]);
+                const Frag<OT> wf = *reinterpret_cast<const Frag<OT>*>(&wlds[wave][j][32 * s + 8 * q]);
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
-                    const Frag<OT> zf = load8(dZ + static_cast<int64_t>(16 * nt + j) * a.dp_out + c0 + 32 * s + 8 * q);
+                    const Frag<OT> zf = *reinterpret_cast<const Frag<OT>*>(&dz_lds[16 * nt + j][32 * s + 8 * q]);
                     dacc[nt] = mma8(wf, zf, dacc[nt]);
                 }
             }
-            wave_sync_lds();
+        }
+        if (has_next) {
+            __syncthreads();   // every wavefront is done with this chunk's LDS tiles
+            stage_to_lds();
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                w[r] = wn[r];
+                v[r] = vn[r];
+            }
         }
     }
 
@@ -537,8 +608,8 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         // dZ_{l-1} = dA .* [A_{l-1} > 0], both layouts.  Rows beyond d_in and batch
         // entries beyond B come out as exact zeros (zero operands), which is what
         // the padding must hold.
-        OT* pbm = static_cast<OT*>(a.dzp_bm) + static_cast<int64_t>(g) * a.Bp * a.dp_in;
-        OT* pfm = static_cast<OT*>(a.dzp_fm) + static_cast<int64_t>(g) * a.dp_in * a.Bp;
+        OT* pbm = static_cast<OT*>(a.dzp_bm) + static_cast<int64_t>(g) * Bp * a.dp_in;
+        OT* pfm = static_cast<OT*>(a.dzp_fm) + static_cast<int64_t>(g) * a.dp_in * Bp;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int b = 16 * nt + j;
@@ -546,9 +617,9 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int row = k0 + 4 * q + r;
-                const float act = to_f32(AT[static_cast<int64_t>(row) * a.Bp + b]);
+                const float act = to_f32(AT[static_cast<int64_t>(row) * Bp + b]);
                 d[r] = act > 0.f ? dacc[nt][r] : 0.f;
-                pfm[static_cast<int64_t>(row) * a.Bp + b] = static_cast<OT>(d[r]);
+                pfm[static_cast<int64_t>(row) * Bp + b] = static_cast<OT>(d[r]);
             }
             store4<OT>(pbm + static_cast<int64_t>(b) * a.dp_in + k0 + 4 * q, d[0], d[1], d[2], d[3]);
         }
@@ -695,7 +766,14 @@ hipError_t launch_backward(lc_handle* h, int l) {
     a.wd = h->md.wd;
     a.vec = (g.d_out % 4 == 0 && g.w_off % 4 == 0) ? 1 : 0;
     a.n_row_blocks = g.dp_in / 64;
-    a.total_blocks = static_cast<int64_t>(S.G) * a.n_row_blocks;
+    a.col_split = 1;
+    if (l == 1) {  // no dA: the columns can be shared out to fill the chip
+        const int n_cc = (g.d_out + kColChunk - 1) / kColChunk;
+        const int64_t base = static_cast<int64_t>(S.G) * a.n_row_blocks;
+        int want = static_cast<int>((1024 + base - 1) / base);
+        a.col_split = want < 1 ? 1 : (want > n_cc ? n_cc : want);
+    }
+    a.total_blocks = static_cast<int64_t>(S.G) * a.n_row_blocks * a.col_split;
     const unsigned grid = xcd_grid(a.total_blocks);
     timing_start(h, kTimeBwd);
     const hipError_t e = bf16 ? launch_bwd_nt<bf16_t>(a, S.Bp / 16, grid, h->stream)
