@@ -138,8 +138,8 @@ int one_local_step(lc_handle* h) {
         LC_HIP(h, launch_quad_step(h));
     } else {
         LC_HIP(h, launch_gather(h, false, h->k));
-        for (int l = 1; l <= h->L; ++l) LC_HIP(h, launch_forward(h, false, l));
-        LC_HIP(h, launch_softmax(h, false, 0));
+        for (int l = 1; l <= h->L; ++l) LC_HIP(h, launch_forward(h, false, l, 0));
+        if (!forward_fuses_softmax(h)) LC_HIP(h, launch_softmax(h, false, 0));
         // layer L first: dZ_{l-1} is produced from W_l before W_l is overwritten
         // inside the same kernel, and kernels run in stream order
         for (int l = h->L; l >= 1; --l) LC_HIP(h, launch_backward(h, l));
@@ -208,6 +208,8 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
         off = g.b_off + g.d_out;
     }
     h->attached = false;
+    // 256 MB: the size of the memory-side cache; below it weights are worth keeping cached
+    h->stream_weights = 8.0 * static_cast<double>(m) * static_cast<double>(h->Ps) > 256.0 * 1024 * 1024;
     h->X = h->V = nullptr;
     h->G = h->qa = h->qc = nullptr;
     h->data = nullptr;
@@ -315,8 +317,8 @@ int lc_loss(lc_handle* h, double* out) {
         hipError_t e = hipSuccess;
         for (int p = 0; p < passes && e == hipSuccess; ++p) {
             e = launch_gather(h, true, static_cast<int64_t>(p) * per_pass);
-            for (int l = 1; l <= h->L && e == hipSuccess; ++l) e = launch_forward(h, true, l);
-            if (e == hipSuccess) e = launch_softmax(h, true, p * h->eval.G);
+            for (int l = 1; l <= h->L && e == hipSuccess; ++l) e = launch_forward(h, true, l, p * h->eval.G);
+            if (e == hipSuccess && !forward_fuses_softmax(h)) e = launch_softmax(h, true, p * h->eval.G);
         }
         if (e == hipSuccess) e = hipMemcpyAsync(host, h->eval.loss, sizeof(float) * n, hipMemcpyDeviceToHost, h->stream);
         if (e == hipSuccess) e = hipStreamSynchronize(h->stream);

@@ -58,6 +58,7 @@ struct lc_handle {
     int L;
     lc::LayerGeom layer[LC_MAX_LAYERS + 1];  // index 1..L
     bool attached;
+    bool stream_weights;    // X and V together exceed the on-chip caches by far
     float *X, *V;
     const float* G;
     const float *qa, *qc;
@@ -87,7 +88,8 @@ hipError_t launch_quad_step(lc_handle* h);
 hipError_t launch_quad_loss(lc_handle* h, int* n_partial);
 
 hipError_t launch_gather(lc_handle* h, bool eval, int64_t k_or_base);
-hipError_t launch_forward(lc_handle* h, bool eval, int l);
+hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset);
+bool forward_fuses_softmax(const lc_handle* h);  // last layer's kernel also does a3
 hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset);
 hipError_t launch_backward(lc_handle* h, int l);
 

@@ -96,9 +96,16 @@ __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, float a, float b, floa
     *reinterpret_cast<bf16x4*>(p) = v;
 }
 
-// Four consecutive floats of a weight row, zero outside [0, d_out).
-__device__ __forceinline__ float4 load_w4(const float* row, int c, int d_out, bool vec) {
-    if (vec && c + 3 < d_out) return *reinterpret_cast<const float4*>(row + c);
+// Four consecutive floats of a weight row, zero outside [0, d_out).  When the
+// state of all replicas is far larger than the caches, each weight is touched
+// once per kernel and the loads and stores carry the non-temporal hint; small
+// models, whose weights stay cache-resident between kernels, use plain accesses.
+__device__ __forceinline__ float4 load_w4(const float* row, int c, int d_out, bool vec, bool stream) {
+    if (vec && c + 3 < d_out) {
+        if (!stream) return *reinterpret_cast<const float4*>(row + c);
+        const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(row + c));
+        return make_float4(t[0], t[1], t[2], t[3]);
+    }
     float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
     if (c < d_out) r.x = row[c];
     if (c + 1 < d_out) r.y = row[c + 1];
@@ -106,9 +113,10 @@ __device__ __forceinline__ float4 load_w4(const float* row, int c, int d_out, bo
     if (c + 3 < d_out) r.w = row[c + 3];
     return r;
 }
-__device__ __forceinline__ void store_w4(float* row, int c, int d_out, bool vec, float4 v) {
+__device__ __forceinline__ void store_w4(float* row, int c, int d_out, bool vec, bool stream, float4 v) {
     if (vec && c + 3 < d_out) {
-        *reinterpret_cast<float4*>(row + c) = v;
+        if (stream) __builtin_nontemporal_store(f32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<f32x4*>(row + c));
+        else *reinterpret_cast<float4*>(row + c) = v;
         return;
     }
     if (c < d_out) row[c] = v.x;
@@ -231,25 +239,39 @@ struct FwdArgs {
     void* out_fm;         // [G][dp_out][Bp] of OT or null
     int last;             // 1: no ReLU, fp32 output
     int vec;              // weight rows may be read with 16-byte loads
+    int stream;           // non-temporal weight loads
     int n_chunks;         // column chunks per group
+    int m_split;          // workgroups sharing one column chunk, each taking MT batch tiles
     int64_t total_blocks;
+    // last layer with all classes in one chunk: softmax cross-entropy in the epilogue
+    int fuse_softmax;
+    const int32_t* labels;  // [G][Bp], -1 = no sample
+    void* dz_bm;            // [G][Bp][dp_out] of OT or null (evaluation)
+    void* dz_fm;            // [G][dp_out][Bp] of OT or null
+    float* loss;            // [G]
+    int eval;               // 1: loss[g] = sum over valid samples; 0: mean over B
 };
 
-// One block = one replica x 64 output columns; its NW wavefronts split the
-// reduction over d_in and combine their partial tiles in LDS.
+// One block = one replica x 64 output columns x MT batch tiles of 16 rows; its
+// NW wavefronts split the reduction over d_in and combine their partial tiles
+// in LDS.  Large models use MT = all batch tiles (every weight is read from
+// memory once); small ones split the batch over several blocks to fill the chip.
 template <typename OT, int MT, int NW>
 __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
     __shared__ float red[MT * 16][kColChunk + 4];
     const int64_t logical = xcd_logical_block(a.total_blocks);
     if (logical < 0) return;
-    const int g = static_cast<int>(logical / a.n_chunks);
-    const int c0 = static_cast<int>(logical % a.n_chunks) * kColChunk;
+    const int per_group = a.n_chunks * a.m_split;
+    const int g = static_cast<int>(logical / per_group);
+    const int rem = static_cast<int>(logical % per_group);
+    const int c0 = (rem / a.m_split) * kColChunk;
+    const int row0 = (rem % a.m_split) * MT * 16;   // first batch row of this block
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 15, q = lane >> 4;
 
     const float* W = a.X + g * a.x_stride + a.w_off;
-    const OT* A = static_cast<const OT*>(a.a_in) + static_cast<int64_t>(g) * a.Bp * a.dp_in;
-    const bool vec = a.vec != 0;
+    const OT* A = static_cast<const OT*>(a.a_in) + (static_cast<int64_t>(g) * a.Bp + row0) * a.dp_in;
+    const bool vec = a.vec != 0, stream = a.stream != 0;
 
     f32x4 acc[MT][4];
 #pragma unroll
@@ -264,7 +286,7 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int row = k0 + e;
-            w[e] = row < a.d_in ? load_w4(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec)
+            w[e] = row < a.d_in ? load_w4(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, stream)
                                 : make_float4(0.f, 0.f, 0.f, 0.f);
         }
         Frag<OT> af[MT];
@@ -322,24 +344,66 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
     if (a.last) {
         float* out = static_cast<float*>(a.out_bm) + static_cast<int64_t>(g) * a.Bp * a.dp_out;
         for (int e = threadIdx.x; e < MT * 16 * kColChunk; e += nthr) {
-            const int b = e / kColChunk, c = c0 + e % kColChunk;
-            if (b < a.B && c < a.d_out) out[static_cast<int64_t>(b) * a.dp_out + c] = red[b][e % kColChunk] + bias[c];
+            const int bl = e / kColChunk, b = row0 + bl, c = c0 + e % kColChunk;
+            if (b < a.B && c < a.d_out) {
+                const float z = red[bl][e % kColChunk] + bias[c];
+                out[static_cast<int64_t>(b) * a.dp_out + c] = z;
+                red[bl][e % kColChunk] = z;
+            }
+        }
+        if (a.fuse_softmax) {
+            // all classes of a sample sit in this block's tile: loss and dZ_L here
+            __shared__ float lred[128];
+            __syncthreads();
+            const int b = threadIdx.x;
+            float nll = 0.f;
+            if (b < 128) {
+                if (b < a.B) {
+                    const int y = a.labels[static_cast<int64_t>(g) * a.Bp + b];
+                    if (y >= 0) {
+                        const float* z = red[b];
+                        float zmax = z[0];
+                        for (int c = 1; c < a.d_out; ++c) zmax = fmaxf(zmax, z[c]);
+                        float sum = 0.f;
+                        for (int c = 0; c < a.d_out; ++c) sum += expf(z[c] - zmax);
+                        nll = -(z[y] - zmax - logf(sum));
+                        if (a.dz_bm) {
+                            OT* dbm = static_cast<OT*>(a.dz_bm) + (static_cast<int64_t>(g) * a.Bp + b) * a.dp_out;
+                            OT* dfm = static_cast<OT*>(a.dz_fm) + static_cast<int64_t>(g) * a.dp_out * a.Bp + b;
+                            const float inv = 1.f / sum, invB = 1.f / static_cast<float>(a.B);
+                            for (int c = 0; c < a.d_out; ++c) {
+                                const float pr = expf(z[c] - zmax) * inv;
+                                const OT d = static_cast<OT>((pr - (c == y ? 1.f : 0.f)) * invB);
+                                dbm[c] = d;
+                                dfm[static_cast<int64_t>(c) * a.Bp] = d;
+                            }
+                        }
+                    }
+                }
+                lred[b] = nll;
+            }
+            __syncthreads();
+            for (int w = 64; w > 0; w >>= 1) {
+                if (b < w) lred[b] += lred[b + w];
+                __syncthreads();
+            }
+            if (b == 0) a.loss[g] = a.eval ? lred[0] : lred[0] / static_cast<float>(a.B);
         }
     } else {
         OT* obm = static_cast<OT*>(a.out_bm) + static_cast<int64_t>(g) * a.Bp * a.dp_out;
         for (int e = threadIdx.x; e < MT * 16 * kColChunk; e += nthr) {
-            const int b = e / kColChunk, c = c0 + e % kColChunk;
+            const int bl = e / kColChunk, b = row0 + bl, c = c0 + e % kColChunk;
             if (b < a.B && c < a.d_out) {
-                const float z = red[b][e % kColChunk] + bias[c];
+                const float z = red[bl][e % kColChunk] + bias[c];
                 obm[static_cast<int64_t>(b) * a.dp_out + c] = static_cast<OT>(z > 0.f ? z : 0.f);
             }
         }
         if (a.out_fm) {
             OT* ofm = static_cast<OT*>(a.out_fm) + static_cast<int64_t>(g) * a.dp_out * a.Bp;
             for (int e = threadIdx.x; e < MT * 16 * kColChunk; e += nthr) {
-                const int cl = e / (MT * 16), b = e % (MT * 16), c = c0 + cl;
+                const int cl = e / (MT * 16), bl = e % (MT * 16), b = row0 + bl, c = c0 + cl;
                 if (b < a.B && c < a.d_out) {
-                    const float z = red[b][cl] + bias[c];
+                    const float z = red[bl][cl] + bias[c];
                     ofm[static_cast<int64_t>(c) * a.Bp + b] = static_cast<OT>(z > 0.f ? z : 0.f);
                 }
             }
@@ -413,6 +477,7 @@ struct BwdArgs {
     void* dzp_fm;        // dZ_{l-1} feature-major[G][dp_in][Bp]
     float lr, beta, wd;
     int vec;
+    int stream;          // non-temporal weight loads and stores
     int n_row_blocks;    // row blocks per group (64 rows each)
     int col_split;       // workgroups sharing one row block's columns (1 when dA is needed)
     int64_t total_blocks;
@@ -453,7 +518,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 15, q = lane >> 4;
     const int k0 = (rb * 4 + wave) * kRowsPerWave;   // < dp_in: the grid covers dp_in / 64 row blocks exactly
-    const bool vec = a.vec != 0;
+    const bool vec = a.vec != 0, stream = a.stream != 0;
     const bool need_da = a.dzp_bm != nullptr;
 
     float* W = a.X + g * a.x_stride + a.w_off;
@@ -462,26 +527,23 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
     const OT* dZ = static_cast<const OT*>(a.dz_bm) + static_cast<int64_t>(g) * Bp * a.dp_out;
     const OT* dZT = static_cast<const OT*>(a.dz_fm) + static_cast<int64_t>(g) * a.dp_out * Bp;
 
-    // bias: db_l = sum_b dZ_l, then the same update (first workgroup of the replica)
-    if (rb == 0 && cs == 0) {
-        float* bx = a.X + g * a.x_stride + a.b_off;
-        float* bv = a.V + g * a.x_stride + a.b_off;
-        for (int c = tid; c < a.d_out; c += 256) {
-            float s = 0.f;
-            for (int b = 0; b < a.B; ++b) s += to_f32(dZT[static_cast<int64_t>(c) * Bp + b]);
-            const float x = bx[c];
-            const float v = a.beta * bv[c] + (s + a.wd * x);
-            bv[c] = v;
-            bx[c] = x - a.lr * v;
-        }
-    }
-
     // column chunks of this workgroup
     const int n_cc = (a.d_out + kColChunk - 1) / kColChunk;
     const int cc_per = (n_cc + a.col_split - 1) / a.col_split;
     const int cc_lo = cs * cc_per;
     const int cc_hi = cc_lo + cc_per < n_cc ? cc_lo + cc_per : n_cc;
     if (cc_lo >= cc_hi) return;   // uniform over the workgroup
+    // Workgroups advance through their columns at about the same pace; if all of
+    // them started at column 0 the rows they touch at any moment would differ by
+    // multiples of 16 * d_out * 4 bytes and pile onto the same memory channels.
+    // Each workgroup therefore starts its walk at a different chunk and wraps.
+    const int cc_n = cc_hi - cc_lo;
+    const int cc_shift = static_cast<int>((logical * 7) % cc_n);
+    auto chunk_at = [&](int i) {   // i-th chunk of this workgroup's walk
+        int c = i + cc_shift;
+        if (c >= cc_n) c -= cc_n;
+        return cc_lo + c;
+    };
 
     f32x4 dacc[NT];
 #pragma unroll
@@ -501,8 +563,8 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         for (int r = 0; r < 4; ++r) {
             const int row = k0 + 4 * q + r;
             if (row < a.d_in) {
-                ww[r] = load_w4(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec);
-                vv[r] = load_w4(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec);
+                ww[r] = load_w4(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, stream);
+                vv[r] = load_w4(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, stream);
             } else {
                 ww[r] = vv[r] = make_float4(0.f, 0.f, 0.f, 0.f);
             }
@@ -535,15 +597,28 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         }
     };
 
-    issue_loads(cc_lo, w, v);
+    issue_loads(chunk_at(0), w, v);
     stage_to_lds();
     __syncthreads();
 
-    for (int cc = cc_lo; cc < cc_hi; ++cc) {
-        const int c0 = cc * kColChunk;
-        const bool has_next = cc + 1 < cc_hi;
-        if (has_next) issue_loads(cc + 1, wn, vn);
+    for (int i = 0; i < cc_n; ++i) {
+        const int c0 = chunk_at(i) * kColChunk;
+        const bool has_next = i + 1 < cc_n;
+        if (has_next) issue_loads(chunk_at(i + 1), wn, vn);
 
+        // bias of these 64 columns: db_l = sum_b dZ_l from the staged slice, then the
+        // same update (first row block of the replica; one thread per column)
+        if (rb == 0 && tid < kColChunk && c0 + tid < a.d_out) {
+            const OT* zr = dzt_lds[(tid & 3) * 16 + (tid >> 2)];
+            float sb = 0.f;
+            for (int b = 0; b < a.B; ++b) sb += to_f32(zr[b]);
+            float* bx = a.X + g * a.x_stride + a.b_off + c0 + tid;
+            float* bv = a.V + g * a.x_stride + a.b_off + c0 + tid;
+            const float x = *bx;
+            const float vb = a.beta * *bv + (sb + a.wd * x);
+            *bv = vb;
+            *bx = x - a.lr * vb;
+        }
         // dW tile: sum over the batch of A^T[k][b] dZ^T[c][b]
         f32x4 acc[4];
 #pragma unroll
@@ -575,8 +650,8 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
             w[r].z -= a.lr * v[r].z;
             w[r].w -= a.lr * v[r].w;
             if (row < a.d_in) {
-                store_w4(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, v[r]);
-                store_w4(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, w[r]);
+                store_w4(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, stream, v[r]);
+                store_w4(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, stream, w[r]);
             }
         }
         if (need_da) {
@@ -631,6 +706,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
 template <typename OT, int NW>
 hipError_t launch_fwd_mt(const FwdArgs& a, int mt, unsigned grid, hipStream_t s) {
     switch (mt) {
+        case 1: hipLaunchKernelGGL((forward_kernel<OT, 1, NW>), dim3(grid), dim3(NW * 64), 0, s, a); break;
         case 2: hipLaunchKernelGGL((forward_kernel<OT, 2, NW>), dim3(grid), dim3(NW * 64), 0, s, a); break;
         case 4: hipLaunchKernelGGL((forward_kernel<OT, 4, NW>), dim3(grid), dim3(NW * 64), 0, s, a); break;
         case 8: hipLaunchKernelGGL((forward_kernel<OT, 8, NW>), dim3(grid), dim3(NW * 64), 0, s, a); break;
@@ -686,7 +762,7 @@ hipError_t launch_gather(lc_handle* h, bool eval, int64_t k_or_base) {
     return hipGetLastError();
 }
 
-hipError_t launch_forward(lc_handle* h, bool eval, int l) {
+hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     const ActSet& S = eval ? h->eval : h->train;
     const LayerGeom& g = h->layer[l];
     const bool bf16 = !eval && h->md.gemm == LC_GEMM_BF16;
@@ -706,10 +782,25 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l) {
     a.out_fm = S.a_fm[l];
     a.last = l == h->L ? 1 : 0;
     a.vec = (g.d_out % 4 == 0 && g.w_off % 4 == 0) ? 1 : 0;
+    a.stream = (!eval && h->stream_weights) ? 1 : 0;
     a.n_chunks = g.dp_out / kColChunk;
-    a.total_blocks = static_cast<int64_t>(S.G) * a.n_chunks;
+    // softmax cross-entropy rides in the epilogue when one block sees all classes of all samples
+    a.fuse_softmax = (a.last && g.d_out <= kColChunk) ? 1 : 0;
+    a.labels = S.labels;
+    a.dz_bm = eval ? nullptr : S.dz_bm[h->L];
+    a.dz_fm = eval ? nullptr : S.dz_fm[h->L];
+    a.loss = S.loss + loss_offset;
+    a.eval = eval ? 1 : 0;
+    // batch tiles per block: all of them, unless that leaves most of the chip idle
+    int mt = mt_for(S.Bp);
+    a.m_split = 1;
+    if (!a.fuse_softmax)
+        while (mt > 1 && static_cast<int64_t>(S.G) * a.n_chunks * a.m_split < 256) {
+            mt /= 2;
+            a.m_split *= 2;
+        }
+    a.total_blocks = static_cast<int64_t>(S.G) * a.n_chunks * a.m_split;
     const unsigned grid = xcd_grid(a.total_blocks);
-    const int mt = mt_for(S.Bp);
     // few blocks: split the reduction over more wavefronts per block
     const bool wide = a.total_blocks * 4 < 2048 && g.dp_in >= 512;
     if (!eval) timing_start(h, kTimeFwd);
@@ -719,6 +810,8 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l) {
     if (!eval) timing_stop(h, kTimeFwd);
     return e;
 }
+
+bool forward_fuses_softmax(const lc_handle* h) { return h->layer[h->L].d_out <= kColChunk; }
 
 hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset) {
     const ActSet& S = eval ? h->eval : h->train;
@@ -765,6 +858,7 @@ hipError_t launch_backward(lc_handle* h, int l) {
     a.beta = h->md.beta;
     a.wd = h->md.wd;
     a.vec = (g.d_out % 4 == 0 && g.w_off % 4 == 0) ? 1 : 0;
+    a.stream = h->stream_weights ? 1 : 0;
     a.n_row_blocks = g.dp_in / 64;
     a.col_split = 1;
     if (l == 1) {  // no dA: the columns can be shared out to fill the chip
