@@ -59,6 +59,8 @@ struct lc_handle {
     lc::LayerGeom layer[LC_MAX_LAYERS + 1];  // index 1..L
     bool attached;
     bool stream_weights;    // X and V together exceed the on-chip caches by far
+    bool avg_two_phase;        // averaging: two-kernel form for states larger than the caches
+    int64_t avg_chunk_floats;  // its column chunk (x_bar chunk stays cached between the kernels)
     float *X, *V;
     const float* G;
     const float *qa, *qc;

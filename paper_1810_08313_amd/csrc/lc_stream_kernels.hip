@@ -52,6 +52,57 @@ __global__ __launch_bounds__(kThreads) void average_kernel(const float* __restri
     if (out_single) *reinterpret_cast<float4*>(out_single + col) = mean;
 }
 
+// Two-kernel form of the averaging step for states larger than the caches.
+// Writing m row streams from one kernel while it is still reading them costs
+// this memory system about a fifth of its bandwidth; separating the phases does
+// not.  The columns are processed in chunks small enough for one row's chunk to
+// stay in the L2 / memory-side cache between the two kernels:
+//   reduce_chunk    reads the m rows of the chunk and writes the mean over row 0
+//                   (one stream out, and no bytes beyond the algorithmic ones)
+//   broadcast_chunk copies the cached row-0 chunk to rows 1..m-1, one row after
+//                   the other; consecutive blocks write consecutive addresses
+constexpr int kReduceCols = 8;   // float4 columns per thread in reduce_chunk
+
+__global__ __launch_bounds__(kThreads) void reduce_chunk_kernel(float* X, int m, int64_t Ps, int64_t c_lo,
+                                                                int64_t c_hi) {
+    const int64_t base = c_lo / 4 + static_cast<int64_t>(blockIdx.x) * kThreads * kReduceCols;
+    double s[kReduceCols][4];
+#pragma unroll
+    for (int u = 0; u < kReduceCols; ++u) s[u][0] = s[u][1] = s[u][2] = s[u][3] = 0.0;
+    for (int i = 0; i < m; ++i) {
+        float4 r[kReduceCols];
+#pragma unroll
+        for (int u = 0; u < kReduceCols; ++u) {
+            const int64_t c = (base + u * kThreads + threadIdx.x) * 4;
+            r[u] = c < c_hi ? ld_stream(X + static_cast<int64_t>(i) * Ps + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < kReduceCols; ++u) {
+            s[u][0] += static_cast<double>(r[u].x);
+            s[u][1] += static_cast<double>(r[u].y);
+            s[u][2] += static_cast<double>(r[u].z);
+            s[u][3] += static_cast<double>(r[u].w);
+        }
+    }
+    const double dm = static_cast<double>(m);
+#pragma unroll
+    for (int u = 0; u < kReduceCols; ++u) {
+        const int64_t c = (base + u * kThreads + threadIdx.x) * 4;
+        if (c < c_hi)
+            *reinterpret_cast<float4*>(X + c) =
+                make_float4(static_cast<float>(s[u][0] / dm), static_cast<float>(s[u][1] / dm),
+                            static_cast<float>(s[u][2] / dm), static_cast<float>(s[u][3] / dm));
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void broadcast_chunk_kernel(float* X, int64_t Ps, int64_t c_lo, int64_t c_hi,
+                                                                   int64_t blocks_per_row) {
+    const int64_t row = 1 + blockIdx.x / blocks_per_row, b = blockIdx.x % blocks_per_row;
+    const int64_t col = c_lo + (b * kThreads + threadIdx.x) * 4;
+    if (col >= c_hi) return;
+    st_stream(X + row * Ps + col, *reinterpret_cast<const float4*>(X + col));
+}
+
 __device__ __forceinline__ void sgd_update4(float4& x, float4& v, const float4& g, float lr, float beta, float wd) {
     v.x = beta * v.x + (g.x + wd * x.x);
     v.y = beta * v.y + (g.y + wd * x.y);
@@ -152,6 +203,25 @@ inline unsigned blocks_for(int64_t threads) { return static_cast<unsigned>((thre
 }  // namespace
 
 hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* out_single) {
+    // in-place averaging of a state larger than the caches: chunked reduce into row 0,
+    // then row-by-row broadcast
+    const bool two_phase = out_rows == h->X && X == h->X && !out_single && h->m >= 2 && h->avg_two_phase &&
+                           static_cast<double>(h->m) * static_cast<double>(h->Ps) * 4.0 > 512.0 * 1024 * 1024;
+    if (two_phase) {
+        timing_start(h, kTimeAvg);
+        const int64_t chunk = h->avg_chunk_floats;
+        for (int64_t lo = 0; lo < h->Ps; lo += chunk) {
+            const int64_t hi = lo + chunk < h->Ps ? lo + chunk : h->Ps;
+            const int64_t nblk = ((hi - lo) / 4 + kThreads - 1) / kThreads;
+            const int64_t nred = (nblk + kReduceCols - 1) / kReduceCols;
+            hipLaunchKernelGGL(reduce_chunk_kernel, dim3(static_cast<unsigned>(nred)), dim3(kThreads), 0, h->stream,
+                               h->X, h->m, h->Ps, lo, hi);
+            hipLaunchKernelGGL(broadcast_chunk_kernel, dim3(static_cast<unsigned>(nblk * (h->m - 1))), dim3(kThreads),
+                               0, h->stream, h->X, h->Ps, lo, hi, nblk);
+        }
+        timing_stop(h, kTimeAvg);
+        return hipGetLastError();
+    }
     if (out_rows) timing_start(h, kTimeAvg);
     hipLaunchKernelGGL(average_kernel, dim3(blocks_for(h->Ps / 4)), dim3(kThreads), 0, h->stream, X, out_rows,
                        out_single, h->m, h->Ps);
