@@ -138,11 +138,17 @@ int one_local_step(lc_handle* h) {
         LC_HIP(h, launch_quad_step(h));
     } else {
         LC_HIP(h, launch_gather(h, false, h->k));
-        for (int l = 1; l <= h->L; ++l) LC_HIP(h, launch_forward(h, false, l, 0));
-        if (!forward_fuses_softmax(h)) LC_HIP(h, launch_softmax(h, false, 0));
-        // layer L first: dZ_{l-1} is produced from W_l before W_l is overwritten
-        // inside the same kernel, and kernels run in stream order
-        for (int l = h->L; l >= 1; --l) LC_HIP(h, launch_backward(h, l));
+        // layer L first in the backward sweep: dZ_{l-1} is produced from W_l before W_l
+        // is overwritten inside the same kernel, and kernels run in stream order
+        if (head_is_fused(h)) {
+            for (int l = 1; l < h->L; ++l) LC_HIP(h, launch_forward(h, false, l, 0));
+            LC_HIP(h, launch_head(h));
+            for (int l = h->L - 1; l >= 1; --l) LC_HIP(h, launch_backward(h, l));
+        } else {
+            for (int l = 1; l <= h->L; ++l) LC_HIP(h, launch_forward(h, false, l, 0));
+            LC_HIP(h, launch_softmax(h, false, 0));
+            for (int l = h->L; l >= 1; --l) LC_HIP(h, launch_backward(h, l));
+        }
     }
     h->k += 1;
     return LC_OK;

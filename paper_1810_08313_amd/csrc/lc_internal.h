@@ -94,6 +94,8 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset);
 bool forward_fuses_softmax(const lc_handle* h);  // last layer's kernel also does a3
 hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset);
 hipError_t launch_backward(lc_handle* h, int l);
+bool head_is_fused(const lc_handle* h);   // last layer: forward + softmax + backward in one kernel
+hipError_t launch_head(lc_handle* h);
 
 // timing helpers used by the launchers
 void timing_start(lc_handle* h, int which);

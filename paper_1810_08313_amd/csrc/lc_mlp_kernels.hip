@@ -701,6 +701,257 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
     }
 }
 
+// ----------------------------------------------------------------------- head
+//
+// Last layer with all classes inside one 64-column tile (d_L <= 64): forward,
+// softmax cross-entropy and the layer's whole backward pass (dW_L, db_L, update,
+// dZ_{L-1}) in ONE kernel, one workgroup of 8 wavefronts per replica.  The deltas
+// dZ_L never leave LDS.  For very small layers this replaces three launches whose
+// cost is dominated by dependent memory round trips, not by work.
+
+struct HeadArgs {
+    float* X;
+    float* V;
+    int64_t x_stride;
+    int64_t w_off, b_off;
+    int d_in, d_out, dp_in, dp_out;
+    int B;
+    const void* a_bm;        // A_{L-1} batch-major   [G][Bp][dp_in]
+    const void* a_fm;        // A_{L-1} feature-major [G][dp_in][Bp]
+    const int32_t* labels;   // [G][Bp]
+    float* logits;           // [G][Bp][dp_out] fp32
+    void* dzp_bm;            // dZ_{L-1} batch-major  or null (single-layer model)
+    void* dzp_fm;
+    float* loss;             // [G]
+    float lr, beta, wd;
+    int vec, stream;
+};
+
+template <typename OT, int NT>
+__global__ __launch_bounds__(512) void head_kernel(HeadArgs a) {
+    constexpr int kPad = sizeof(OT) == 2 ? 8 : 4;
+    constexpr int Bp = 16 * NT, NS = NT / 2, NW = 8;
+    __shared__ float red[Bp][kColChunk + 4];
+    __shared__ __attribute__((aligned(16))) OT dzt_lds[kColChunk][Bp + kPad];
+    __shared__ __attribute__((aligned(16))) OT dz_lds[Bp][kColChunk + kPad];
+    __shared__ __attribute__((aligned(16))) OT wlds[NW][kRowsPerWave][kColChunk + kPad];
+    __shared__ float lred[128];
+
+    const int g = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 15, q = lane >> 4;
+    const bool vec = a.vec != 0, stream = a.stream != 0;
+    const bool need_da = a.dzp_bm != nullptr;
+    float* W = a.X + g * a.x_stride + a.w_off;
+    float* Vw = a.V + g * a.x_stride + a.w_off;
+    const OT* A = static_cast<const OT*>(a.a_bm) + static_cast<int64_t>(g) * Bp * a.dp_in;
+    const OT* AT = static_cast<const OT*>(a.a_fm) + static_cast<int64_t>(g) * a.dp_in * Bp;
+
+    // ---- phase 1: logits = A_{L-1} W_L + b_L (reduction over d_in split over the wavefronts)
+    {
+        f32x4 acc[NT][4];
+#pragma unroll
+        for (int mt = 0; mt < NT; ++mt)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const int n_steps = a.dp_in / 32;
+        for (int s = wave; s < n_steps; s += NW) {
+            const int k0 = s * 32 + 8 * q;
+            float4 w[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int row = k0 + e;
+                w[e] = row < a.d_in ? load_w4(W + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream)
+                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            Frag<OT> af[NT];
+#pragma unroll
+            for (int mt = 0; mt < NT; ++mt) af[mt] = load8(A + static_cast<int64_t>(16 * mt + j) * a.dp_in + k0);
+            Frag<OT> bf;
+            float x[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = w[e].x;
+            pack8(bf, x);
+#pragma unroll
+            for (int mt = 0; mt < NT; ++mt) acc[mt][0] = mma8(af[mt], bf, acc[mt][0]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = w[e].y;
+            pack8(bf, x);
+#pragma unroll
+            for (int mt = 0; mt < NT; ++mt) acc[mt][1] = mma8(af[mt], bf, acc[mt][1]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = w[e].z;
+            pack8(bf, x);
+#pragma unroll
+            for (int mt = 0; mt < NT; ++mt) acc[mt][2] = mma8(af[mt], bf, acc[mt][2]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = w[e].w;
+            pack8(bf, x);
+#pragma unroll
+            for (int mt = 0; mt < NT; ++mt) acc[mt][3] = mma8(af[mt], bf, acc[mt][3]);
+        }
+        for (int w = 0; w < NW; ++w) {
+            if (wave == w) {
+#pragma unroll
+                for (int mt = 0; mt < NT; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float4* p = reinterpret_cast<float4*>(&red[16 * mt + 4 * q + r][4 * j]);
+                        float4 v = make_float4(acc[mt][0][r], acc[mt][1][r], acc[mt][2][r], acc[mt][3][r]);
+                        if (w > 0) {
+                            const float4 o = *p;
+                            v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                        }
+                        *p = v;
+                    }
+            }
+            __syncthreads();
+        }
+    }
+    // bias; logits to memory; clear the delta tiles (entries beyond B and d_out must be zero)
+    {
+        const float* bias = a.X + g * a.x_stride + a.b_off;
+        float* out = a.logits + static_cast<int64_t>(g) * Bp * a.dp_out;
+        for (int e = tid; e < Bp * kColChunk; e += NW * 64) {
+            const int b = e / kColChunk, c = e % kColChunk;
+            if (b < a.B && c < a.d_out) {
+                const float z = red[b][c] + bias[c];
+                out[static_cast<int64_t>(b) * a.dp_out + c] = z;
+                red[b][c] = z;
+            }
+        }
+        for (int e = tid; e < kColChunk * (Bp + kPad); e += NW * 64) (&dzt_lds[0][0])[e] = static_cast<OT>(0.f);
+        for (int e = tid; e < Bp * (kColChunk + kPad); e += NW * 64) (&dz_lds[0][0])[e] = static_cast<OT>(0.f);
+    }
+    __syncthreads();
+
+    // ---- phase 2: softmax cross-entropy; dZ_L = (p - onehot) / B goes to the LDS tiles
+    {
+        const int b = tid;
+        float nll = 0.f;
+        if (b < 128) {
+            if (b < a.B) {
+                const int y = a.labels[static_cast<int64_t>(g) * Bp + b];
+                if (y >= 0) {
+                    const float* z = red[b];
+                    float zmax = z[0];
+                    for (int c = 1; c < a.d_out; ++c) zmax = fmaxf(zmax, z[c]);
+                    float sum = 0.f;
+                    for (int c = 0; c < a.d_out; ++c) sum += expf(z[c] - zmax);
+                    nll = -(z[y] - zmax - logf(sum));
+                    const float inv = 1.f / sum, invB = 1.f / static_cast<float>(a.B);
+                    for (int c = 0; c < a.d_out; ++c) {
+                        const float pr = expf(z[c] - zmax) * inv;
+                        const OT d = static_cast<OT>((pr - (c == y ? 1.f : 0.f)) * invB);
+                        dz_lds[b][c] = d;
+                        dzt_lds[(c & 3) * 16 + (c >> 2)][b] = d;
+                    }
+                }
+            }
+            lred[b] = nll;
+        }
+        __syncthreads();
+        for (int w = 64; w > 0; w >>= 1) {
+            if (b < w) lred[b] += lred[b + w];
+            __syncthreads();
+        }
+        if (b == 0) a.loss[g] = lred[0] / static_cast<float>(a.B);
+    }
+
+    // ---- phase 3: backward of the layer.  Bias first (one thread per class) ...
+    if (tid < a.d_out) {
+        const OT* zr = dzt_lds[(tid & 3) * 16 + (tid >> 2)];
+        float sb = 0.f;
+        for (int b = 0; b < a.B; ++b) sb += to_f32(zr[b]);
+        float* bx = a.X + g * a.x_stride + a.b_off + tid;
+        float* bv = a.V + g * a.x_stride + a.b_off + tid;
+        const float x = *bx;
+        const float vb = a.beta * *bv + (sb + a.wd * x);
+        *bv = vb;
+        *bx = x - a.lr * vb;
+    }
+    // ... then the weight rows, 16 per wavefront and trip
+    OT* pbm = need_da ? static_cast<OT*>(a.dzp_bm) + static_cast<int64_t>(g) * Bp * a.dp_in : nullptr;
+    OT* pfm = need_da ? static_cast<OT*>(a.dzp_fm) + static_cast<int64_t>(g) * a.dp_in * Bp : nullptr;
+    const int n_rg = a.dp_in / kRowsPerWave;
+    for (int rg = wave; rg < n_rg; rg += NW) {
+        const int k0 = rg * kRowsPerWave;
+        float4 w[4], v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = k0 + 4 * q + r;
+            if (row < a.d_in) {
+                w[r] = load_w4(W + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream);
+                v[r] = load_w4(Vw + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream);
+            } else {
+                w[r] = v[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+        f32x4 acc[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const Frag<OT> af = load8(AT + static_cast<int64_t>(k0 + j) * Bp + 32 * s + 8 * q);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const Frag<OT> bf = *reinterpret_cast<const Frag<OT>*>(&dzt_lds[t * 16 + j][32 * s + 8 * q]);
+                acc[t] = mma8(af, bf, acc[t]);
+            }
+        }
+        if (need_da) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) store4<OT>(&wlds[wave][4 * q + r][4 * j], w[r].x, w[r].y, w[r].z, w[r].w);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = k0 + 4 * q + r;
+            const float4 gr = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
+            v[r].x = a.beta * v[r].x + (gr.x + a.wd * w[r].x);
+            v[r].y = a.beta * v[r].y + (gr.y + a.wd * w[r].y);
+            v[r].z = a.beta * v[r].z + (gr.z + a.wd * w[r].z);
+            v[r].w = a.beta * v[r].w + (gr.w + a.wd * w[r].w);
+            w[r].x -= a.lr * v[r].x;
+            w[r].y -= a.lr * v[r].y;
+            w[r].z -= a.lr * v[r].z;
+            w[r].w -= a.lr * v[r].w;
+            if (row < a.d_in) {
+                store_w4(Vw + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream, v[r]);
+                store_w4(W + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream, w[r]);
+            }
+        }
+        if (need_da) {
+            wave_sync_lds();
+            f32x4 dacc[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) dacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const Frag<OT> wf = *reinterpret_cast<const Frag<OT>*>(&wlds[wave][j][32 * s + 8 * q]);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const Frag<OT> zf = *reinterpret_cast<const Frag<OT>*>(&dz_lds[16 * nt + j][32 * s + 8 * q]);
+                    dacc[nt] = mma8(wf, zf, dacc[nt]);
+                }
+            }
+            wave_sync_lds();
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int b = 16 * nt + j;
+                float d[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = k0 + 4 * q + r;
+                    const float act = to_f32(AT[static_cast<int64_t>(row) * Bp + b]);
+                    d[r] = act > 0.f ? dacc[nt][r] : 0.f;
+                    pfm[static_cast<int64_t>(row) * Bp + b] = static_cast<OT>(d[r]);
+                }
+                store4<OT>(pbm + static_cast<int64_t>(b) * a.dp_in + k0 + 4 * q, d[0], d[1], d[2], d[3]);
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------ dispatch
 
 template <typename OT, int NW>
@@ -812,6 +1063,56 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
 }
 
 bool forward_fuses_softmax(const lc_handle* h) { return h->layer[h->L].d_out <= kColChunk; }
+
+// One workgroup per replica is only faster than three spread-out launches while the
+// layer is tiny (measured: wins at 64 input rows, loses from 256 on).
+bool head_is_fused(const lc_handle* h) {
+    return h->layer[h->L].d_out <= kColChunk && h->layer[h->L].dp_in <= 128;
+}
+
+hipError_t launch_head(lc_handle* h) {
+    const ActSet& S = h->train;
+    const int L = h->L;
+    const LayerGeom& g = h->layer[L];
+    const bool bf16 = h->md.gemm == LC_GEMM_BF16;
+    HeadArgs a;
+    a.X = h->X;
+    a.V = h->V;
+    a.x_stride = h->Ps;
+    a.w_off = g.w_off;
+    a.b_off = g.b_off;
+    a.d_in = g.d_in;
+    a.d_out = g.d_out;
+    a.dp_in = g.dp_in;
+    a.dp_out = g.dp_out;
+    a.B = S.B;
+    a.a_bm = S.a_bm[L - 1];
+    a.a_fm = S.a_fm[L - 1];
+    a.labels = S.labels;
+    a.logits = static_cast<float*>(S.a_bm[L]);
+    a.dzp_bm = L > 1 ? S.dz_bm[L - 1] : nullptr;
+    a.dzp_fm = L > 1 ? S.dz_fm[L - 1] : nullptr;
+    a.loss = S.loss;
+    a.lr = h->md.lr;
+    a.beta = h->md.beta;
+    a.wd = h->md.wd;
+    a.vec = (g.d_out % 4 == 0 && g.w_off % 4 == 0) ? 1 : 0;
+    a.stream = 0;   // the last layer is small: keep it cached
+    const dim3 grid(S.G), block(512);
+    timing_start(h, kTimeBwd);
+    const int nt = S.Bp / 16;
+    if (bf16) {
+        if (nt == 2) hipLaunchKernelGGL((head_kernel<bf16_t, 2>), grid, block, 0, h->stream, a);
+        else if (nt == 4) hipLaunchKernelGGL((head_kernel<bf16_t, 4>), grid, block, 0, h->stream, a);
+        else hipLaunchKernelGGL((head_kernel<bf16_t, 8>), grid, block, 0, h->stream, a);
+    } else {
+        if (nt == 2) hipLaunchKernelGGL((head_kernel<float, 2>), grid, block, 0, h->stream, a);
+        else if (nt == 4) hipLaunchKernelGGL((head_kernel<float, 4>), grid, block, 0, h->stream, a);
+        else hipLaunchKernelGGL((head_kernel<float, 8>), grid, block, 0, h->stream, a);
+    }
+    timing_stop(h, kTimeBwd);
+    return hipGetLastError();
+}
 
 hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset) {
     const ActSet& S = eval ? h->eval : h->train;
