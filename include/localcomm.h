@@ -143,6 +143,18 @@ int lc_loss(lc_handle* h, double* out);
  * tau0 < 1, or a result that does not fit an int. */
 int adacomm_next_tau(double F0, double Fl, int tau0);
 
+/* AdaComm with the refinements of Sec. 4.3.  Candidate
+ *   c = ceil( sqrt( (lr0 / lrl) * Fl / F0 ) * tau0 )      (Sec. 4.3.2, practical coupling; lr0 = lrl
+ *                                                           gives the basic rule)
+ * "Faster decay when training saturates" (Sec. 4.3.1): c is taken only if c + slack < tau_prev,
+ * otherwise the period becomes ceil(gamma * tau_prev), 0 < gamma <= 1 (the paper uses 1/2).  At the
+ * first decision after a learning-rate change (lr_changed != 0) c is taken as it is: the coupling
+ * exists to let the period grow there.  Evaluated in IEEE double in this order: Fl/F0, lr0/lrl,
+ * their product, sqrt, times tau0, ceil; gamma * tau_prev, ceil.  Returns the period >= 1 or
+ * LC_ERR_ARG. */
+int adacomm_next_tau_ex(double F0, double Fl, int tau0, int tau_prev, double gamma, int slack,
+                        double lr0, double lrl, int lr_changed);
+
 /* Whole schedule on the host side of the library: K iterations as periods of
  * tau local steps each followed by lc_average(), the last period truncated.
  * adaptive != 0: F_0 = lc_loss() at entry; at the first averaging step at or
@@ -156,6 +168,18 @@ int adacomm_next_tau(double F0, double Fl, int tau0);
  * Synchronises before returning. */
 int lc_run(lc_handle* h, int64_t K, int tau0, int adaptive, int64_t interval,
            int64_t* sched_k, int32_t* sched_tau, int cap, int32_t* n_sched, int64_t* rounds);
+
+/* lc_run() with the refinements.  refine != 0 decides with adacomm_next_tau_ex (lr0 = the rate
+ * in force at entry).  The learning-rate schedule is n_lr pairs: from iteration lr_at[j] on
+ * (counted from 0 at lc_init, increasing) the rate is lr_val[j].  Changes take effect at
+ * averaging steps only; with postpone_lr != 0 a due change waits until the period has reached 1
+ * ("first gradually decay the communication period to 1 and then decay the learning rate",
+ * Sec. 4.3.2).  sched_lr (host, capacity cap) receives the rate in force after each decision.
+ * F_0 is always evaluated, so interval >= 1 is required. */
+int lc_run_ex(lc_handle* h, int64_t K, int tau0, int64_t interval, int refine, double gamma, int slack,
+              int n_lr, const int64_t* lr_at, const float* lr_val, int postpone_lr,
+              int64_t* sched_k, int32_t* sched_tau, float* sched_lr, int cap, int32_t* n_sched,
+              int64_t* rounds);
 
 /* One (momentum-)SGD update of every worker from explicit gradients G (device,
  * fp32 [m, lc_row_stride(P)], 256-byte aligned): g <- G + wd x; v <- beta v + g;

@@ -90,6 +90,12 @@ def lib() -> C.CDLL:
     L.orc_run.restype = C.c_int
     L.orc_run.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int64, lp, C.POINTER(C.c_int),
                           C.c_int, C.POINTER(C.c_int), lp]
+    L.orc_next_tau_ex.restype = C.c_int
+    L.orc_next_tau_ex.argtypes = [C.c_double, C.c_double, C.c_int, C.c_int, C.c_double, C.c_int, C.c_double,
+                                  C.c_double, C.c_int]
+    L.orc_run_ex.restype = C.c_int
+    L.orc_run_ex.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int64, C.c_int, C.c_double, C.c_int, C.c_int, lp, fp,
+                             C.c_int, lp, C.POINTER(C.c_int), fp, C.c_int, C.POINTER(C.c_int), lp]
     _lib = L
     return L
 
@@ -131,6 +137,12 @@ def bf16_round(a) -> np.ndarray:
 
 def next_tau(F0: float, Fl: float, tau0: int) -> int:
     return int(lib().orc_next_tau(float(F0), float(Fl), int(tau0)))
+
+
+def next_tau_ex(F0: float, Fl: float, tau0: int, tau_prev: int, gamma: float = 0.5, slack: int = 0,
+                lr0: float = 1.0, lrl: float = 1.0, lr_changed: bool = False) -> int:
+    return int(lib().orc_next_tau_ex(float(F0), float(Fl), int(tau0), int(tau_prev), float(gamma), int(slack),
+                                     float(lr0), float(lrl), int(bool(lr_changed))))
 
 
 def mlp_loss_grad(md: OrcModel, x: np.ndarray, data: np.ndarray, labels: np.ndarray,
@@ -254,3 +266,20 @@ class Run:
             raise RuntimeError(f"orc_run failed: {rc}")
         n = min(ns.value, cap)
         return [(int(sk[j]), int(st[j])) for j in range(n)], int(rounds.value)
+
+    def run_ex(self, K: int, tau0: int, interval: int, refine: bool = True, gamma: float = 0.5, slack: int = 0,
+               lr_schedule: Sequence[Tuple[int, float]] = (), postpone_lr: bool = True, cap: int = 4096):
+        """Driver with the AdaComm refinements; returns ([(k, tau, lr)], rounds)."""
+        n = len(lr_schedule)
+        at = (C.c_int64 * max(n, 1))(*[int(a) for a, _ in lr_schedule])
+        val = (C.c_float * max(n, 1))(*[float(v) for _, v in lr_schedule])
+        sk = (C.c_int64 * cap)()
+        st = (C.c_int * cap)()
+        sl = (C.c_float * cap)()
+        ns, rounds = C.c_int(0), C.c_int64(0)
+        rc = lib().orc_run_ex(self._h, int(K), int(tau0), int(interval), int(bool(refine)), float(gamma), int(slack),
+                              n, at, val, int(bool(postpone_lr)), sk, st, sl, cap, C.byref(ns), C.byref(rounds))
+        if rc != 0:
+            raise RuntimeError(f"orc_run_ex failed: {rc}")
+        m = min(ns.value, cap)
+        return [(int(sk[j]), int(st[j]), float(sl[j])) for j in range(m)], int(rounds.value)

@@ -274,6 +274,27 @@ int orc_next_tau(double F0, double Fl, int tau0) {
     return t < 1 ? 1 : t;
 }
 
+int orc_next_tau_ex(double F0, double Fl, int tau0, int tau_prev, double gamma, int slack,
+                    double lr0, double lrl, int lr_changed) {
+    if (!(F0 > 0.0) || !(Fl >= 0.0) || !isfinite(F0) || !isfinite(Fl) || tau0 < 1 || tau_prev < 1) return -1;
+    if (!(gamma > 0.0) || !(gamma <= 1.0) || slack < 0) return -1;
+    if (!(lr0 > 0.0) || !(lrl > 0.0) || !isfinite(lr0) || !isfinite(lrl)) return -1;
+    const double ratio = Fl / F0;
+    const double coupling = lr0 / lrl;
+    const double scaled = coupling * ratio;
+    const double root = sqrt(scaled);
+    const double prod = root * (double)tau0;
+    const double up = ceil(prod);
+    if (!(up < 2147483647.0)) return -2;
+    int cand = (int)up;
+    if (cand < 1) cand = 1;
+    if (lr_changed) return cand;
+    if ((int64_t)cand + (int64_t)slack < (int64_t)tau_prev) return cand;
+    const double shrunk = ceil(gamma * (double)tau_prev);
+    const int t = (int)shrunk;
+    return t < 1 ? 1 : t;
+}
+
 /* ------------------------------------------------------------------ a run -- */
 
 orc_state* orc_create(int m, const orc_model* md, uint64_t seed, const float* x1,
@@ -457,6 +478,45 @@ int orc_run(orc_state* s, int64_t K, int tau0, int adaptive, int64_t interval,
             if (nt < 0) { *n_sched = ns; *rounds = r; return nt; }
             tau = nt;
             if (ns < cap) { sched_k[ns] = s->k; sched_tau[ns] = tau; }
+            ++ns;
+            while (next_eval <= s->k) next_eval += interval;
+        }
+    }
+    *n_sched = ns;
+    *rounds = r;
+    return 0;
+}
+
+int orc_run_ex(orc_state* s, int64_t K, int tau0, int64_t interval, int refine, double gamma, int slack,
+               int n_lr, const int64_t* lr_at, const float* lr_val, int postpone_lr,
+               int64_t* sched_k, int* sched_tau, float* sched_lr, int cap, int* n_sched, int64_t* rounds) {
+    int tau = tau0, ns = 0, next_lr = 0, lr_changed = 0;
+    int64_t r = 0, next_eval = s->k + interval;
+    const double lr0 = (double)s->md.lr;
+    const double F0 = orc_loss(s);
+    if (ns < cap) { sched_k[ns] = s->k; sched_tau[ns] = tau; sched_lr[ns] = s->md.lr; }
+    ++ns;
+    const int64_t k_end = s->k + K;
+    while (s->k < k_end) {
+        const int64_t left = k_end - s->k;
+        const int t = (int64_t)tau < left ? tau : (int)left;
+        orc_local_steps(s, t);
+        orc_average(s);
+        ++r;
+        /* scheduled learning-rate changes, applied at synchronisation points */
+        while (next_lr < n_lr && s->k >= lr_at[next_lr] && (!postpone_lr || tau == 1)) {
+            s->md.lr = lr_val[next_lr];
+            ++next_lr;
+            lr_changed = 1;
+        }
+        if (s->k >= next_eval && s->k < k_end) {
+            const double Fl = orc_loss(s);
+            const int nt = refine ? orc_next_tau_ex(F0, Fl, tau0, tau, gamma, slack, lr0, (double)s->md.lr, lr_changed)
+                                  : orc_next_tau(F0, Fl, tau0);
+            if (nt < 0) { *n_sched = ns; *rounds = r; return nt; }
+            tau = nt;
+            lr_changed = 0;
+            if (ns < cap) { sched_k[ns] = s->k; sched_tau[ns] = tau; sched_lr[ns] = s->md.lr; }
             ++ns;
             while (next_eval <= s->k) next_eval += interval;
         }

@@ -84,6 +84,15 @@ void orc_sgd_update(int64_t P, float* x, float* v, const float* g, float lr, flo
  * Negative on invalid input (F0 <= 0, Fl < 0, non-finite, tau0 < 1). */
 int orc_next_tau(double F0, double Fl, int tau0);
 
+/* AdaComm refinements (Sec. 4.3): candidate c = ceil( sqrt( (lr0/lrl) * Fl/F0 ) * tau0 ), the
+ * practical learning-rate coupling of Sec. 4.3.2 (lr0 = lrl gives the basic rule).  "Faster
+ * decay when training saturates" (Sec. 4.3.1): c is taken only if c + slack < tau_prev,
+ * otherwise the period becomes ceil(gamma * tau_prev).  At the first decision after a
+ * learning-rate change (lr_changed != 0) c is taken as it is, since the coupling exists to let
+ * the period grow there.  Result at least 1; negative on invalid input. */
+int orc_next_tau_ex(double F0, double Fl, int tau0, int tau_prev, double gamma, int slack,
+                    double lr0, double lrl, int lr_changed);
+
 /* --- a run ------------------------------------------------------------------ */
 
 /* m workers all starting at x1[P].  data [N,d_0] fp32, labels [N]; for QUAD
@@ -121,6 +130,15 @@ double orc_loss(orc_state* s);
  * number of averaging steps.  Returns 0, or a negative orc_next_tau error. */
 int orc_run(orc_state* s, int64_t K, int tau0, int adaptive, int64_t interval,
             int64_t* sched_k, int* sched_tau, int cap, int* n_sched, int64_t* rounds);
+
+/* Driver with the refinements.  The learning-rate schedule is n_lr pairs (lr_at[j], lr_val[j]):
+ * from iteration lr_at[j] on the rate should be lr_val[j].  Changes take effect at averaging
+ * steps only; with postpone_lr != 0 a due change waits until tau has reached 1 (Sec. 4.3.2,
+ * last paragraph).  refine = 0 uses orc_next_tau with the coupling factor ignored.
+ * sched_lr receives the learning rate in force after each decision. */
+int orc_run_ex(orc_state* s, int64_t K, int tau0, int64_t interval, int refine, double gamma, int slack,
+               int n_lr, const int64_t* lr_at, const float* lr_val, int postpone_lr,
+               int64_t* sched_k, int* sched_tau, float* sched_lr, int cap, int* n_sched, int64_t* rounds);
 
 #ifdef __cplusplus
 }

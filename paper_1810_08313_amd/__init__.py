@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     LcModel,
     LocalSGD,
     adacomm_next_tau,
+    adacomm_next_tau_ex,
     lc_param_count,
     lc_row_stride,
     lib,

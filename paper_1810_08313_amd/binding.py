@@ -86,6 +86,14 @@ def lib() -> C.CDLL:
     L.lc_run.restype = C.c_int
     L.lc_run.argtypes = [vp, C.c_int64, C.c_int, C.c_int, C.c_int64, C.POINTER(C.c_int64),
                          C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int64)]
+    L.adacomm_next_tau_ex.restype = C.c_int
+    L.adacomm_next_tau_ex.argtypes = [C.c_double, C.c_double, C.c_int, C.c_int, C.c_double, C.c_int, C.c_double,
+                                      C.c_double, C.c_int]
+    L.lc_run_ex.restype = C.c_int
+    L.lc_run_ex.argtypes = [vp, C.c_int64, C.c_int, C.c_int64, C.c_int, C.c_double, C.c_int, C.c_int,
+                            C.POINTER(C.c_int64), C.POINTER(C.c_float), C.c_int, C.POINTER(C.c_int64),
+                            C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int, C.POINTER(C.c_int32),
+                            C.POINTER(C.c_int64)]
     L.lc_set_grad.restype = C.c_int
     L.lc_set_grad.argtypes = [vp, vp]
     L.lc_update_from_grad.restype = C.c_int
@@ -140,6 +148,16 @@ def adacomm_next_tau(F0: float, Fl: float, tau0: int) -> int:
     t = int(lib().adacomm_next_tau(float(F0), float(Fl), int(tau0)))
     if t < 0:
         raise LcError(t, "adacomm_next_tau")
+    return t
+
+
+def adacomm_next_tau_ex(F0: float, Fl: float, tau0: int, tau_prev: int, gamma: float = 0.5, slack: int = 0,
+                        lr0: float = 1.0, lrl: float = 1.0, lr_changed: bool = False) -> int:
+    """AdaComm with the saturation and learning-rate refinements; raises LcError on invalid input."""
+    t = int(lib().adacomm_next_tau_ex(float(F0), float(Fl), int(tau0), int(tau_prev), float(gamma), int(slack),
+                                      float(lr0), float(lrl), int(bool(lr_changed))))
+    if t < 0:
+        raise LcError(t, "adacomm_next_tau_ex")
     return t
 
 
@@ -240,6 +258,21 @@ class LocalSGD:
                                    C.byref(ns), C.byref(rounds)), "lc_run")
         n = min(ns.value, cap)
         return [(int(sk[j]), int(st[j])) for j in range(n)], int(rounds.value)
+
+    def run_ex(self, K: int, tau0: int, interval: int, refine: bool = True, gamma: float = 0.5, slack: int = 0,
+               lr_schedule: Sequence[Tuple[int, float]] = (), postpone_lr: bool = True, cap: int = 4096):
+        n = len(lr_schedule)
+        at = (C.c_int64 * max(n, 1))(*[int(a) for a, _ in lr_schedule])
+        val = (C.c_float * max(n, 1))(*[float(v) for _, v in lr_schedule])
+        sk = (C.c_int64 * cap)()
+        st = (C.c_int32 * cap)()
+        sl = (C.c_float * cap)()
+        ns, rounds = C.c_int32(0), C.c_int64(0)
+        self._check(self._L.lc_run_ex(self._h, int(K), int(tau0), int(interval), int(bool(refine)), float(gamma),
+                                      int(slack), n, at, val, int(bool(postpone_lr)), sk, st, sl, cap, C.byref(ns),
+                                      C.byref(rounds)), "lc_run_ex")
+        m = min(ns.value, cap)
+        return [(int(sk[j]), int(st[j]), float(sl[j])) for j in range(m)], int(rounds.value)
 
     def set_grad(self, G) -> None:
         """G: numpy [m, P] (copied, padded) or a torch device tensor [m, Ps]."""

@@ -361,6 +361,91 @@ int adacomm_next_tau(double F0, double Fl, int tau0) {
     return t < 1 ? 1 : t;
 }
 
+int adacomm_next_tau_ex(double F0, double Fl, int tau0, int tau_prev, double gamma, int slack, double lr0,
+                        double lrl, int lr_changed) {
+    if (!(F0 > 0.0) || !(Fl >= 0.0) || !isfinite(F0) || !isfinite(Fl) || tau0 < 1 || tau_prev < 1) return LC_ERR_ARG;
+    if (!(gamma > 0.0) || !(gamma <= 1.0) || slack < 0) return LC_ERR_ARG;
+    if (!(lr0 > 0.0) || !(lrl > 0.0) || !isfinite(lr0) || !isfinite(lrl)) return LC_ERR_ARG;
+    volatile double ratio = Fl / F0;
+    volatile double coupling = lr0 / lrl;
+    volatile double scaled = coupling * ratio;
+    volatile double root = sqrt(scaled);
+    volatile double prod = root * static_cast<double>(tau0);
+    const double up = ceil(prod);
+    if (!(up < 2147483647.0)) return LC_ERR_ARG;
+    int cand = static_cast<int>(up);
+    if (cand < 1) cand = 1;
+    if (lr_changed) return cand;
+    if (static_cast<int64_t>(cand) + slack < static_cast<int64_t>(tau_prev)) return cand;
+    volatile double shrunk = gamma * static_cast<double>(tau_prev);
+    const int t = static_cast<int>(ceil(shrunk));
+    return t < 1 ? 1 : t;
+}
+
+int lc_run_ex(lc_handle* h, int64_t K, int tau0, int64_t interval, int refine, double gamma, int slack, int n_lr,
+              const int64_t* lr_at, const float* lr_val, int postpone_lr, int64_t* sched_k, int32_t* sched_tau,
+              float* sched_lr, int cap, int32_t* n_sched, int64_t* rounds) {
+    const int rc = require_attached(h);
+    if (rc != LC_OK) return rc;
+    if (K < 0 || tau0 < 1 || interval < 1 || cap < 0 || n_lr < 0 || !n_sched || !rounds) return LC_ERR_ARG;
+    if (cap > 0 && (!sched_k || !sched_tau || !sched_lr)) return LC_ERR_ARG;
+    if (n_lr > 0 && (!lr_at || !lr_val)) return LC_ERR_ARG;
+    for (int j = 0; j < n_lr; ++j)
+        if (!(lr_val[j] > 0.f) || (j > 0 && lr_at[j] < lr_at[j - 1])) return LC_ERR_ARG;
+    int tau = tau0, ns = 0, next_lr = 0, lr_changed = 0;
+    int64_t r = 0, next_eval = h->k + interval;
+    const double lr0 = static_cast<double>(h->md.lr);
+    double F0 = 0.0;
+    *n_sched = 0;
+    *rounds = 0;
+    int e = lc_loss(h, &F0);
+    if (e != LC_OK) return e;
+    if (ns < cap) {
+        sched_k[ns] = h->k;
+        sched_tau[ns] = tau;
+        sched_lr[ns] = h->md.lr;
+    }
+    ++ns;
+    const int64_t k_end = h->k + K;
+    while (h->k < k_end) {
+        const int64_t left = k_end - h->k;
+        const int t = static_cast<int64_t>(tau) < left ? tau : static_cast<int>(left);
+        e = lc_local_steps(h, t);
+        if (e == LC_OK) e = lc_average(h);
+        if (e != LC_OK) return e;
+        ++r;
+        while (next_lr < n_lr && h->k >= lr_at[next_lr] && (!postpone_lr || tau == 1)) {
+            h->md.lr = lr_val[next_lr];
+            ++next_lr;
+            lr_changed = 1;
+        }
+        if (h->k >= next_eval && h->k < k_end) {
+            double Fl = 0.0;
+            e = lc_loss(h, &Fl);
+            if (e != LC_OK) return e;
+            const int nt = refine ? adacomm_next_tau_ex(F0, Fl, tau0, tau, gamma, slack, lr0,
+                                                        static_cast<double>(h->md.lr), lr_changed)
+                                  : adacomm_next_tau(F0, Fl, tau0);
+            if (nt < 0) return nt;
+            tau = nt;
+            lr_changed = 0;
+            if (ns < cap) {
+                sched_k[ns] = h->k;
+                sched_tau[ns] = tau;
+                sched_lr[ns] = h->md.lr;
+            }
+            ++ns;
+            while (next_eval <= h->k) next_eval += interval;
+        }
+        *n_sched = ns;
+        *rounds = r;
+    }
+    *n_sched = ns;
+    *rounds = r;
+    LC_HIP(h, hipStreamSynchronize(h->stream));
+    return LC_OK;
+}
+
 int lc_run(lc_handle* h, int64_t K, int tau0, int adaptive, int64_t interval, int64_t* sched_k,
            int32_t* sched_tau, int cap, int32_t* n_sched, int64_t* rounds) {
     const int rc = require_attached(h);

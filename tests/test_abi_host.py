@@ -95,6 +95,27 @@ def test_controller_bit_exact_against_oracle(pkg, orc):
         pkg.adacomm_next_tau(0.0, 1.0, 5)
 
 
+def test_refined_controller_bit_exact_against_oracle(pkg, orc):
+    g = np.random.default_rng(5)
+    L = pkg.lib()
+    n = 0
+    for _ in range(20000):
+        F0, Fl = float(g.uniform(1e-3, 5.0)), float(g.uniform(0.0, 6.0))
+        tau0, tau_prev = int(g.integers(1, 100)), int(g.integers(1, 120))
+        gamma = float(g.choice([0.5, 0.25, 0.75, 1.0]))
+        slack = int(g.integers(0, 3))
+        lr0, lrl = float(g.choice([0.4, 0.2, 0.1])), float(g.choice([0.4, 0.04, 0.004, 0.1]))
+        ch = int(g.integers(0, 2))
+        a = L.adacomm_next_tau_ex(F0, Fl, tau0, tau_prev, gamma, slack, lr0, lrl, ch)
+        assert a == orc.next_tau_ex(F0, Fl, tau0, tau_prev, gamma, slack, lr0, lrl, bool(ch)) and a >= 1
+        n += 1
+    for bad in [(0.0, 1.0, 5, 5, 0.5, 0, 1.0, 1.0, 0), (1.0, 1.0, 5, 0, 0.5, 0, 1.0, 1.0, 0),
+                (1.0, 1.0, 5, 5, 0.0, 0, 1.0, 1.0, 0), (1.0, 1.0, 5, 5, 0.5, -1, 1.0, 1.0, 0),
+                (1.0, 1.0, 5, 5, 0.5, 0, 0.0, 1.0, 0), (1.0, 1.0, 5, 5, 0.5, 0, 1.0, float("nan"), 0)]:
+        assert L.adacomm_next_tau_ex(*bad) < 0 and orc.next_tau_ex(*bad[:8], bool(bad[8])) < 0
+    assert pkg.adacomm_next_tau_ex(2.0, 2.0, 20, 20) == 10
+
+
 def test_no_cpu_fallback_without_gpu(pkg):
     import torch
     if torch.cuda.is_available():

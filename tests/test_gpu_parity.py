@@ -368,6 +368,38 @@ def test_quadratic_closed_form_and_schedule(pkg, orc):
     run.close()
 
 
+def test_refined_schedule_bit_exact(pkg, orc):
+    """AdaComm with saturation decay, learning-rate coupling and postponed rate
+    change: same (iteration, tau, lr) decisions as the oracle, on the quadratic
+    (exactly predictable losses) and on a small MLP."""
+    _say("refined schedule")
+    m, P = 4, 333
+    a, c, x0 = synth.quad_problem(8, m, P, common_a=True)
+    c = (c * 0.05).astype(np.float32)
+    kw = dict(lr=0.02)
+    ref = orc.Run(m, orc.make_model(orc.KIND_QUAD, [P], **kw), 0, x0, qa=a, qc=c)
+    run = pkg.LocalSGD(m, pkg.make_model(pkg.KIND_QUAD, [P], **kw), 0, x0, qa=a, qc=c)
+    args = dict(refine=True, gamma=0.5, slack=0, lr_schedule=[(70, 0.005)], postpone_lr=True)
+    s_ref, r_ref = ref.run_ex(260, 12, 20, **args)
+    s_gpu, r_gpu = run.run_ex(260, 12, 20, **args)
+    assert s_gpu == s_ref and r_gpu == r_ref and len(s_ref) > 6
+    assert any(lr == pytest.approx(0.005) for _, _, lr in s_ref)
+    X, V, k = run.get_state()
+    assert k == ref.k == 260
+    assert np.abs(X - ref.X).max() < 1e-4 * np.abs(ref.X).max()
+    run.close()
+
+    dims = [64, 32, 10]
+    ref, run = _problem(pkg, orc, dims, 4, 32, N=2000, lr=0.05, beta=0.0, E=1024, mean_sd=2.0)
+    args = dict(refine=True, gamma=0.5, slack=1, lr_schedule=[(60, 0.0125)], postpone_lr=False)
+    s_ref, r_ref = ref.run_ex(140, 8, 24, **args)
+    s_gpu, r_gpu = run.run_ex(140, 8, 24, **args)
+    assert s_gpu == s_ref and r_gpu == r_ref
+    X, V, k = run.get_state()
+    _assert_close(X, ref.X, dims, 1e-3, "X after refined run")
+    run.close()
+
+
 # --------------------------------------------------------------- error paths
 
 def test_attach_errors_and_bad_tau(pkg):
