@@ -181,6 +181,22 @@ int lc_run_ex(lc_handle* h, int64_t K, int tau0, int64_t interval, int refine, d
               int64_t* sched_k, int32_t* sched_tau, float* sched_lr, int cap, int32_t* n_sched,
               int64_t* rounds);
 
+/* Block momentum (Sec. 5.3.1): treat the local updates of one period as one big step between two
+ * synchronised models and give that step a global momentum.  lc_block_momentum_begin() records
+ * the current model of worker 0 as x_sync (call it when the workers are synchronised: right after
+ * lc_set_state with equal rows, or after lc_average), sets the global buffer u = 0 and clears the
+ * local buffers.  While the mode is on, lc_average() (also inside lc_run / lc_run_ex) computes
+ *     G = (x_sync - x_bar) / lr ;  u <- beta_glob u + G ;  x_sync <- x_sync - lr u
+ * writes x_sync to every row and clears every worker's local momentum buffer ("we restart
+ * momentum SGD on local models after every averaging step"; the paper uses beta_glob = 0.3 with
+ * local momentum 0.9).  G is read as the averaged model change per unit learning rate, which for
+ * plain local SGD is the paper's accumulated mean gradient.  u and x_sync live in the scratch
+ * buffer.  lc_block_momentum_end() returns to plain averaging.  lc_get_block_momentum() copies
+ * u and x_sync to host arrays of P floats (either may be NULL); it synchronises. */
+int lc_block_momentum_begin(lc_handle* h, float beta_glob);
+int lc_block_momentum_end(lc_handle* h);
+int lc_get_block_momentum(lc_handle* h, float* u_host, float* x_sync_host);
+
 /* One (momentum-)SGD update of every worker from explicit gradients G (device,
  * fp32 [m, lc_row_stride(P)], 256-byte aligned): g <- G + wd x; v <- beta v + g;
  * x <- x - lr v (mini-batch SGD update of Sec. 2).  The iteration counter is

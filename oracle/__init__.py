@@ -90,6 +90,12 @@ def lib() -> C.CDLL:
     L.orc_run.restype = C.c_int
     L.orc_run.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int64, lp, C.POINTER(C.c_int),
                           C.c_int, C.POINTER(C.c_int), lp]
+    L.orc_block_begin.restype = None
+    L.orc_block_begin.argtypes = [C.c_void_p, C.c_float]
+    L.orc_block_end.restype = None
+    L.orc_block_end.argtypes = [C.c_void_p]
+    L.orc_block_u.restype = fp
+    L.orc_block_u.argtypes = [C.c_void_p]
     L.orc_next_tau_ex.restype = C.c_int
     L.orc_next_tau_ex.argtypes = [C.c_double, C.c_double, C.c_int, C.c_int, C.c_double, C.c_int, C.c_double,
                                   C.c_double, C.c_int]
@@ -255,6 +261,16 @@ class Run:
 
     def loss(self) -> float:
         return float(lib().orc_loss(self._h))
+
+    def block_begin(self, beta_glob: float) -> None:
+        lib().orc_block_begin(self._h, float(beta_glob))
+
+    def block_end(self) -> None:
+        lib().orc_block_end(self._h)
+
+    @property
+    def block_u(self) -> np.ndarray:
+        return np.ctypeslib.as_array(lib().orc_block_u(self._h), shape=(self.P,)).copy()
 
     def run(self, K: int, tau0: int, adaptive: bool = False, interval: int = 0, cap: int = 4096):
         sk = (C.c_int64 * cap)()

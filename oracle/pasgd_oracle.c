@@ -22,6 +22,9 @@ struct orc_state {
     const float* data;
     const int32_t* labels;
     const float *qa, *qc;      /* QUAD constants [m,P] */
+    int block;                 /* block momentum active */
+    float beta_glob;
+    float *u, *xs;             /* global buffer and last synchronised model [P] */
 };
 
 static int g_threads = 1;
@@ -319,6 +322,8 @@ orc_state* orc_create(int m, const orc_model* md, uint64_t seed, const float* x1
 
 void orc_destroy(orc_state* s) {
     if (!s) return;
+    free(s->u);
+    free(s->xs);
     free(s->X);
     free(s->V);
     free(s->last_loss);
@@ -402,9 +407,32 @@ static void mean_model(const orc_state* s, float* xbar) {
     }
 }
 
+void orc_block_begin(orc_state* s, float beta_glob) {
+    if (!s->u) s->u = (float*)malloc(sizeof(float) * (size_t)s->P);
+    if (!s->xs) s->xs = (float*)malloc(sizeof(float) * (size_t)s->P);
+    memset(s->u, 0, sizeof(float) * (size_t)s->P);
+    memcpy(s->xs, s->X, sizeof(float) * (size_t)s->P);
+    memset(s->V, 0, sizeof(float) * (size_t)s->m * s->P);
+    s->beta_glob = beta_glob;
+    s->block = 1;
+}
+
+void orc_block_end(orc_state* s) { s->block = 0; }
+const float* orc_block_u(const orc_state* s) { return s->block ? s->u : NULL; }
+
 void orc_average(orc_state* s) {
     float* xbar = (float*)malloc(sizeof(float) * (size_t)s->P);
     mean_model(s, xbar);
+    if (s->block) {
+        const double lr = (double)s->md.lr, bg = (double)s->beta_glob;
+        for (int64_t j = 0; j < s->P; ++j) {
+            const double G = ((double)s->xs[j] - (double)xbar[j]) / lr;
+            s->u[j] = (float)(bg * (double)s->u[j] + G);
+            s->xs[j] = (float)((double)s->xs[j] - lr * (double)s->u[j]);
+            xbar[j] = s->xs[j];
+        }
+        memset(s->V, 0, sizeof(float) * (size_t)s->m * s->P);
+    }
     for (int i = 0; i < s->m; ++i) memcpy(s->X + (int64_t)i * s->P, xbar, sizeof(float) * (size_t)s->P);
     free(xbar);
 }

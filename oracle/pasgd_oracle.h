@@ -119,6 +119,17 @@ void orc_local_steps_subset(orc_state* s, int tau, const int* ids, int n);
 void orc_update_from_grad(orc_state* s, const float* G);
 /* Replace every worker's model by the mean of all models; buffers untouched. */
 void orc_average(orc_state* s);
+/* Block momentum (Sec. 5.3.1).  orc_block_begin() records the current (synchronised) model of
+ * worker 0 as x_sync, sets the global buffer u = 0 and clears the local buffers; from then on
+ * orc_average() is the block-momentum step
+ *     G = (x_sync - x_bar) / lr        the accumulated step of the period, in gradient units
+ *     u <- beta_glob u + G ;  x_sync <- x_sync - lr u ;  every worker <- x_sync
+ * and clears every worker's local momentum buffer (momentum SGD restarts after each averaging
+ * step).  orc_block_end() returns to plain averaging. */
+void orc_block_begin(orc_state* s, float beta_glob);
+void orc_block_end(orc_state* s);
+const float* orc_block_u(const orc_state* s);   /* [P] or NULL */
+
 /* Training loss of the averaged model on the first E samples, fp32 operands. */
 double orc_loss(orc_state* s);
 

@@ -94,6 +94,12 @@ def lib() -> C.CDLL:
                             C.POINTER(C.c_int64), C.POINTER(C.c_float), C.c_int, C.POINTER(C.c_int64),
                             C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int, C.POINTER(C.c_int32),
                             C.POINTER(C.c_int64)]
+    L.lc_block_momentum_begin.restype = C.c_int
+    L.lc_block_momentum_begin.argtypes = [vp, C.c_float]
+    L.lc_block_momentum_end.restype = C.c_int
+    L.lc_block_momentum_end.argtypes = [vp]
+    L.lc_get_block_momentum.restype = C.c_int
+    L.lc_get_block_momentum.argtypes = [vp, vp, vp]
     L.lc_set_grad.restype = C.c_int
     L.lc_set_grad.argtypes = [vp, vp]
     L.lc_update_from_grad.restype = C.c_int
@@ -273,6 +279,17 @@ class LocalSGD:
                                       C.byref(rounds)), "lc_run_ex")
         m = min(ns.value, cap)
         return [(int(sk[j]), int(st[j]), float(sl[j])) for j in range(m)], int(rounds.value)
+
+    def block_momentum_begin(self, beta_glob: float) -> None:
+        self._check(self._L.lc_block_momentum_begin(self._h, float(beta_glob)), "lc_block_momentum_begin")
+
+    def block_momentum_end(self) -> None:
+        self._check(self._L.lc_block_momentum_end(self._h), "lc_block_momentum_end")
+
+    def get_block_momentum(self) -> Tuple[np.ndarray, np.ndarray]:
+        u, xs = np.empty(self.P, np.float32), np.empty(self.P, np.float32)
+        self._check(self._L.lc_get_block_momentum(self._h, u.ctypes.data, xs.ctypes.data), "lc_get_block_momentum")
+        return u, xs
 
     def set_grad(self, G) -> None:
         """G: numpy [m, P] (copied, padded) or a torch device tensor [m, Ps]."""

@@ -80,6 +80,8 @@ struct Carver {
 size_t carve(lc_handle* h, char* base) {
     Carver c{base, 0};
     h->xbar = static_cast<float*>(c.take(sizeof(float) * static_cast<size_t>(h->Ps)));
+    h->bm_u = static_cast<float*>(c.take(sizeof(float) * static_cast<size_t>(h->Ps)));
+    h->bm_xs = static_cast<float*>(c.take(sizeof(float) * static_cast<size_t>(h->Ps)));
     if (h->md.kind == LC_KIND_QUAD) {
         h->n_partial = static_cast<int>((h->P + 255) / 256);
         h->partial = static_cast<double*>(c.take(sizeof(double) * static_cast<size_t>(h->n_partial)));
@@ -151,6 +153,7 @@ int one_local_step(lc_handle* h) {
         }
     }
     h->k += 1;
+    h->v_cleared = false;   // the step just queued wrote V = g
     return LC_OK;
 }
 
@@ -235,6 +238,9 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     h->last_hip = 0;
     h->timing_which = kTimeNone;
     h->ev_used = 0;
+    h->bm_on = false;
+    h->bm_beta = 0.f;
+    h->v_cleared = false;
     (void)carve(h, nullptr);
     *out = h;
     return LC_OK;
@@ -298,6 +304,37 @@ int lc_average(lc_handle* h) {
     const int rc = require_attached(h);
     if (rc != LC_OK) return rc;
     LC_HIP(h, launch_average(h, h->X, h->X, nullptr));
+    if (h->bm_on) h->v_cleared = true;   // local momentum restarts after every block-momentum step
+    return LC_OK;
+}
+
+int lc_block_momentum_begin(lc_handle* h, float beta_glob) {
+    const int rc = require_attached(h);
+    if (rc != LC_OK) return rc;
+    if (!(beta_glob >= 0.f) || !(beta_glob < 1.f) || !(h->md.lr > 0.f)) return LC_ERR_ARG;
+    const size_t bytes = sizeof(float) * static_cast<size_t>(h->Ps);
+    LC_HIP(h, hipMemsetAsync(h->bm_u, 0, bytes, h->stream));
+    LC_HIP(h, hipMemcpyAsync(h->bm_xs, h->X, bytes, hipMemcpyDeviceToDevice, h->stream));
+    h->bm_on = true;
+    h->bm_beta = beta_glob;
+    h->v_cleared = true;
+    return LC_OK;
+}
+
+int lc_block_momentum_end(lc_handle* h) {
+    if (!h) return LC_ERR_ARG;
+    h->bm_on = false;
+    return LC_OK;
+}
+
+int lc_get_block_momentum(lc_handle* h, float* u_host, float* x_sync_host) {
+    const int rc = require_attached(h);
+    if (rc != LC_OK) return rc;
+    if (!h->bm_on) return LC_ERR_STATE;
+    const size_t bytes = sizeof(float) * static_cast<size_t>(h->P);
+    if (u_host) LC_HIP(h, hipMemcpyAsync(u_host, h->bm_u, bytes, hipMemcpyDeviceToHost, h->stream));
+    if (x_sync_host) LC_HIP(h, hipMemcpyAsync(x_sync_host, h->bm_xs, bytes, hipMemcpyDeviceToHost, h->stream));
+    LC_HIP(h, hipStreamSynchronize(h->stream));
     return LC_OK;
 }
 
@@ -508,6 +545,7 @@ int lc_update_from_grad(lc_handle* h) {
     if (!h) return LC_ERR_ARG;
     if (!h->attached || !h->G) return LC_ERR_STATE;
     LC_HIP(h, launch_update_from_grad(h));
+    h->v_cleared = false;
     return LC_OK;
 }
 
@@ -515,6 +553,7 @@ int lc_update_from_grad_and_average(lc_handle* h) {
     if (!h) return LC_ERR_ARG;
     if (!h->attached || !h->G) return LC_ERR_STATE;
     LC_HIP(h, launch_update_and_average(h));
+    h->v_cleared = false;
     return LC_OK;
 }
 
@@ -523,8 +562,10 @@ int lc_get_state(lc_handle* h, float* X_host, float* V_host, int64_t* k) {
     if (!h->attached) return LC_ERR_STATE;
     const size_t row = sizeof(float) * static_cast<size_t>(h->P), pitch = sizeof(float) * static_cast<size_t>(h->Ps);
     if (X_host) LC_HIP(h, hipMemcpy2DAsync(X_host, row, h->X, pitch, row, h->m, hipMemcpyDeviceToHost, h->stream));
-    if (V_host) LC_HIP(h, hipMemcpy2DAsync(V_host, row, h->V, pitch, row, h->m, hipMemcpyDeviceToHost, h->stream));
+    if (V_host && !h->v_cleared)
+        LC_HIP(h, hipMemcpy2DAsync(V_host, row, h->V, pitch, row, h->m, hipMemcpyDeviceToHost, h->stream));
     LC_HIP(h, hipStreamSynchronize(h->stream));
+    if (V_host && h->v_cleared) memset(V_host, 0, row * static_cast<size_t>(h->m));   // cleared, not yet rewritten
     if (k) *k = h->k;
     return LC_OK;
 }
@@ -534,7 +575,10 @@ int lc_set_state(lc_handle* h, const float* X_host, const float* V_host, int64_t
     if (!h->attached) return LC_ERR_STATE;
     const size_t row = sizeof(float) * static_cast<size_t>(h->P), pitch = sizeof(float) * static_cast<size_t>(h->Ps);
     if (X_host) LC_HIP(h, hipMemcpy2DAsync(h->X, pitch, X_host, row, row, h->m, hipMemcpyHostToDevice, h->stream));
-    if (V_host) LC_HIP(h, hipMemcpy2DAsync(h->V, pitch, V_host, row, row, h->m, hipMemcpyHostToDevice, h->stream));
+    if (V_host) {
+        LC_HIP(h, hipMemcpy2DAsync(h->V, pitch, V_host, row, row, h->m, hipMemcpyHostToDevice, h->stream));
+        h->v_cleared = false;
+    }
     LC_HIP(h, hipStreamSynchronize(h->stream));
     h->k = k;
     return LC_OK;

@@ -71,6 +71,11 @@ struct lc_handle {
     hipStream_t stream;
     lc::ActSet train, eval;
     float* xbar;            // [Ps]
+    // block momentum: global buffer, last synchronised model, and the deferred clearing of V
+    float *bm_u, *bm_xs;    // [Ps]
+    bool bm_on;
+    float bm_beta;
+    bool v_cleared;         // V counts as zero: the next update uses beta = 0 and overwrites it
     double* partial;        // reduction partials
     int n_partial;
     int last_hip;
@@ -84,6 +89,7 @@ namespace lc {
 
 // ---- launchers (each returns a hipError_t from hipGetLastError) --------------
 hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* out_single);
+inline float effective_beta(const lc_handle* h) { return h->v_cleared ? 0.f : h->md.beta; }
 hipError_t launch_update_from_grad(lc_handle* h);
 hipError_t launch_update_and_average(lc_handle* h);
 hipError_t launch_quad_step(lc_handle* h);

@@ -1094,7 +1094,7 @@ hipError_t launch_head(lc_handle* h) {
     a.dzp_fm = L > 1 ? S.dz_fm[L - 1] : nullptr;
     a.loss = S.loss;
     a.lr = h->md.lr;
-    a.beta = h->md.beta;
+    a.beta = effective_beta(h);
     a.wd = h->md.wd;
     a.vec = (g.d_out % 4 == 0 && g.w_off % 4 == 0) ? 1 : 0;
     a.stream = 0;   // the last layer is small: keep it cached
@@ -1156,7 +1156,7 @@ hipError_t launch_backward(lc_handle* h, int l) {
     a.dzp_bm = l > 1 ? S.dz_bm[l - 1] : nullptr;
     a.dzp_fm = l > 1 ? S.dz_fm[l - 1] : nullptr;
     a.lr = h->md.lr;
-    a.beta = h->md.beta;
+    a.beta = effective_beta(h);
     a.wd = h->md.wd;
     a.vec = (g.d_out % 4 == 0 && g.w_off % 4 == 0) ? 1 : 0;
     a.stream = h->stream_weights ? 1 : 0;

@@ -21,12 +21,37 @@ __device__ __forceinline__ void st_stream(float* p, float4 v) {
     __builtin_nontemporal_store(f32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<f32x4*>(p));
 }
 
+// Block momentum (Sec. 5.3.1) applied to one float4 of the mean: G = (x_sync - x_bar) / lr,
+// u <- beta_glob u + G, x_sync <- x_sync - lr u; returns the new synchronised values.
+struct BlockMomentum {
+    float* u;      // null: plain averaging
+    float* xs;
+    float beta_glob, lr, inv_lr;
+};
+
+__device__ __forceinline__ float4 apply_block_momentum(const BlockMomentum& bm, int64_t col, float4 mean) {
+    if (!bm.u) return mean;
+    float4 u = *reinterpret_cast<const float4*>(bm.u + col);
+    float4 xs = *reinterpret_cast<const float4*>(bm.xs + col);
+    u.x = bm.beta_glob * u.x + (xs.x - mean.x) * bm.inv_lr;
+    u.y = bm.beta_glob * u.y + (xs.y - mean.y) * bm.inv_lr;
+    u.z = bm.beta_glob * u.z + (xs.z - mean.z) * bm.inv_lr;
+    u.w = bm.beta_glob * u.w + (xs.w - mean.w) * bm.inv_lr;
+    xs.x -= bm.lr * u.x;
+    xs.y -= bm.lr * u.y;
+    xs.z -= bm.lr * u.z;
+    xs.w -= bm.lr * u.w;
+    *reinterpret_cast<float4*>(bm.u + col) = u;
+    *reinterpret_cast<float4*>(bm.xs + col) = xs;
+    return xs;
+}
+
 // x_bar = (1/m) sum_i x^(i), written to every row of out_rows (in place when
 // out_rows == X) and/or to the single vector out_single.  The sum is carried in
 // double: adding m floats in double is exact for any realistic spread of
 // magnitudes, so the result is the correctly rounded mean whatever the order.
 __global__ __launch_bounds__(kThreads) void average_kernel(const float* __restrict__ X, float* out_rows,
-                                                           float* out_single, int m, int64_t Ps) {
+                                                           float* out_single, int m, int64_t Ps, BlockMomentum bm) {
     const int64_t col = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
     if (col >= Ps) return;
     double s0 = 0, s1 = 0, s2 = 0, s3 = 0;
@@ -45,11 +70,13 @@ __global__ __launch_bounds__(kThreads) void average_kernel(const float* __restri
             }
     }
     const double dm = static_cast<double>(m);
-    const float4 mean = make_float4(static_cast<float>(s0 / dm), static_cast<float>(s1 / dm),
-                                    static_cast<float>(s2 / dm), static_cast<float>(s3 / dm));
-    if (out_rows)
-        for (int i = 0; i < m; ++i) st_stream(out_rows + static_cast<int64_t>(i) * Ps + col, mean);
+    float4 mean = make_float4(static_cast<float>(s0 / dm), static_cast<float>(s1 / dm),
+                              static_cast<float>(s2 / dm), static_cast<float>(s3 / dm));
     if (out_single) *reinterpret_cast<float4*>(out_single + col) = mean;
+    if (out_rows) {
+        mean = apply_block_momentum(bm, col, mean);
+        for (int i = 0; i < m; ++i) st_stream(out_rows + static_cast<int64_t>(i) * Ps + col, mean);
+    }
 }
 
 // Two-kernel form of the averaging step for states larger than the caches.
@@ -64,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void average_kernel(const float* __restri
 constexpr int kReduceCols = 8;   // float4 columns per thread in reduce_chunk
 
 __global__ __launch_bounds__(kThreads) void reduce_chunk_kernel(float* X, int m, int64_t Ps, int64_t c_lo,
-                                                                int64_t c_hi) {
+                                                                int64_t c_hi, BlockMomentum bm) {
     const int64_t base = c_lo / 4 + static_cast<int64_t>(blockIdx.x) * kThreads * kReduceCols;
     double s[kReduceCols][4];
 #pragma unroll
@@ -89,9 +116,10 @@ __global__ __launch_bounds__(kThreads) void reduce_chunk_kernel(float* X, int m,
     for (int u = 0; u < kReduceCols; ++u) {
         const int64_t c = (base + u * kThreads + threadIdx.x) * 4;
         if (c < c_hi)
-            *reinterpret_cast<float4*>(X + c) =
+            *reinterpret_cast<float4*>(X + c) = apply_block_momentum(
+                bm, c,
                 make_float4(static_cast<float>(s[u][0] / dm), static_cast<float>(s[u][1] / dm),
-                            static_cast<float>(s[u][2] / dm), static_cast<float>(s[u][3] / dm));
+                            static_cast<float>(s[u][2] / dm), static_cast<float>(s[u][3] / dm)));
     }
 }
 
@@ -203,6 +231,8 @@ inline unsigned blocks_for(int64_t threads) { return static_cast<unsigned>((thre
 }  // namespace
 
 hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* out_single) {
+    BlockMomentum bm{nullptr, nullptr, 0.f, 0.f, 0.f};
+    if (h->bm_on && out_rows) bm = BlockMomentum{h->bm_u, h->bm_xs, h->bm_beta, h->md.lr, 1.f / h->md.lr};
     // in-place averaging of a state larger than the caches: chunked reduce into row 0,
     // then row-by-row broadcast
     const bool two_phase = out_rows == h->X && X == h->X && !out_single && h->m >= 2 && h->avg_two_phase &&
@@ -215,7 +245,7 @@ hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* 
             const int64_t nblk = ((hi - lo) / 4 + kThreads - 1) / kThreads;
             const int64_t nred = (nblk + kReduceCols - 1) / kReduceCols;
             hipLaunchKernelGGL(reduce_chunk_kernel, dim3(static_cast<unsigned>(nred)), dim3(kThreads), 0, h->stream,
-                               h->X, h->m, h->Ps, lo, hi);
+                               h->X, h->m, h->Ps, lo, hi, bm);
             hipLaunchKernelGGL(broadcast_chunk_kernel, dim3(static_cast<unsigned>(nblk * (h->m - 1))), dim3(kThreads),
                                0, h->stream, h->X, h->Ps, lo, hi, nblk);
         }
@@ -224,7 +254,7 @@ hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* 
     }
     if (out_rows) timing_start(h, kTimeAvg);
     hipLaunchKernelGGL(average_kernel, dim3(blocks_for(h->Ps / 4)), dim3(kThreads), 0, h->stream, X, out_rows,
-                       out_single, h->m, h->Ps);
+                       out_single, h->m, h->Ps, bm);
     if (out_rows) timing_stop(h, kTimeAvg);
     return hipGetLastError();
 }
@@ -233,7 +263,7 @@ hipError_t launch_update_from_grad(lc_handle* h) {
     const int64_t n4 = static_cast<int64_t>(h->m) * h->Ps / 4;
     timing_start(h, kTimeUpd);
     hipLaunchKernelGGL(update_kernel, dim3(blocks_for(n4)), dim3(kThreads), 0, h->stream, h->X, h->V, h->G, n4,
-                       h->md.lr, h->md.beta, h->md.wd);
+                       h->md.lr, effective_beta(h), h->md.wd);
     timing_stop(h, kTimeUpd);
     return hipGetLastError();
 }
@@ -241,7 +271,7 @@ hipError_t launch_update_from_grad(lc_handle* h) {
 hipError_t launch_update_and_average(lc_handle* h) {
     timing_start(h, kTimeUpdAvg);
     hipLaunchKernelGGL(update_average_kernel, dim3(blocks_for(h->Ps / 4)), dim3(kThreads), 0, h->stream, h->X, h->V,
-                       h->G, h->m, h->Ps, h->md.lr, h->md.beta, h->md.wd);
+                       h->G, h->m, h->Ps, h->md.lr, effective_beta(h), h->md.wd);
     timing_stop(h, kTimeUpdAvg);
     return hipGetLastError();
 }
@@ -249,7 +279,7 @@ hipError_t launch_update_and_average(lc_handle* h) {
 hipError_t launch_quad_step(lc_handle* h) {
     const int64_t n4 = static_cast<int64_t>(h->m) * h->Ps / 4;
     hipLaunchKernelGGL(quad_step_kernel, dim3(blocks_for(n4)), dim3(kThreads), 0, h->stream, h->X, h->V, h->qa,
-                       h->qc, n4, h->md.lr, h->md.beta, h->md.wd);
+                       h->qc, n4, h->md.lr, effective_beta(h), h->md.wd);
     return hipGetLastError();
 }
 

@@ -400,6 +400,64 @@ def test_refined_schedule_bit_exact(pkg, orc):
     run.close()
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_block_momentum_rounds(pkg, orc, bf16):
+    """Block momentum (global factor 0.3, local 0.9, local buffers restarted at every
+    averaging step) over several periods against the oracle."""
+    dims, m, B, tau = [130, 70, 33, 7], 4, 48, 3
+    _say(f"block momentum bf16={bf16}")
+    ref, run = _problem(pkg, orc, dims, m, B, lr=0.05, beta=0.9, bf16=bf16)
+    tol = TOL16 if bf16 else TOL32
+    ref.block_begin(0.3)
+    run.block_momentum_begin(0.3)
+    for r in range(3):
+        ref.local_steps(tau)
+        run.local_steps(tau)
+        ref.average()
+        run.average()
+        X, V, k = run.get_state()
+        u, xs = run.get_block_momentum()
+        _assert_close(X, ref.X, dims, tol * (2 if r else 1), f"X round {r}")
+        _assert_close(u[None, :], ref.block_u[None, :], dims, tol * 5, f"u round {r}")
+        assert np.array_equal(xs, X[0]) and np.abs(V).max() == 0.0 and np.abs(ref.V).max() == 0.0
+        for i in range(1, m):
+            assert np.array_equal(X[i].view(np.uint32), X[0].view(np.uint32))
+    # back to plain averaging: buffers survive the averaging step again
+    ref.block_end()
+    run.block_momentum_end()
+    ref.local_steps(2)
+    run.local_steps(2)
+    ref.average()
+    run.average()
+    X, V, _ = run.get_state()
+    _assert_close(X, ref.X, dims, tol * 3, "X after leaving the mode")
+    assert np.abs(V).max() > 0
+    run.close()
+
+
+def test_block_momentum_quadratic_closed_form_and_driver(pkg, orc):
+    _say("block momentum quadratic")
+    m, P, lr, bg, tau, R = 4, 333, 0.1, 0.3, 5, 6
+    a, c, x0 = synth.quad_problem(12, m, P, common_a=True)
+    run = pkg.LocalSGD(m, pkg.make_model(pkg.KIND_QUAD, [P], lr=lr), 0, x0, qa=a, qc=c)
+    run.block_momentum_begin(bg)
+    sched, rounds = run.run(tau * R, tau)
+    assert rounds == R
+    a64, cbar = a[0].astype(np.float64), c.astype(np.float64).mean(axis=0)
+    lr64 = np.float64(np.float32(lr))
+    rho_t = (1.0 - lr64 * a64) ** tau
+    e, u = x0.astype(np.float64) - cbar, np.zeros(P)
+    for _ in range(R):
+        u = bg * u + (1.0 - rho_t) * e / lr64
+        e = e - lr64 * u
+    X, V, k = run.get_state()
+    gu, _ = run.get_block_momentum()
+    assert k == tau * R
+    assert np.abs(X[0] - (cbar + e)).max() < 2e-5
+    assert np.abs(gu - u).max() < 2e-4 * max(1.0, np.abs(u).max())
+    run.close()
+
+
 # --------------------------------------------------------------- error paths
 
 def test_attach_errors_and_bad_tau(pkg):
@@ -512,4 +570,23 @@ def test_full_size_averaging_and_update(pkg, m, P):
         assert np.array_equal(got[i].view(np.uint32), want.view(np.uint32))
     assert bool((X == X[0:1]).all().item())
     assert bool((V[:, cols] == Vb).all().item())
+    # block momentum at this size (the chunked reduce + broadcast path): two periods of one
+    # explicit-gradient update each, checked on the sampled columns
+    bg, lr = 0.3, kw["lr"]
+    assert L.lc_block_momentum_begin(h, C.c_float(bg)) == 0
+    xs = X[0, cols].cpu().numpy().astype(np.float64)
+    u = np.zeros_like(xs)
+    for _ in range(2):
+        assert L.lc_update_from_grad(h) == 0
+        torch.cuda.synchronize()
+        rows = X[:, cols].cpu().numpy()
+        xbar = rows.astype(np.float64).mean(axis=0).astype(np.float32).astype(np.float64)
+        assert L.lc_average(h) == 0
+        torch.cuda.synchronize()
+        u = bg * u + (xs - xbar) / np.float64(np.float32(lr))
+        xs = xs - np.float64(np.float32(lr)) * u
+        got = X[:, cols].cpu().numpy()
+        assert np.abs(got[0] - xs).max() < 1e-5 * np.abs(xs).max()
+        assert all(np.array_equal(got[i], got[0]) for i in range(1, m))
+    assert bool((X == X[0:1]).all().item())
     L.lc_destroy(h)
