@@ -148,7 +148,7 @@ int one_local_step(lc_handle* h) {
             for (int l = h->L - 1; l >= 1; --l) LC_HIP(h, launch_backward(h, l));
         } else {
             for (int l = 1; l <= h->L; ++l) LC_HIP(h, launch_forward(h, false, l, 0));
-            LC_HIP(h, launch_softmax(h, false, 0));
+            if (!forward_fuses_softmax(h)) LC_HIP(h, launch_softmax(h, false, 0));
             for (int l = h->L; l >= 1; --l) LC_HIP(h, launch_backward(h, l));
         }
     }

@@ -121,6 +121,8 @@ SHAPES = [
     ([784, 256, 10], 8, 64),
     # full 128-row batch tile
     ([200, 128, 10], 3, 128),
+    # more classes than one 64-column tile: separate softmax kernel, two-chunk last layer
+    ([40, 50, 70], 2, 16),
 ]
 
 
