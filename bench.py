@@ -29,6 +29,17 @@ DEFAULT_STEPS = {"cfg1": 2000, "cfg2": 2000, "cfg3": 200, "cfg4": 40, "cfg5a": 5
 DEFAULT_WARMUP = {"cfg1": 100, "cfg2": 100, "cfg3": 20, "cfg4": 5, "cfg5a": 5, "cfg5b": 3}
 FLAT = {"cfg5a": (16, 25_600_000), "cfg5b": (8, 138_000_000)}
 
+# HBM bytes per launch of the dominant kernel (backward + fused update, averaged over the layers'
+# launches of one iteration) and its MFMA busy share, from rocprofv3 --pmc runs of this script:
+# FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (calibration on the plain streaming update kernel) and
+# SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE / 8 XCDs x 1024 SIMDs).  Summaries with the commands
+# are in profiles/pmc_traffic_mfma_<workload>.txt.
+PMC = {
+    "cfg2": {"traffic": (28.156e6 + 2.381e6) / 2, "mfma_busy_pct": (7.77 + 1.13) / 2},
+    "cfg3": {"traffic": (822.645e6 + 2 * 152.948e6) / 3, "mfma_busy_pct": (3.12 * 157 + 3.42 * 2 * 60) / (157 + 120)},
+    "cfg4": {"traffic": (6466.381e6 + 3 * 2909.427e6) / 4, "mfma_busy_pct": (0.81 * 1287 + 1.61 * 3 * 580) / (1287 + 1740)},
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -80,9 +91,11 @@ def bench_mlp(args, pkg, synth):
     achieved = per_launch_bytes / (avg_launch_ms * 1e-3) / 1e9
     roof = {"bound": "hbm", "kernel": "backward_kernel (dA + dW + momentum update, all layers)",
             "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": PMC[name]["traffic"] if name in PMC and args.tau is None else None,
             "launches": launches, "avg_launch_us": round(avg_launch_ms * 1e3, 2),
-            "algorithmic_bytes_per_launch": per_launch_bytes}
+            "algorithmic_bytes_per_launch": per_launch_bytes,
+            "mfma_busy_pct": round(PMC[name]["mfma_busy_pct"], 2) if name in PMC else None}
     final_loss = run.loss()
     run.close()
     cfg = {"workload": f"{name}: MLP {'-'.join(map(str, w.dims))}, m={w.m}, B={w.B}, "
@@ -103,7 +116,7 @@ def bench_flat(args, pkg, name):
     K = args.steps if args.steps is not None else DEFAULT_STEPS[name]
     W = args.warmup if args.warmup is not None else DEFAULT_WARMUP[name]
     res = flat_measure(pkg, m, P, K, W)
-    roof = {"bound": "hbm", "kernel": "average_kernel", "achieved": round(res["avg_gbs"], 1), "peak": HBM_PEAK_GBS,
+    roof = {"bound": "hbm", "kernel": "averaging step (reduce_chunk_kernel + broadcast_chunk_kernel over all chunks)", "achieved": round(res["avg_gbs"], 1), "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": round(res["avg_gbs"] / HBM_PEAK_GBS, 4), "traffic": None,
             "launches": res["launches"], "avg_launch_us": round(res["avg_us"], 2),
             "algorithmic_bytes_per_launch": 8.0 * m * P}
