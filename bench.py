@@ -50,6 +50,7 @@ def parse():
     ap.add_argument("--tau", type=int, default=None, help="fixed communication period (overrides the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the averaging-stress figures")
+    ap.add_argument("--eager", action="store_true", help="write the average to every row at once (no deferred broadcast)")
     return ap.parse_args()
 
 
@@ -68,6 +69,7 @@ def bench_mlp(args, pkg, synth):
     W = args.warmup if args.warmup is not None else DEFAULT_WARMUP[name]
     md = pkg.make_model(pkg.KIND_MLP, w.dims, B=w.B, N=w.N, E=w.E, lr=w.lr, beta=w.beta, wd=w.wd, bf16=w.bf16)
     run = pkg.LocalSGD(w.m, md, w.seed, w.x1, w.data, w.labels)
+    run.set_lazy_broadcast(not args.eager)   # bit-identical results; see lc_set_lazy_broadcast
     interval = w.interval if adaptive else 0
 
     run.run(W, tau0, adaptive=False) if W > 0 else None
@@ -102,7 +104,8 @@ def bench_mlp(args, pkg, synth):
                        f"{'AdaComm tau0=' if adaptive else 'tau='}{tau0}"
                        f"{', interval=%d' % interval if adaptive else ''}, lr={w.lr}, momentum={w.beta}",
            "m": w.m, "P": w.P, "batch_per_replica": w.B, "tau0": tau0, "adaptive": adaptive,
-           "averaging_rounds": rounds, "tau_schedule": sched[:16], "final_loss": round(final_loss, 6)}
+           "averaging_rounds": rounds, "tau_schedule": sched[:16], "final_loss": round(final_loss, 6),
+           "deferred_broadcast": not args.eager}
     return dict(value=w.m * K / sec, sec=sec, K=K, W=W, roofline=roof, config=cfg,
                 dtype="bf16" if w.bf16 else "f32", workload=w, tau0=tau0)
 

@@ -130,6 +130,17 @@ int lc_local_steps(lc_handle* h, int tau);
  * nothing more.  Asynchronous. */
 int lc_average(lc_handle* h);
 
+/* Deferred broadcast.  With on != 0 (LC_KIND_MLP only) lc_average() only computes the averaged
+ * model (reads m rows, writes one vector in scratch): the next local step reads that one model for
+ * every replica -- it is served from cache m-1 times out of m -- and writes every row of X, as it
+ * does anyway.  This removes the m row writes of the averaging step and most weight reads of the
+ * step after it; at tau = 1 the traffic per iteration falls from about 28 to 16 bytes per
+ * parameter.  Results are bit-identical to the eager form.  While a broadcast is pending the rows
+ * of X in device memory are STALE; every entry point of this library accounts for that, but a
+ * caller who reads X directly must call lc_materialize() first.  Turning the mode off materialises. */
+int lc_set_lazy_broadcast(lc_handle* h, int on);
+int lc_materialize(lc_handle* h);
+
 /* Training loss of the averaged model F(x_bar) on the first E samples (the
  * quantity the basic update rule of Sec. 4.2 reads).  Always evaluated with
  * fp32 operands.  Does not modify X or V.  Synchronises the stream; *out is a

@@ -20,7 +20,10 @@
  * PyTorch CPU autograd + torch.optim.SGD in fp64 and against central finite
  * differences; the controller against exact rational arithmetic; the index
  * stream's mixer against the published SplitMix64 output sequence; bf16
- * rounding against torch's conversion.  No function here is "parity unpinned".
+ * rounding against torch's conversion; the refined controller against exact
+ * rational arithmetic and its driver against the quadratic closed form; block
+ * momentum against synchronous momentum SGD (tau=1), plain averaging
+ * (beta_glob=0) and a quadratic recurrence.  No function here is "parity unpinned".
  */
 #ifndef PASGD_ORACLE_H
 #define PASGD_ORACLE_H

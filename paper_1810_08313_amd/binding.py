@@ -79,6 +79,10 @@ def lib() -> C.CDLL:
     L.lc_local_steps.argtypes = [vp, C.c_int]
     L.lc_average.restype = C.c_int
     L.lc_average.argtypes = [vp]
+    L.lc_set_lazy_broadcast.restype = C.c_int
+    L.lc_set_lazy_broadcast.argtypes = [vp, C.c_int]
+    L.lc_materialize.restype = C.c_int
+    L.lc_materialize.argtypes = [vp]
     L.lc_loss.restype = C.c_int
     L.lc_loss.argtypes = [vp, C.POINTER(C.c_double)]
     L.adacomm_next_tau.restype = C.c_int
@@ -249,6 +253,12 @@ class LocalSGD:
 
     def average(self) -> None:
         self._check(self._L.lc_average(self._h), "lc_average")
+
+    def set_lazy_broadcast(self, on: bool) -> None:
+        self._check(self._L.lc_set_lazy_broadcast(self._h, int(bool(on))), "lc_set_lazy_broadcast")
+
+    def materialize(self) -> None:
+        self._check(self._L.lc_materialize(self._h), "lc_materialize")
 
     def loss(self) -> float:
         out = C.c_double(0.0)

@@ -135,8 +135,18 @@ int require_objective(const lc_handle* h) {
     return LC_OK;
 }
 
+// Make the rows of X real again after a deferred broadcast.
+int materialise(lc_handle* h) {
+    if (!h->lazy_rows) return LC_OK;
+    LC_HIP(h, launch_broadcast_xbar(h));
+    h->lazy_rows = false;
+    return LC_OK;
+}
+
 int one_local_step(lc_handle* h) {
     if (h->md.kind == LC_KIND_QUAD) {
+        const int rc = materialise(h);
+        if (rc != LC_OK) return rc;
         LC_HIP(h, launch_quad_step(h));
     } else {
         LC_HIP(h, launch_gather(h, false, h->k));
@@ -154,6 +164,7 @@ int one_local_step(lc_handle* h) {
     }
     h->k += 1;
     h->v_cleared = false;   // the step just queued wrote V = g
+    h->lazy_rows = false;   // ... and every row of X
     return LC_OK;
 }
 
@@ -241,6 +252,7 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     h->bm_on = false;
     h->bm_beta = 0.f;
     h->v_cleared = false;
+    h->lazy_enabled = h->lazy_rows = h->lazy_enabled_step = false;
     (void)carve(h, nullptr);
     *out = h;
     return LC_OK;
@@ -303,15 +315,47 @@ int lc_local_steps(lc_handle* h, int tau) {
 int lc_average(lc_handle* h) {
     const int rc = require_attached(h);
     if (rc != LC_OK) return rc;
-    LC_HIP(h, launch_average(h, h->X, h->X, nullptr));
+    if (h->lazy_rows) {
+        if (!h->bm_on) return LC_OK;   // already synchronised: averaging again changes nothing
+        const int mrc = materialise(h);   // block momentum moves even a synchronised model (u decays)
+        if (mrc != LC_OK) return mrc;
+    }
+    if (h->lazy_enabled && h->md.kind == LC_KIND_MLP) {
+        // reduce only: the next local step reads the one averaged model and writes every row
+        h->lazy_enabled_step = true;
+        const hipError_t e = launch_average(h, h->X, nullptr, h->xbar);
+        h->lazy_enabled_step = false;
+        LC_HIP(h, e);
+        h->lazy_rows = true;
+    } else {
+        LC_HIP(h, launch_average(h, h->X, h->X, nullptr));
+    }
     if (h->bm_on) h->v_cleared = true;   // local momentum restarts after every block-momentum step
     return LC_OK;
+}
+
+int lc_set_lazy_broadcast(lc_handle* h, int on) {
+    if (!h) return LC_ERR_ARG;
+    if (!on && h->attached) {
+        const int rc = materialise(h);
+        if (rc != LC_OK) return rc;
+    }
+    h->lazy_enabled = on != 0;
+    return LC_OK;
+}
+
+int lc_materialize(lc_handle* h) {
+    const int rc = require_attached(h);
+    if (rc != LC_OK) return rc;
+    return materialise(h);
 }
 
 int lc_block_momentum_begin(lc_handle* h, float beta_glob) {
     const int rc = require_attached(h);
     if (rc != LC_OK) return rc;
     if (!(beta_glob >= 0.f) || !(beta_glob < 1.f) || !(h->md.lr > 0.f)) return LC_ERR_ARG;
+    const int mrc = materialise(h);
+    if (mrc != LC_OK) return mrc;
     const size_t bytes = sizeof(float) * static_cast<size_t>(h->Ps);
     LC_HIP(h, hipMemsetAsync(h->bm_u, 0, bytes, h->stream));
     LC_HIP(h, hipMemcpyAsync(h->bm_xs, h->X, bytes, hipMemcpyDeviceToDevice, h->stream));
@@ -342,7 +386,7 @@ int lc_loss(lc_handle* h, double* out) {
     const int rc = require_objective(h);
     if (rc != LC_OK) return rc;
     if (!out) return LC_ERR_ARG;
-    LC_HIP(h, launch_average(h, h->X, nullptr, h->xbar));
+    if (!h->lazy_rows) LC_HIP(h, launch_average(h, h->X, nullptr, h->xbar));   // else xbar is the model already
     double F = 0.0;
     if (h->md.kind == LC_KIND_QUAD) {
         int np = 0;
@@ -544,6 +588,8 @@ int lc_set_grad(lc_handle* h, const void* G) {
 int lc_update_from_grad(lc_handle* h) {
     if (!h) return LC_ERR_ARG;
     if (!h->attached || !h->G) return LC_ERR_STATE;
+    const int mrc = materialise(h);
+    if (mrc != LC_OK) return mrc;
     LC_HIP(h, launch_update_from_grad(h));
     h->v_cleared = false;
     return LC_OK;
@@ -552,6 +598,8 @@ int lc_update_from_grad(lc_handle* h) {
 int lc_update_from_grad_and_average(lc_handle* h) {
     if (!h) return LC_ERR_ARG;
     if (!h->attached || !h->G) return LC_ERR_STATE;
+    const int mrc = materialise(h);
+    if (mrc != LC_OK) return mrc;
     LC_HIP(h, launch_update_and_average(h));
     h->v_cleared = false;
     return LC_OK;
@@ -561,7 +609,11 @@ int lc_get_state(lc_handle* h, float* X_host, float* V_host, int64_t* k) {
     if (!h) return LC_ERR_ARG;
     if (!h->attached) return LC_ERR_STATE;
     const size_t row = sizeof(float) * static_cast<size_t>(h->P), pitch = sizeof(float) * static_cast<size_t>(h->Ps);
-    if (X_host) LC_HIP(h, hipMemcpy2DAsync(X_host, row, h->X, pitch, row, h->m, hipMemcpyDeviceToHost, h->stream));
+    if (X_host) {
+        const int mrc = materialise(h);
+        if (mrc != LC_OK) return mrc;
+        LC_HIP(h, hipMemcpy2DAsync(X_host, row, h->X, pitch, row, h->m, hipMemcpyDeviceToHost, h->stream));
+    }
     if (V_host && !h->v_cleared)
         LC_HIP(h, hipMemcpy2DAsync(V_host, row, h->V, pitch, row, h->m, hipMemcpyDeviceToHost, h->stream));
     LC_HIP(h, hipStreamSynchronize(h->stream));
@@ -574,7 +626,10 @@ int lc_set_state(lc_handle* h, const float* X_host, const float* V_host, int64_t
     if (!h || k < 0) return LC_ERR_ARG;
     if (!h->attached) return LC_ERR_STATE;
     const size_t row = sizeof(float) * static_cast<size_t>(h->P), pitch = sizeof(float) * static_cast<size_t>(h->Ps);
-    if (X_host) LC_HIP(h, hipMemcpy2DAsync(h->X, pitch, X_host, row, row, h->m, hipMemcpyHostToDevice, h->stream));
+    if (X_host) {
+        LC_HIP(h, hipMemcpy2DAsync(h->X, pitch, X_host, row, row, h->m, hipMemcpyHostToDevice, h->stream));
+        h->lazy_rows = false;
+    }
     if (V_host) {
         LC_HIP(h, hipMemcpy2DAsync(h->V, pitch, V_host, row, row, h->m, hipMemcpyHostToDevice, h->stream));
         h->v_cleared = false;

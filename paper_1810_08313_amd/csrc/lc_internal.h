@@ -76,6 +76,10 @@ struct lc_handle {
     bool bm_on;
     float bm_beta;
     bool v_cleared;         // V counts as zero: the next update uses beta = 0 and overwrites it
+    // lazy broadcast: after an averaging step the rows of X are stale and every replica's model is
+    // the single vector xbar, until the next local step (which writes every row) or a materialise
+    bool lazy_enabled, lazy_rows;
+    bool lazy_enabled_step;   // set only while lc_average runs its reduce-only form
     double* partial;        // reduction partials
     int n_partial;
     int last_hip;
@@ -90,6 +94,7 @@ namespace lc {
 // ---- launchers (each returns a hipError_t from hipGetLastError) --------------
 hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* out_single);
 inline float effective_beta(const lc_handle* h) { return h->v_cleared ? 0.f : h->md.beta; }
+hipError_t launch_broadcast_xbar(lc_handle* h);   // xbar -> every row of X
 hipError_t launch_update_from_grad(lc_handle* h);
 hipError_t launch_update_and_average(lc_handle* h);
 hipError_t launch_quad_step(lc_handle* h);

@@ -466,6 +466,8 @@ struct BwdArgs {
     float* X;
     float* V;
     int64_t x_stride;
+    const float* Xr;     // where the weights are READ: X itself, or the single averaged model that all
+    int64_t xr_stride;   // replicas share right after a lazy averaging step (stride 0)
     int64_t w_off, b_off;
     int d_in, d_out, dp_in, dp_out;
     int B, Bp;
@@ -522,6 +524,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
     const bool need_da = a.dzp_bm != nullptr;
 
     float* W = a.X + g * a.x_stride + a.w_off;
+    const float* Wr = a.Xr + g * a.xr_stride + a.w_off;
     float* Vw = a.V + g * a.x_stride + a.w_off;
     const OT* AT = static_cast<const OT*>(a.a_fm) + static_cast<int64_t>(g) * a.dp_in * Bp;
     const OT* dZ = static_cast<const OT*>(a.dz_bm) + static_cast<int64_t>(g) * Bp * a.dp_out;
@@ -563,7 +566,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         for (int r = 0; r < 4; ++r) {
             const int row = k0 + 4 * q + r;
             if (row < a.d_in) {
-                ww[r] = load_w4(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, stream);
+                ww[r] = load_w4(Wr + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, stream);
                 vv[r] = load_w4(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, stream);
             } else {
                 ww[r] = vv[r] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -614,7 +617,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
             for (int b = 0; b < a.B; ++b) sb += to_f32(zr[b]);
             float* bx = a.X + g * a.x_stride + a.b_off + c0 + tid;
             float* bv = a.V + g * a.x_stride + a.b_off + c0 + tid;
-            const float x = *bx;
+            const float x = a.Xr[g * a.xr_stride + a.b_off + c0 + tid];
             const float vb = a.beta * *bv + (sb + a.wd * x);
             *bv = vb;
             *bx = x - a.lr * vb;
@@ -713,6 +716,8 @@ struct HeadArgs {
     float* X;
     float* V;
     int64_t x_stride;
+    const float* Xr;         // read source of the weights (see BwdArgs)
+    int64_t xr_stride;
     int64_t w_off, b_off;
     int d_in, d_out, dp_in, dp_out;
     int B;
@@ -743,6 +748,7 @@ __global__ __launch_bounds__(512) void head_kernel(HeadArgs a) {
     const bool vec = a.vec != 0, stream = a.stream != 0;
     const bool need_da = a.dzp_bm != nullptr;
     float* W = a.X + g * a.x_stride + a.w_off;
+    const float* Wr = a.Xr + g * a.xr_stride + a.w_off;
     float* Vw = a.V + g * a.x_stride + a.w_off;
     const OT* A = static_cast<const OT*>(a.a_bm) + static_cast<int64_t>(g) * Bp * a.dp_in;
     const OT* AT = static_cast<const OT*>(a.a_fm) + static_cast<int64_t>(g) * a.dp_in * Bp;
@@ -761,7 +767,7 @@ __global__ __launch_bounds__(512) void head_kernel(HeadArgs a) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int row = k0 + e;
-                w[e] = row < a.d_in ? load_w4(W + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream)
+                w[e] = row < a.d_in ? load_w4(Wr + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream)
                                     : make_float4(0.f, 0.f, 0.f, 0.f);
             }
             Frag<OT> af[NT];
@@ -810,7 +816,7 @@ __global__ __launch_bounds__(512) void head_kernel(HeadArgs a) {
     }
     // bias; logits to memory; clear the delta tiles (entries beyond B and d_out must be zero)
     {
-        const float* bias = a.X + g * a.x_stride + a.b_off;
+        const float* bias = a.Xr + g * a.xr_stride + a.b_off;
         float* out = a.logits + static_cast<int64_t>(g) * Bp * a.dp_out;
         for (int e = tid; e < Bp * kColChunk; e += NW * 64) {
             const int b = e / kColChunk, c = e % kColChunk;
@@ -865,7 +871,7 @@ __global__ __launch_bounds__(512) void head_kernel(HeadArgs a) {
         for (int b = 0; b < a.B; ++b) sb += to_f32(zr[b]);
         float* bx = a.X + g * a.x_stride + a.b_off + tid;
         float* bv = a.V + g * a.x_stride + a.b_off + tid;
-        const float x = *bx;
+        const float x = a.Xr[g * a.xr_stride + a.b_off + tid];
         const float vb = a.beta * *bv + (sb + a.wd * x);
         *bv = vb;
         *bx = x - a.lr * vb;
@@ -881,7 +887,7 @@ __global__ __launch_bounds__(512) void head_kernel(HeadArgs a) {
         for (int r = 0; r < 4; ++r) {
             const int row = k0 + 4 * q + r;
             if (row < a.d_in) {
-                w[r] = load_w4(W + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream);
+                w[r] = load_w4(Wr + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream);
                 v[r] = load_w4(Vw + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream);
             } else {
                 w[r] = v[r] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -1018,8 +1024,9 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     const LayerGeom& g = h->layer[l];
     const bool bf16 = !eval && h->md.gemm == LC_GEMM_BF16;
     FwdArgs a;
-    a.X = eval ? h->xbar : h->X;
-    a.x_stride = eval ? 0 : h->Ps;
+    const bool shared = eval || h->lazy_rows;   // one model for all groups
+    a.X = shared ? h->xbar : h->X;
+    a.x_stride = shared ? 0 : h->Ps;
     a.w_off = g.w_off;
     a.b_off = g.b_off;
     a.d_in = g.d_in;
@@ -1033,7 +1040,7 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     a.out_fm = S.a_fm[l];
     a.last = l == h->L ? 1 : 0;
     a.vec = (g.d_out % 4 == 0 && g.w_off % 4 == 0) ? 1 : 0;
-    a.stream = (!eval && h->stream_weights) ? 1 : 0;
+    a.stream = (!shared && h->stream_weights) ? 1 : 0;
     a.n_chunks = g.dp_out / kColChunk;
     // softmax cross-entropy rides in the epilogue when one block sees all classes of all samples
     a.fuse_softmax = (a.last && g.d_out <= kColChunk) ? 1 : 0;
@@ -1079,6 +1086,8 @@ hipError_t launch_head(lc_handle* h) {
     a.X = h->X;
     a.V = h->V;
     a.x_stride = h->Ps;
+    a.Xr = h->lazy_rows ? h->xbar : h->X;
+    a.xr_stride = h->lazy_rows ? 0 : h->Ps;
     a.w_off = g.w_off;
     a.b_off = g.b_off;
     a.d_in = g.d_in;
@@ -1141,6 +1150,8 @@ hipError_t launch_backward(lc_handle* h, int l) {
     a.X = h->X;
     a.V = h->V;
     a.x_stride = h->Ps;
+    a.Xr = h->lazy_rows ? h->xbar : h->X;
+    a.xr_stride = h->lazy_rows ? 0 : h->Ps;
     a.w_off = g.w_off;
     a.b_off = g.b_off;
     a.d_in = g.d_in;

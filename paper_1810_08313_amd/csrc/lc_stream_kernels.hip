@@ -72,11 +72,10 @@ __global__ __launch_bounds__(kThreads) void average_kernel(const float* __restri
     const double dm = static_cast<double>(m);
     float4 mean = make_float4(static_cast<float>(s0 / dm), static_cast<float>(s1 / dm),
                               static_cast<float>(s2 / dm), static_cast<float>(s3 / dm));
+    mean = apply_block_momentum(bm, col, mean);
     if (out_single) *reinterpret_cast<float4*>(out_single + col) = mean;
-    if (out_rows) {
-        mean = apply_block_momentum(bm, col, mean);
+    if (out_rows)
         for (int i = 0; i < m; ++i) st_stream(out_rows + static_cast<int64_t>(i) * Ps + col, mean);
-    }
 }
 
 // Two-kernel form of the averaging step for states larger than the caches.
@@ -90,8 +89,8 @@ __global__ __launch_bounds__(kThreads) void average_kernel(const float* __restri
 //                   the other; consecutive blocks write consecutive addresses
 constexpr int kReduceCols = 8;   // float4 columns per thread in reduce_chunk
 
-__global__ __launch_bounds__(kThreads) void reduce_chunk_kernel(float* X, int m, int64_t Ps, int64_t c_lo,
-                                                                int64_t c_hi, BlockMomentum bm) {
+__global__ __launch_bounds__(kThreads) void reduce_chunk_kernel(const float* X, float* dst, int m, int64_t Ps,
+                                                                int64_t c_lo, int64_t c_hi, BlockMomentum bm) {
     const int64_t base = c_lo / 4 + static_cast<int64_t>(blockIdx.x) * kThreads * kReduceCols;
     double s[kReduceCols][4];
 #pragma unroll
@@ -116,19 +115,20 @@ __global__ __launch_bounds__(kThreads) void reduce_chunk_kernel(float* X, int m,
     for (int u = 0; u < kReduceCols; ++u) {
         const int64_t c = (base + u * kThreads + threadIdx.x) * 4;
         if (c < c_hi)
-            *reinterpret_cast<float4*>(X + c) = apply_block_momentum(
+            *reinterpret_cast<float4*>(dst + c) = apply_block_momentum(
                 bm, c,
                 make_float4(static_cast<float>(s[u][0] / dm), static_cast<float>(s[u][1] / dm),
                             static_cast<float>(s[u][2] / dm), static_cast<float>(s[u][3] / dm)));
     }
 }
 
-__global__ __launch_bounds__(kThreads) void broadcast_chunk_kernel(float* X, int64_t Ps, int64_t c_lo, int64_t c_hi,
+__global__ __launch_bounds__(kThreads) void broadcast_chunk_kernel(const float* src, float* X, int first_row,
+                                                                   int64_t Ps, int64_t c_lo, int64_t c_hi,
                                                                    int64_t blocks_per_row) {
-    const int64_t row = 1 + blockIdx.x / blocks_per_row, b = blockIdx.x % blocks_per_row;
+    const int64_t row = first_row + blockIdx.x / blocks_per_row, b = blockIdx.x % blocks_per_row;
     const int64_t col = c_lo + (b * kThreads + threadIdx.x) * 4;
     if (col >= c_hi) return;
-    st_stream(X + row * Ps + col, *reinterpret_cast<const float4*>(X + col));
+    st_stream(X + row * Ps + col, *reinterpret_cast<const float4*>(src + col));
 }
 
 __device__ __forceinline__ void sgd_update4(float4& x, float4& v, const float4& g, float lr, float beta, float wd) {
@@ -231,31 +231,46 @@ inline unsigned blocks_for(int64_t threads) { return static_cast<unsigned>((thre
 }  // namespace
 
 hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* out_single) {
+    // block momentum belongs to the averaging step proper (some destination for the new model),
+    // not to the mean that lc_loss takes of unsynchronised workers
+    const bool step = out_rows != nullptr || h->lazy_enabled_step;
     BlockMomentum bm{nullptr, nullptr, 0.f, 0.f, 0.f};
-    if (h->bm_on && out_rows) bm = BlockMomentum{h->bm_u, h->bm_xs, h->bm_beta, h->md.lr, 1.f / h->md.lr};
-    // in-place averaging of a state larger than the caches: chunked reduce into row 0,
-    // then row-by-row broadcast
-    const bool two_phase = out_rows == h->X && X == h->X && !out_single && h->m >= 2 && h->avg_two_phase &&
-                           static_cast<double>(h->m) * static_cast<double>(h->Ps) * 4.0 > 512.0 * 1024 * 1024;
-    if (two_phase) {
+    if (h->bm_on && step) bm = BlockMomentum{h->bm_u, h->bm_xs, h->bm_beta, h->md.lr, 1.f / h->md.lr};
+    // a state larger than the caches: chunked reduce (into row 0, or into xbar when the broadcast
+    // is deferred), then row-by-row broadcast
+    const bool big = static_cast<double>(h->m) * static_cast<double>(h->Ps) * 4.0 > 512.0 * 1024 * 1024;
+    if (step && X == h->X && h->m >= 2 && h->avg_two_phase && big) {
         timing_start(h, kTimeAvg);
         const int64_t chunk = h->avg_chunk_floats;
+        float* dst = out_rows ? h->X : out_single;
         for (int64_t lo = 0; lo < h->Ps; lo += chunk) {
             const int64_t hi = lo + chunk < h->Ps ? lo + chunk : h->Ps;
             const int64_t nblk = ((hi - lo) / 4 + kThreads - 1) / kThreads;
             const int64_t nred = (nblk + kReduceCols - 1) / kReduceCols;
             hipLaunchKernelGGL(reduce_chunk_kernel, dim3(static_cast<unsigned>(nred)), dim3(kThreads), 0, h->stream,
-                               h->X, h->m, h->Ps, lo, hi, bm);
-            hipLaunchKernelGGL(broadcast_chunk_kernel, dim3(static_cast<unsigned>(nblk * (h->m - 1))), dim3(kThreads),
-                               0, h->stream, h->X, h->Ps, lo, hi, nblk);
+                               h->X, dst, h->m, h->Ps, lo, hi, bm);
+            if (out_rows)
+                hipLaunchKernelGGL(broadcast_chunk_kernel, dim3(static_cast<unsigned>(nblk * (h->m - 1))),
+                                   dim3(kThreads), 0, h->stream, h->X, h->X, 1, h->Ps, lo, hi, nblk);
         }
         timing_stop(h, kTimeAvg);
         return hipGetLastError();
     }
-    if (out_rows) timing_start(h, kTimeAvg);
+    if (step) timing_start(h, kTimeAvg);
     hipLaunchKernelGGL(average_kernel, dim3(blocks_for(h->Ps / 4)), dim3(kThreads), 0, h->stream, X, out_rows,
                        out_single, h->m, h->Ps, bm);
-    if (out_rows) timing_stop(h, kTimeAvg);
+    if (step) timing_stop(h, kTimeAvg);
+    return hipGetLastError();
+}
+
+hipError_t launch_broadcast_xbar(lc_handle* h) {
+    const int64_t chunk = h->avg_chunk_floats;
+    for (int64_t lo = 0; lo < h->Ps; lo += chunk) {
+        const int64_t hi = lo + chunk < h->Ps ? lo + chunk : h->Ps;
+        const int64_t nblk = ((hi - lo) / 4 + kThreads - 1) / kThreads;
+        hipLaunchKernelGGL(broadcast_chunk_kernel, dim3(static_cast<unsigned>(nblk * h->m)), dim3(kThreads), 0,
+                           h->stream, h->xbar, h->X, 0, h->Ps, lo, hi, nblk);
+    }
     return hipGetLastError();
 }
 

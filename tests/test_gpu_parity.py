@@ -460,6 +460,52 @@ def test_block_momentum_quadratic_closed_form_and_driver(pkg, orc):
     run.close()
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_lazy_broadcast_is_bit_identical_to_eager(pkg, orc, bf16):
+    """Deferred broadcast: the averaging step only reduces, the next local step reads
+    the one averaged model.  Same bits as the eager form at every observable point."""
+    dims, m, B = [130, 70, 33, 7], 4, 48
+    _say(f"lazy broadcast bf16={bf16}")
+    _, eager = _problem(pkg, orc, dims, m, B, wd=5e-4, bf16=bf16)
+    ref, lazy = _problem(pkg, orc, dims, m, B, wd=5e-4, bf16=bf16)
+    lazy.set_lazy_broadcast(True)
+    for tau in (1, 1, 3, 2):
+        for r in (eager, lazy):
+            r.local_steps(tau)
+            r.average()
+        assert lazy.loss() == eager.loss()                     # evaluated while the broadcast is pending
+        for r in (eager, lazy):
+            r.average()                                        # averaging twice changes nothing
+    Xe, Ve, ke = eager.get_state()
+    Xl, Vl, kl = lazy.get_state()                              # materialises
+    assert ke == kl == 7
+    assert np.array_equal(Xe.view(np.uint32), Xl.view(np.uint32))
+    assert np.array_equal(Ve.view(np.uint32), Vl.view(np.uint32))
+    # and both follow the oracle
+    for tau in (1, 1, 3, 2):
+        ref.local_steps(tau)
+        ref.average()
+    _assert_close(Xl, ref.X, dims, (TOL16 if bf16 else TOL32) * 3, "X")
+    # a pending broadcast is visible in device memory until materialised
+    lazy.local_steps(2)
+    lazy.average()
+    assert not bool((lazy.X[1:] == lazy.X[0:1]).all().item())
+    lazy.materialize()
+    assert bool((lazy.X[1:] == lazy.X[0:1]).all().item())
+    # drivers and block momentum work on top of it
+    eager.local_steps(2)
+    eager.average()
+    for r in (eager, lazy):
+        r.block_momentum_begin(0.3)
+        r.run(7, 3)
+    Xe, Ve, _ = eager.get_state()
+    Xl, Vl, _ = lazy.get_state()
+    assert np.array_equal(Xe.view(np.uint32), Xl.view(np.uint32))
+    assert np.array_equal(Ve.view(np.uint32), Vl.view(np.uint32))
+    eager.close()
+    lazy.close()
+
+
 # --------------------------------------------------------------- error paths
 
 def test_attach_errors_and_bad_tau(pkg):
