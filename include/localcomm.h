@@ -49,6 +49,7 @@ typedef enum {
 
 typedef enum { LC_KIND_QUAD = 0, LC_KIND_MLP = 1 } lc_kind;
 typedef enum { LC_GEMM_FP32 = 0, LC_GEMM_BF16 = 1 } lc_gemm_dtype;
+typedef enum { LC_SAMPLE_REPLACEMENT = 0, LC_SAMPLE_PARTITION = 1 } lc_sampler;
 
 /* Model and optimiser description.
  *   LC_KIND_MLP : ReLU multi-layer perceptron with softmax cross-entropy loss;
@@ -58,7 +59,18 @@ typedef enum { LC_GEMM_FP32 = 0, LC_GEMM_BF16 = 1 } lc_gemm_dtype;
  *                 c[i,p])^2 with the exact gradient (no sampling); dims[0] = P.
  *   gemm        : LC_GEMM_BF16 rounds activations, deltas and the weight operand
  *                 of every matrix product to bfloat16 (accumulation fp32, master
- *                 weights and momentum fp32); the dataset is then bf16 too. */
+ *                 weights and momentum fp32); the dataset is then bf16 too.
+ *   sampler     : LC_SAMPLE_REPLACEMENT draws every sample with replacement from the
+ *                 whole set (the index stream documented at lc_init).
+ *                 LC_SAMPLE_PARTITION follows Sec. 5.1 ("each worker machine is assigned
+ *                 with a partition which will be randomly shuffled after every epoch"):
+ *                 worker i of m owns samples [floor(i N / m), floor((i+1) N / m)); an epoch
+ *                 is S = floor(floor(N / m) / B) iterations; in epoch e = k / S the worker
+ *                 walks a pseudo-random permutation of its partition, B positions per
+ *                 iteration: position p = (k mod S) B + b maps to lo_i + pi(p), pi being a
+ *                 4-round balanced Feistel network on 2w bits (2^(2w) >= n_i) with round
+ *                 function mix(key + G (round+1) + right half) and cycle walking, key =
+ *                 mix(mix(seed + G (e+1)) + G (i+1)).  Needs floor(N / m) >= B. */
 typedef struct {
     int32_t kind;                     /* lc_kind */
     int32_t n_layers;
@@ -70,6 +82,7 @@ typedef struct {
     float beta;                       /* momentum factor, 0 = plain SGD */
     float wd;                         /* weight decay added to the gradient */
     int32_t gemm;                     /* lc_gemm_dtype */
+    int32_t sampler;                  /* lc_sampler */
 } lc_model;
 
 typedef struct lc_handle lc_handle;

@@ -30,6 +30,7 @@ class OrcModel(C.Structure):
         ("beta", C.c_float),
         ("wd", C.c_float),
         ("bf16", C.c_int),
+        ("sampler", C.c_int),
     ]
 
 
@@ -49,6 +50,8 @@ def lib() -> C.CDLL:
     L.orc_mix64.argtypes = [C.c_uint64]
     L.orc_index.restype = C.c_int64
     L.orc_index.argtypes = [C.c_uint64, C.c_int, C.c_int64, C.c_int, C.c_int64]
+    L.orc_index_partition.restype = C.c_int64
+    L.orc_index_partition.argtypes = [C.c_uint64, C.c_int, C.c_int64, C.c_int, C.c_int64, C.c_int, C.c_int]
     L.orc_bf16_round.restype = C.c_float
     L.orc_bf16_round.argtypes = [C.c_float]
     L.orc_param_count.restype = C.c_int64
@@ -111,8 +114,9 @@ def _f(a: np.ndarray):
 
 
 def make_model(kind: int, dims: Sequence[int], B: int = 1, N: int = 1, E: int = 1, lr: float = 0.1,
-               beta: float = 0.0, wd: float = 0.0, bf16: bool = False) -> OrcModel:
+               beta: float = 0.0, wd: float = 0.0, bf16: bool = False, sampler: int = 0) -> OrcModel:
     md = OrcModel()
+    md.sampler = int(sampler)
     md.kind = kind
     md.n_layers = len(dims) - 1 if kind == KIND_MLP else 0
     for j, d in enumerate(dims):
@@ -129,6 +133,10 @@ def mix64(z: int) -> int:
 
 def index(seed: int, i: int, k: int, b: int, N: int) -> int:
     return int(lib().orc_index(C.c_uint64(seed & (2**64 - 1)), i, k, b, N))
+
+
+def index_partition(seed: int, i: int, k: int, b: int, N: int, m: int, B: int) -> int:
+    return int(lib().orc_index_partition(C.c_uint64(seed & (2**64 - 1)), i, k, b, N, m, B))
 
 
 def bf16_round(a) -> np.ndarray:

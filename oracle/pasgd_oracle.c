@@ -47,6 +47,41 @@ int64_t orc_index(uint64_t seed, int i, int64_t k, int b, int64_t N) {
     return (int64_t)(h % (uint64_t)N);
 }
 
+/* Bijection of [0, n): balanced Feistel network on 2w bits (2^(2w) >= n), four rounds whose round
+ * function is the SplitMix64 mixer of (round key + right half); values that land outside [0, n) are
+ * walked through the network again (the network is a permutation of the 2w-bit domain, so the walk
+ * returns below n after finitely many steps). */
+static uint64_t feistel_permute(uint64_t x, uint64_t n, uint64_t key) {
+    int w = 1;
+    while (((uint64_t)1 << (2 * w)) < n) ++w;
+    const uint64_t mask = ((uint64_t)1 << w) - 1;
+    const uint64_t gamma = 0x9E3779B97F4A7C15ULL;
+    do {
+        uint64_t l = x >> w, r = x & mask;
+        for (int round = 0; round < 4; ++round) {
+            const uint64_t f = orc_mix64(key + gamma * (uint64_t)(round + 1) + r) & mask;
+            const uint64_t t = l ^ f;
+            l = r;
+            r = t;
+        }
+        x = (l << w) | r;
+    } while (x >= n);
+    return x;
+}
+
+int64_t orc_index_partition(uint64_t seed, int i, int64_t k, int b, int64_t N, int m, int B) {
+    const int64_t lo = (int64_t)i * N / m, hi = (int64_t)(i + 1) * N / m;
+    const int64_t n = hi - lo;
+    const int64_t nmin = N / m;                     /* the smallest partition has floor(N / m) samples */
+    const int64_t S = nmin / B;
+    if (S < 1) return -1;
+    const int64_t epoch = k / S, pos = (k % S) * B + b;
+    const uint64_t gamma = 0x9E3779B97F4A7C15ULL;
+    uint64_t key = orc_mix64(seed + gamma * ((uint64_t)epoch + 1));
+    key = orc_mix64(key + gamma * ((uint64_t)i + 1));
+    return lo + (int64_t)feistel_permute((uint64_t)pos, (uint64_t)n, key);
+}
+
 float orc_bf16_round(float x) {
     uint32_t u;
     memcpy(&u, &x, 4);
@@ -366,7 +401,9 @@ static void worker_step(orc_state* s, int i, int64_t k) {
         s->last_loss[i] = (float)f;
     } else {
         int64_t* idx = (int64_t*)malloc(sizeof(int64_t) * (size_t)s->md.B);
-        for (int b = 0; b < s->md.B; ++b) idx[b] = orc_index(s->seed, i, k, b, s->md.N);
+        for (int b = 0; b < s->md.B; ++b)
+            idx[b] = s->md.sampler ? orc_index_partition(s->seed, i, k, b, s->md.N, s->m, s->md.B)
+                                   : orc_index(s->seed, i, k, b, s->md.N);
         s->last_loss[i] = orc_mlp_loss_grad(&s->md, x, s->data, s->labels, idx, g);
         free(idx);
     }

@@ -47,6 +47,7 @@ typedef struct {
     int E;                         /* evaluation subset: first E samples */
     float lr, beta, wd;            /* eta, momentum factor, weight decay */
     int bf16;                      /* 1: bf16 operands in the training GEMMs */
+    int sampler;                   /* 0: with replacement from the whole set; 1: per-worker partition, reshuffled every epoch */
 } orc_model;
 
 typedef struct orc_state orc_state;
@@ -60,6 +61,14 @@ uint64_t orc_mix64(uint64_t z);
  * from 0) is drawn with replacement from the whole dataset (Sec. 2, "randomly
  * sampled mini-batch", one stream per worker as in the tau=1 special case). */
 int64_t orc_index(uint64_t seed, int i, int64_t k, int b, int64_t N);
+
+/* Partition sampler (Sec. 5.1, "Dataset": each worker is assigned a partition which is randomly
+ * shuffled after every epoch).  Worker i of m owns samples [floor(i N / m), floor((i+1) N / m));
+ * an epoch is S = floor(min_i n_i / B) iterations; in epoch e = k / S the worker walks a pseudo-random
+ * permutation of its partition (4-round Feistel network keyed by seed, worker and epoch, with cycle
+ * walking), B positions per iteration.  Returns the dataset index, or -1 if a partition is smaller
+ * than one batch. */
+int64_t orc_index_partition(uint64_t seed, int i, int64_t k, int b, int64_t N, int m, int B);
 
 /* fp32 -> nearest bfloat16 value (ties to even), returned as fp32. */
 float orc_bf16_round(float x);

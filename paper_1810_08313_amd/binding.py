@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(HERE, "liblocalcomm.so")
 MAX_LAYERS = 8
 KIND_QUAD, KIND_MLP = 0, 1
 GEMM_FP32, GEMM_BF16 = 0, 1
+SAMPLE_REPLACEMENT, SAMPLE_PARTITION = 0, 1
 TIME_BWD, TIME_FWD, TIME_AVG, TIME_UPD, TIME_UPDAVG, TIME_NONE = 0, 1, 2, 3, 4, -1
 
 
@@ -33,6 +34,7 @@ class LcModel(C.Structure):
         ("beta", C.c_float),
         ("wd", C.c_float),
         ("gemm", C.c_int32),
+        ("sampler", C.c_int32),
     ]
 
 
@@ -133,8 +135,9 @@ def _strerror(status: int) -> str:
 
 
 def make_model(kind: int, dims: Sequence[int], B: int = 1, N: int = 1, E: int = 1, lr: float = 0.1,
-               beta: float = 0.0, wd: float = 0.0, bf16: bool = False) -> LcModel:
+               beta: float = 0.0, wd: float = 0.0, bf16: bool = False, sampler: int = 0) -> LcModel:
     md = LcModel()
+    md.sampler = int(sampler)
     md.kind = kind
     md.n_layers = len(dims) - 1 if kind == KIND_MLP else 0
     for j, d in enumerate(dims):

@@ -62,6 +62,7 @@ int model_ok(const lc_model* md) {
     if (md->N < 1 || md->N > 2147483647LL) return LC_ERR_MODEL;
     if (md->E < 1 || md->E > md->N) return LC_ERR_MODEL;
     if (md->gemm != LC_GEMM_FP32 && md->gemm != LC_GEMM_BF16) return LC_ERR_MODEL;
+    if (md->sampler != LC_SAMPLE_REPLACEMENT && md->sampler != LC_SAMPLE_PARTITION) return LC_ERR_MODEL;
     return LC_OK;
 }
 
@@ -207,6 +208,7 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     const int64_t want = lc_param_count(md);
     if (want < 0) return static_cast<int>(want);
     if (P != want) return LC_ERR_MODEL;
+    if (md->kind == LC_KIND_MLP && md->sampler == LC_SAMPLE_PARTITION && md->N / m < md->B) return LC_ERR_MODEL;
     lc_handle* h = new (std::nothrow) lc_handle();
     if (!h) return LC_ERR_ARG;
     h->m = m;

@@ -157,6 +157,37 @@ __device__ __forceinline__ int64_t batch_index(uint64_t seed, int i, int64_t k, 
     return static_cast<int64_t>(hsh % static_cast<uint64_t>(N));
 }
 
+// Partition sampler: bijection of [0, n) by a 4-round balanced Feistel network on 2w bits with
+// cycle walking.  The network permutes its 2w-bit domain, so a walk that starts below n returns
+// below n after finitely many rounds (fewer than four on average, as the domain is < 4 n).
+__device__ __forceinline__ uint64_t feistel_permute(uint64_t x, uint64_t n, uint64_t key) {
+    int w = 1;
+    while ((1ULL << (2 * w)) < n) ++w;
+    const uint64_t mask = (1ULL << w) - 1;
+    const uint64_t gamma = 0x9E3779B97F4A7C15ULL;
+    do {
+        uint64_t l = x >> w, r = x & mask;
+#pragma unroll
+        for (int round = 0; round < 4; ++round) {
+            const uint64_t f = mix64(key + gamma * static_cast<uint64_t>(round + 1) + r) & mask;
+            const uint64_t t = l ^ f;
+            l = r;
+            r = t;
+        }
+        x = (l << w) | r;
+    } while (x >= n);
+    return x;
+}
+__device__ __forceinline__ int64_t partition_index(uint64_t seed, int i, int64_t k, int b, int64_t N, int m, int B) {
+    const int64_t lo = static_cast<int64_t>(i) * N / m, hi = static_cast<int64_t>(i + 1) * N / m;
+    const int64_t S = (N / m) / B;   // >= 1, checked by lc_init
+    const int64_t epoch = k / S, pos = (k % S) * B + b;
+    const uint64_t gamma = 0x9E3779B97F4A7C15ULL;
+    uint64_t key = mix64(seed + gamma * (static_cast<uint64_t>(epoch) + 1));
+    key = mix64(key + gamma * (static_cast<uint64_t>(i) + 1));
+    return lo + static_cast<int64_t>(feistel_permute(static_cast<uint64_t>(pos), static_cast<uint64_t>(hi - lo), key));
+}
+
 // --------------------------------------------------------------------- gather
 
 struct GatherArgs {
@@ -172,6 +203,7 @@ struct GatherArgs {
     int64_t k;              // training: local iteration; evaluation: first sample of the pass
     int64_t limit;          // evaluation: samples >= limit are invalid
     int eval;
+    int sampler, m;         // training: lc_sampler and the number of workers
 };
 
 // One block copies a 32-sample x 64-feature tile through LDS and writes it in
@@ -190,7 +222,8 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
                 idx = a.k + static_cast<int64_t>(g) * a.B + b;
                 if (idx >= a.limit) idx = -1;
             } else {
-                idx = batch_index(a.seed, g, a.k, b, a.N);
+                idx = a.sampler ? partition_index(a.seed, g, a.k, b, a.N, a.m, a.B)
+                                : batch_index(a.seed, g, a.k, b, a.N);
             }
         }
         rows[t] = idx;
@@ -1008,6 +1041,8 @@ hipError_t launch_gather(lc_handle* h, bool eval, int64_t k_or_base) {
     a.k = k_or_base;
     a.limit = h->md.E;
     a.eval = eval ? 1 : 0;
+    a.sampler = h->md.sampler;
+    a.m = h->m;
     const dim3 grid(a.dp0 / 64, a.Bp / 32, S.G);
     if (eval) {
         if (bf16) hipLaunchKernelGGL((gather_kernel<bf16_t, float>), grid, dim3(256), 0, h->stream, a);

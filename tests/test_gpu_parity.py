@@ -142,6 +142,33 @@ def test_index_stream_bit_exact(pkg, orc):
     run.close()
 
 
+def test_partition_sampler_bit_exact_and_run(pkg, orc):
+    """Per-worker partitions reshuffled every epoch: the index stream of every worker
+    over more than two epochs, then a short run against the oracle."""
+    _say("partition sampler")
+    dims, m, B, N = [20, 12, 6], 5, 9, 203          # 40 or 41 samples per worker: 4 iterations per epoch
+    data, labels = synth.gaussian_mixture(3, N, dims[0], dims[-1], mean_sd=1.0)
+    x1 = synth.init_params(3, dims)
+    kw = dict(B=B, N=N, E=100, lr=0.05, beta=0.9, sampler=1)
+    ref = orc.Run(m, orc.make_model(orc.KIND_MLP, dims, **kw), 77, x1, data, labels)
+    run = pkg.LocalSGD(m, pkg.make_model(pkg.KIND_MLP, dims, **kw), 77, x1, data, labels)
+    for k in range(10):
+        run.local_steps(1)
+        want = np.array([[orc.index_partition(77, i, k, b, N, m, B) for b in range(B)] for i in range(m)], np.int32)
+        assert np.array_equal(run.last_indices(), want), k
+    ref.local_steps(10)
+    ref.average()
+    run.average()
+    X, V, kk = run.get_state()
+    assert kk == ref.k == 10
+    _assert_close(X, ref.X, dims, 3e-4, "X")
+    run.close()
+    L = pkg.lib()
+    h = C.c_void_p()
+    bad = pkg.make_model(pkg.KIND_MLP, dims, B=64, N=N, E=100, sampler=1)     # 40 samples per worker < 64
+    assert L.lc_init(m, pkg.lc_param_count(bad), C.byref(bad), 1, C.byref(h)) == -2
+
+
 # ------------------------------------------------------------------ averaging
 
 @pytest.mark.parametrize("m,P", [(1, 7), (3, 50), (5, 1000), (16, 70001), (64, 257), (7, 4096)])
