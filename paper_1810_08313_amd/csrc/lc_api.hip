@@ -115,7 +115,7 @@ size_t carve(lc_handle* h, char* base) {
         S.idx = static_cast<int32_t*>(c.take(sizeof(int32_t) * static_cast<size_t>(S.G) * S.Bp));
         const int per_pass = S.G * S.B;
         const int passes = eval ? (h->md.E + per_pass - 1) / per_pass : 1;
-        S.loss = static_cast<float*>(c.take(sizeof(float) * static_cast<size_t>(S.G) * passes));
+        S.loss = static_cast<float*>(c.take(sizeof(float) * static_cast<size_t>(S.G) * passes * kLossParts));
     }
     h->n_partial = 0;
     h->partial = nullptr;
@@ -255,6 +255,7 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     h->bm_beta = 0.f;
     h->v_cleared = false;
     h->lazy_enabled = h->lazy_rows = h->lazy_enabled_step = false;
+    h->loss_parts_train = h->loss_parts_eval = 1;
     (void)carve(h, nullptr);
     *out = h;
     return LC_OK;
@@ -409,7 +410,7 @@ int lc_loss(lc_handle* h, double* out) {
         const int per_pass = h->eval.G * h->eval.B;
         const int E = h->md.E;
         const int passes = (E + per_pass - 1) / per_pass;
-        const size_t n = static_cast<size_t>(h->eval.G) * passes;
+        const size_t n = static_cast<size_t>(h->eval.G) * passes * kLossParts;
         float* host = static_cast<float*>(malloc(sizeof(float) * n));
         if (!host) return LC_ERR_ARG;
         hipError_t e = hipSuccess;
@@ -425,7 +426,8 @@ int lc_loss(lc_handle* h, double* out) {
             h->last_hip = static_cast<int>(e);
             return LC_ERR_HIP;
         }
-        for (size_t g = 0; g < n; ++g) F += static_cast<double>(host[g]);
+        for (size_t g = 0; g < n; g += kLossParts)
+            for (int q = 0; q < h->loss_parts_eval; ++q) F += static_cast<double>(host[g + q]);
         free(host);
         F /= static_cast<double>(E);
     }
@@ -651,8 +653,22 @@ int lc_get_local_losses(lc_handle* h, float* losses_host) {
     if (!h || !losses_host) return LC_ERR_ARG;
     if (!h->attached) return LC_ERR_STATE;
     if (h->md.kind != LC_KIND_MLP) return LC_ERR_UNSUPPORTED;
-    LC_HIP(h, hipMemcpyAsync(losses_host, h->train.loss, sizeof(float) * static_cast<size_t>(h->m), hipMemcpyDeviceToHost, h->stream));
-    LC_HIP(h, hipStreamSynchronize(h->stream));
+    float* parts = static_cast<float*>(malloc(sizeof(float) * static_cast<size_t>(h->m) * kLossParts));
+    if (!parts) return LC_ERR_ARG;
+    hipError_t e = hipMemcpyAsync(parts, h->train.loss, sizeof(float) * static_cast<size_t>(h->m) * kLossParts,
+                                  hipMemcpyDeviceToHost, h->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) {
+        free(parts);
+        h->last_hip = static_cast<int>(e);
+        return LC_ERR_HIP;
+    }
+    for (int i = 0; i < h->m; ++i) {
+        float sum = 0.f;
+        for (int q = 0; q < h->loss_parts_train; ++q) sum += parts[static_cast<size_t>(i) * kLossParts + q];
+        losses_host[i] = sum;
+    }
+    free(parts);
     return LC_OK;
 }
 

@@ -20,6 +20,7 @@ constexpr int kWave = 64;
 constexpr int kColChunk = 64;   // columns of W handled per wave and per loop trip
 constexpr int kRowsPerWave = 16;
 constexpr int kXcds = 8;
+constexpr int kLossParts = 8;    // partial loss sums per group (one per block that shares a group's batch)
 
 inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 
@@ -44,7 +45,7 @@ struct ActSet {
     void* dz_fm[LC_MAX_LAYERS + 1]; // dZ_l feature-major
     int32_t* labels;       // [G][Bp]
     int32_t* idx;          // [G][Bp]
-    float* loss;           // training: [G] batch means; evaluation: [passes][G] sums over valid rows
+    float* loss;           // [.. G][kLossParts] partial sums: training batch means, evaluation sums over valid rows
 };
 
 }  // namespace lc
@@ -79,6 +80,7 @@ struct lc_handle {
     // lazy broadcast: after an averaging step the rows of X are stale and every replica's model is
     // the single vector xbar, until the next local step (which writes every row) or a materialise
     bool lazy_enabled, lazy_rows;
+    int loss_parts_train, loss_parts_eval;   // how many of the kLossParts slots the last launch wrote
     bool lazy_enabled_step;   // set only while lc_average runs its reduce-only form
     double* partial;        // reduction partials
     int n_partial;

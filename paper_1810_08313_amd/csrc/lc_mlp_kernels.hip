@@ -306,6 +306,17 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
     const OT* A = static_cast<const OT*>(a.a_in) + (static_cast<int64_t>(g) * a.Bp + row0) * a.dp_in;
     const bool vec = a.vec != 0, stream = a.stream != 0;
 
+    // everything the epilogue needs from memory is requested now, so that it does not add
+    // dependent round trips after the reduction (these kernels are latency-bound when small)
+    __shared__ float bias_s[kColChunk];
+    if (threadIdx.x < kColChunk) {
+        const int c = c0 + threadIdx.x;
+        bias_s[threadIdx.x] = c < a.d_out ? a.X[g * a.x_stride + a.b_off + c] : 0.f;
+    }
+    int my_label = -1;
+    if (a.fuse_softmax && threadIdx.x < MT * 16 && row0 + threadIdx.x < a.B)
+        my_label = a.labels[static_cast<int64_t>(g) * a.Bp + row0 + threadIdx.x];
+
     f32x4 acc[MT][4];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -372,62 +383,63 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
 
     // epilogue: bias, ReLU, both layouts; only valid (b, c) are written so the
     // zero padding of the activation buffers is preserved
-    const float* bias = a.X + g * a.x_stride + a.b_off;
     const int nthr = NW * 64;
     if (a.last) {
         float* out = static_cast<float*>(a.out_bm) + static_cast<int64_t>(g) * a.Bp * a.dp_out;
         for (int e = threadIdx.x; e < MT * 16 * kColChunk; e += nthr) {
             const int bl = e / kColChunk, b = row0 + bl, c = c0 + e % kColChunk;
             if (b < a.B && c < a.d_out) {
-                const float z = red[bl][e % kColChunk] + bias[c];
+                const float z = red[bl][e % kColChunk] + bias_s[e % kColChunk];
                 out[static_cast<int64_t>(b) * a.dp_out + c] = z;
                 red[bl][e % kColChunk] = z;
             }
         }
         if (a.fuse_softmax) {
-            // all classes of a sample sit in this block's tile: loss and dZ_L here
+            // all classes of a sample sit in this block's tile: loss and dZ_L here, for the
+            // block's own samples; the loss is left as one partial sum per block
             __shared__ float lred[128];
             __syncthreads();
-            const int b = threadIdx.x;
+            const int t = threadIdx.x;
             float nll = 0.f;
-            if (b < 128) {
-                if (b < a.B) {
-                    const int y = a.labels[static_cast<int64_t>(g) * a.Bp + b];
-                    if (y >= 0) {
-                        const float* z = red[b];
-                        float zmax = z[0];
-                        for (int c = 1; c < a.d_out; ++c) zmax = fmaxf(zmax, z[c]);
-                        float sum = 0.f;
-                        for (int c = 0; c < a.d_out; ++c) sum += expf(z[c] - zmax);
-                        nll = -(z[y] - zmax - logf(sum));
-                        if (a.dz_bm) {
-                            OT* dbm = static_cast<OT*>(a.dz_bm) + (static_cast<int64_t>(g) * a.Bp + b) * a.dp_out;
-                            OT* dfm = static_cast<OT*>(a.dz_fm) + static_cast<int64_t>(g) * a.dp_out * a.Bp + b;
-                            const float inv = 1.f / sum, invB = 1.f / static_cast<float>(a.B);
-                            for (int c = 0; c < a.d_out; ++c) {
-                                const float pr = expf(z[c] - zmax) * inv;
-                                const OT d = static_cast<OT>((pr - (c == y ? 1.f : 0.f)) * invB);
-                                dbm[c] = d;
-                                dfm[static_cast<int64_t>(c) * a.Bp] = d;
-                            }
+            if (t < 128) {
+                const int b = row0 + t;
+                if (t < MT * 16 && b < a.B && my_label >= 0) {
+                    const int y = my_label;
+                    const float* z = red[t];
+                    float zmax = z[0];
+                    for (int c = 1; c < a.d_out; ++c) zmax = fmaxf(zmax, z[c]);
+                    float sum = 0.f;
+                    for (int c = 0; c < a.d_out; ++c) sum += expf(z[c] - zmax);
+                    nll = -(z[y] - zmax - logf(sum));
+                    if (a.dz_bm) {
+                        OT* dbm = static_cast<OT*>(a.dz_bm) + (static_cast<int64_t>(g) * a.Bp + b) * a.dp_out;
+                        OT* dfm = static_cast<OT*>(a.dz_fm) + static_cast<int64_t>(g) * a.dp_out * a.Bp + b;
+                        const float inv = 1.f / sum, invB = 1.f / static_cast<float>(a.B);
+                        for (int c = 0; c < a.d_out; ++c) {
+                            const float pr = expf(z[c] - zmax) * inv;
+                            const OT d = static_cast<OT>((pr - (c == y ? 1.f : 0.f)) * invB);
+                            dbm[c] = d;
+                            dfm[static_cast<int64_t>(c) * a.Bp] = d;
                         }
                     }
                 }
-                lred[b] = nll;
+                lred[t] = nll;
             }
             __syncthreads();
             for (int w = 64; w > 0; w >>= 1) {
-                if (b < w) lred[b] += lred[b + w];
+                if (t < w) lred[t] += lred[t + w];
                 __syncthreads();
             }
-            if (b == 0) a.loss[g] = a.eval ? lred[0] : lred[0] / static_cast<float>(a.B);
+            if (t == 0)
+                a.loss[static_cast<int64_t>(g) * kLossParts + rem % a.m_split] =
+                    a.eval ? lred[0] : lred[0] / static_cast<float>(a.B);
         }
     } else {
         OT* obm = static_cast<OT*>(a.out_bm) + static_cast<int64_t>(g) * a.Bp * a.dp_out;
         for (int e = threadIdx.x; e < MT * 16 * kColChunk; e += nthr) {
             const int bl = e / kColChunk, b = row0 + bl, c = c0 + e % kColChunk;
             if (b < a.B && c < a.d_out) {
-                const float z = red[bl][e % kColChunk] + bias[c];
+                const float z = red[bl][e % kColChunk] + bias_s[e % kColChunk];
                 obm[static_cast<int64_t>(b) * a.dp_out + c] = static_cast<OT>(z > 0.f ? z : 0.f);
             }
         }
@@ -436,7 +448,7 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
             for (int e = threadIdx.x; e < MT * 16 * kColChunk; e += nthr) {
                 const int cl = e / (MT * 16), bl = e % (MT * 16), b = row0 + bl, c = c0 + cl;
                 if (b < a.B && c < a.d_out) {
-                    const float z = red[bl][cl] + bias[c];
+                    const float z = red[bl][cl] + bias_s[cl];
                     ofm[static_cast<int64_t>(c) * a.Bp + b] = static_cast<OT>(z > 0.f ? z : 0.f);
                 }
             }
@@ -490,7 +502,7 @@ __global__ __launch_bounds__(128) void softmax_kernel(SoftmaxArgs a) {
         if (b < w) red[b] += red[b + w];
         __syncthreads();
     }
-    if (b == 0) a.loss[g] = a.eval ? red[0] : red[0] / static_cast<float>(a.B);
+    if (b == 0) a.loss[static_cast<int64_t>(g) * kLossParts] = a.eval ? red[0] : red[0] / static_cast<float>(a.B);
 }
 
 // ------------------------------------------------------------------- backward
@@ -590,6 +602,16 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
 #pragma unroll
     for (int s = 0; s < NS; ++s) af[s] = load8(AT + static_cast<int64_t>(k0 + j) * Bp + 32 * s + 8 * q);
 
+    // ReLU gates of this lane's dA entries, fetched now (one bit each) instead of after the walk
+    uint32_t gate = 0;
+    if (need_da) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (to_f32(AT[static_cast<int64_t>(k0 + 4 * q + r) * Bp + 16 * nt + j]) > 0.f) gate |= 1u << (nt * 4 + r);
+    }
+
     float4 w[4], v[4], wn[4], vn[4];
     Frag<OT> st_t[NS], st_b[NS];   // staging registers for the dZ^T and dZ slices
 
@@ -645,13 +667,14 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         // bias of these 64 columns: db_l = sum_b dZ_l from the staged slice, then the
         // same update (first row block of the replica; one thread per column)
         if (rb == 0 && tid < kColChunk && c0 + tid < a.d_out) {
+            float* bx = a.X + g * a.x_stride + a.b_off + c0 + tid;
+            float* bv = a.V + g * a.x_stride + a.b_off + c0 + tid;
+            const float x = a.Xr[g * a.xr_stride + a.b_off + c0 + tid];   // requested before the sum below
+            const float v0 = *bv;
             const OT* zr = dzt_lds[(tid & 3) * 16 + (tid >> 2)];
             float sb = 0.f;
             for (int b = 0; b < a.B; ++b) sb += to_f32(zr[b]);
-            float* bx = a.X + g * a.x_stride + a.b_off + c0 + tid;
-            float* bv = a.V + g * a.x_stride + a.b_off + c0 + tid;
-            const float x = a.Xr[g * a.xr_stride + a.b_off + c0 + tid];
-            const float vb = a.beta * *bv + (sb + a.wd * x);
+            const float vb = a.beta * v0 + (sb + a.wd * x);
             *bv = vb;
             *bx = x - a.lr * vb;
         }
@@ -728,8 +751,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int row = k0 + 4 * q + r;
-                const float act = to_f32(AT[static_cast<int64_t>(row) * Bp + b]);
-                d[r] = act > 0.f ? dacc[nt][r] : 0.f;
+                d[r] = ((gate >> (nt * 4 + r)) & 1u) ? dacc[nt][r] : 0.f;
                 pfm[static_cast<int64_t>(row) * Bp + b] = static_cast<OT>(d[r]);
             }
             store4<OT>(pbm + static_cast<int64_t>(b) * a.dp_in + k0 + 4 * q, d[0], d[1], d[2], d[3]);
@@ -894,7 +916,7 @@ __global__ __launch_bounds__(512) void head_kernel(HeadArgs a) {
             if (b < w) lred[b] += lred[b + w];
             __syncthreads();
         }
-        if (b == 0) a.loss[g] = lred[0] / static_cast<float>(a.B);
+        if (b == 0) a.loss[static_cast<int64_t>(g) * kLossParts] = lred[0] / static_cast<float>(a.B);
     }
 
     // ---- phase 3: backward of the layer.  Bias first (one thread per class) ...
@@ -1082,16 +1104,16 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     a.labels = S.labels;
     a.dz_bm = eval ? nullptr : S.dz_bm[h->L];
     a.dz_fm = eval ? nullptr : S.dz_fm[h->L];
-    a.loss = S.loss + loss_offset;
+    a.loss = S.loss + static_cast<int64_t>(loss_offset) * kLossParts;
     a.eval = eval ? 1 : 0;
     // batch tiles per block: all of them, unless that leaves most of the chip idle
     int mt = mt_for(S.Bp);
     a.m_split = 1;
-    if (!a.fuse_softmax)
-        while (mt > 1 && static_cast<int64_t>(S.G) * a.n_chunks * a.m_split < 256) {
-            mt /= 2;
-            a.m_split *= 2;
-        }
+    while (mt > 1 && static_cast<int64_t>(S.G) * a.n_chunks * a.m_split < 256) {
+        mt /= 2;
+        a.m_split *= 2;
+    }
+    if (a.fuse_softmax) (eval ? h->loss_parts_eval : h->loss_parts_train) = a.m_split;
     a.total_blocks = static_cast<int64_t>(S.G) * a.n_chunks * a.m_split;
     const unsigned grid = xcd_grid(a.total_blocks);
     // few blocks: split the reduction over more wavefronts per block
@@ -1137,6 +1159,7 @@ hipError_t launch_head(lc_handle* h) {
     a.dzp_bm = L > 1 ? S.dz_bm[L - 1] : nullptr;
     a.dzp_fm = L > 1 ? S.dz_fm[L - 1] : nullptr;
     a.loss = S.loss;
+    h->loss_parts_train = 1;
     a.lr = h->md.lr;
     a.beta = effective_beta(h);
     a.wd = h->md.wd;
@@ -1166,7 +1189,8 @@ hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset) {
     a.labels = S.labels;
     a.dz_bm = eval ? nullptr : S.dz_bm[h->L];
     a.dz_fm = eval ? nullptr : S.dz_fm[h->L];
-    a.loss = S.loss + loss_offset;
+    a.loss = S.loss + static_cast<int64_t>(loss_offset) * kLossParts;
+    (eval ? h->loss_parts_eval : h->loss_parts_train) = 1;
     a.C = h->layer[h->L].d_out;
     a.dpL = h->layer[h->L].dp_out;
     a.B = S.B;
