@@ -103,16 +103,19 @@ size_t carve(lc_handle* h, char* base) {
             S.B = h->md.B;
             S.Bp = padded_batch(h->md.B);
         }
+        S.slots = eval ? 1 : kGatherSlots;
+        S.cur_slot = 0;
         for (int l = 0; l <= L; ++l) {
             const size_t dp = static_cast<size_t>(l == 0 ? h->layer[1].dp_in : h->layer[l].dp_out);
             const size_t n = static_cast<size_t>(S.G) * S.Bp * dp;
-            S.a_bm[l] = c.take(n * (l == L ? 4 : es));
-            S.a_fm[l] = (!eval && l < L) ? c.take(n * es) : nullptr;
+            const size_t copies = l == 0 ? static_cast<size_t>(S.slots) : 1;
+            S.a_bm[l] = c.take(n * (l == L ? 4 : es) * copies);
+            S.a_fm[l] = (!eval && l < L) ? c.take(n * es * copies) : nullptr;
             S.dz_bm[l] = (!eval && l >= 1) ? c.take(n * es) : nullptr;
             S.dz_fm[l] = (!eval && l >= 1) ? c.take(n * es) : nullptr;
         }
-        S.labels = static_cast<int32_t*>(c.take(sizeof(int32_t) * static_cast<size_t>(S.G) * S.Bp));
-        S.idx = static_cast<int32_t*>(c.take(sizeof(int32_t) * static_cast<size_t>(S.G) * S.Bp));
+        S.labels = static_cast<int32_t*>(c.take(sizeof(int32_t) * static_cast<size_t>(S.G) * S.Bp * S.slots));
+        S.idx = static_cast<int32_t*>(c.take(sizeof(int32_t) * static_cast<size_t>(S.G) * S.Bp * S.slots));
         const int per_pass = S.G * S.B;
         const int passes = eval ? (h->md.E + per_pass - 1) / per_pass : 1;
         S.loss = static_cast<float*>(c.take(sizeof(float) * static_cast<size_t>(S.G) * passes * kLossParts));
@@ -150,7 +153,7 @@ int one_local_step(lc_handle* h) {
         if (rc != LC_OK) return rc;
         LC_HIP(h, launch_quad_step(h));
     } else {
-        LC_HIP(h, launch_gather(h, false, h->k));
+        // (the mini-batch of this step was gathered into slot train.cur_slot by lc_local_steps)
         // layer L first in the backward sweep: dZ_{l-1} is produced from W_l before W_l
         // is overwritten inside the same kernel, and kernels run in stream order
         if (head_is_fused(h)) {
@@ -308,9 +311,16 @@ int lc_local_steps(lc_handle* h, int tau) {
     const int rc = require_objective(h);
     if (rc != LC_OK) return rc;
     if (tau < 1) return LC_ERR_ARG;
-    for (int t = 0; t < tau; ++t) {
-        const int r = one_local_step(h);
-        if (r != LC_OK) return r;
+    for (int t0 = 0; t0 < tau; t0 += kGatherSlots) {
+        const int n = tau - t0 < kGatherSlots ? tau - t0 : kGatherSlots;
+        // mini-batch selection does not depend on the weights: one launch prepares the inputs
+        // of the next n steps
+        if (h->md.kind == LC_KIND_MLP) LC_HIP(h, launch_gather(h, false, h->k, n));
+        for (int t = 0; t < n; ++t) {
+            h->train.cur_slot = t;
+            const int r = one_local_step(h);
+            if (r != LC_OK) return r;
+        }
     }
     return LC_OK;
 }
@@ -415,7 +425,7 @@ int lc_loss(lc_handle* h, double* out) {
         if (!host) return LC_ERR_ARG;
         hipError_t e = hipSuccess;
         for (int p = 0; p < passes && e == hipSuccess; ++p) {
-            e = launch_gather(h, true, static_cast<int64_t>(p) * per_pass);
+            e = launch_gather(h, true, static_cast<int64_t>(p) * per_pass, 1);
             for (int l = 1; l <= h->L && e == hipSuccess; ++l) e = launch_forward(h, true, l, p * h->eval.G);
             if (e == hipSuccess && !forward_fuses_softmax(h)) e = launch_softmax(h, true, p * h->eval.G);
         }
@@ -677,7 +687,8 @@ int lc_get_last_indices(lc_handle* h, int32_t* idx_host) {
     if (!h->attached) return LC_ERR_STATE;
     if (h->md.kind != LC_KIND_MLP) return LC_ERR_UNSUPPORTED;
     const size_t row = sizeof(int32_t) * static_cast<size_t>(h->train.B), pitch = sizeof(int32_t) * static_cast<size_t>(h->train.Bp);
-    LC_HIP(h, hipMemcpy2DAsync(idx_host, row, h->train.idx, pitch, row, h->m, hipMemcpyDeviceToHost, h->stream));
+    const int32_t* src = h->train.idx + static_cast<size_t>(h->train.cur_slot) * h->train.G * h->train.Bp;
+    LC_HIP(h, hipMemcpy2DAsync(idx_host, row, src, pitch, row, h->m, hipMemcpyDeviceToHost, h->stream));
     LC_HIP(h, hipStreamSynchronize(h->stream));
     return LC_OK;
 }

@@ -20,6 +20,7 @@ constexpr int kWave = 64;
 constexpr int kColChunk = 64;   // columns of W handled per wave and per loop trip
 constexpr int kRowsPerWave = 16;
 constexpr int kXcds = 8;
+constexpr int kGatherSlots = 8;  // local steps whose mini-batches one gather launch prepares
 constexpr int kLossParts = 8;    // partial loss sums per group (one per block that shares a group's batch)
 
 inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
@@ -43,8 +44,9 @@ struct ActSet {
     void* a_fm[LC_MAX_LAYERS + 1];  // A_l feature-major [G][dp_l][Bp]   (training only, l < L)
     void* dz_bm[LC_MAX_LAYERS + 1]; // dZ_l batch-major  (training only, l >= 1)
     void* dz_fm[LC_MAX_LAYERS + 1]; // dZ_l feature-major
-    int32_t* labels;       // [G][Bp]
-    int32_t* idx;          // [G][Bp]
+    int32_t* labels;       // [slots][G][Bp]
+    int32_t* idx;          // [slots][G][Bp]
+    int slots, cur_slot;   // training keeps the inputs of several consecutive steps (A_0, labels, indices)
     float* loss;           // [.. G][kLossParts] partial sums: training batch means, evaluation sums over valid rows
 };
 
@@ -102,7 +104,7 @@ hipError_t launch_update_and_average(lc_handle* h);
 hipError_t launch_quad_step(lc_handle* h);
 hipError_t launch_quad_loss(lc_handle* h, int* n_partial);
 
-hipError_t launch_gather(lc_handle* h, bool eval, int64_t k_or_base);
+hipError_t launch_gather(lc_handle* h, bool eval, int64_t k_or_base, int n_steps);
 hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset);
 bool forward_fuses_softmax(const lc_handle* h);  // last layer's kernel also does a3
 hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset);

@@ -204,15 +204,19 @@ struct GatherArgs {
     int64_t limit;          // evaluation: samples >= limit are invalid
     int eval;
     int sampler, m;         // training: lc_sampler and the number of workers
+    int G;                  // groups per step; blockIdx.z = step * G + group
+    int64_t a_slot, lab_slot;  // elements between the buffers of consecutive steps
 };
 
 // One block copies a 32-sample x 64-feature tile through LDS and writes it in
-// both layouts.  grid = (dp0/64, Bp/32, G).
+// both layouts.  grid = (dp0/64, Bp/32, G * steps): one launch prepares the
+// mini-batches of several consecutive local iterations.
 template <typename DT, typename OT>
 __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
     __shared__ float tile[32][65];
     __shared__ int64_t rows[32];
-    const int g = blockIdx.z, b0 = blockIdx.y * 32, k0 = blockIdx.x * 64;
+    const int g = blockIdx.z % a.G, step = blockIdx.z / a.G;
+    const int b0 = blockIdx.y * 32, k0 = blockIdx.x * 64;
     const int t = threadIdx.x;
     if (t < 32) {
         const int b = b0 + t;
@@ -222,13 +226,13 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
                 idx = a.k + static_cast<int64_t>(g) * a.B + b;
                 if (idx >= a.limit) idx = -1;
             } else {
-                idx = a.sampler ? partition_index(a.seed, g, a.k, b, a.N, a.m, a.B)
-                                : batch_index(a.seed, g, a.k, b, a.N);
+                idx = a.sampler ? partition_index(a.seed, g, a.k + step, b, a.N, a.m, a.B)
+                                : batch_index(a.seed, g, a.k + step, b, a.N);
             }
         }
         rows[t] = idx;
         if (blockIdx.x == 0) {
-            const int64_t o = static_cast<int64_t>(g) * a.Bp + b;
+            const int64_t o = step * a.lab_slot + static_cast<int64_t>(g) * a.Bp + b;
             a.idx_out[o] = static_cast<int32_t>(idx);
             a.lab_out[o] = idx >= 0 ? a.labels[idx] : -1;
         }
@@ -245,14 +249,14 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
         }
     }
     __syncthreads();
-    OT* bm = static_cast<OT*>(a.a_bm) + static_cast<int64_t>(g) * a.Bp * a.dp0;
+    OT* bm = static_cast<OT*>(a.a_bm) + step * a.a_slot + static_cast<int64_t>(g) * a.Bp * a.dp0;
     {
         const int r = t >> 3, seg = (t & 7) * 8;
 #pragma unroll
         for (int e = 0; e < 8; ++e) bm[static_cast<int64_t>(b0 + r) * a.dp0 + k0 + seg + e] = static_cast<OT>(tile[r][seg + e]);
     }
     if (a.a_fm) {
-        OT* fm = static_cast<OT*>(a.a_fm) + static_cast<int64_t>(g) * a.dp0 * a.Bp;
+        OT* fm = static_cast<OT*>(a.a_fm) + step * a.a_slot + static_cast<int64_t>(g) * a.dp0 * a.Bp;
         const int kk = t >> 2, seg = (t & 3) * 8;
 #pragma unroll
         for (int e = 0; e < 8; ++e) fm[static_cast<int64_t>(k0 + kk) * a.Bp + b0 + seg + e] = static_cast<OT>(tile[seg + e][kk]);
@@ -1044,7 +1048,19 @@ inline unsigned xcd_grid(int64_t total) { return static_cast<unsigned>((total + 
 
 }  // namespace
 
-hipError_t launch_gather(lc_handle* h, bool eval, int64_t k_or_base) {
+// Input buffers of the training step in progress (slot train.cur_slot).
+inline size_t a0_slot_elems(const lc_handle* h, const ActSet& S) {
+    return static_cast<size_t>(S.G) * S.Bp * h->layer[1].dp_in;
+}
+inline const void* a0_ptr(const lc_handle* h, const ActSet& S, const void* base, bool eval) {
+    const size_t es = (!eval && h->md.gemm == LC_GEMM_BF16) ? 2 : 4;
+    return static_cast<const char*>(base) + static_cast<size_t>(S.cur_slot) * a0_slot_elems(h, S) * es;
+}
+inline const int32_t* labels_ptr(const ActSet& S) {
+    return S.labels + static_cast<size_t>(S.cur_slot) * S.G * S.Bp;
+}
+
+hipError_t launch_gather(lc_handle* h, bool eval, int64_t k_or_base, int n_steps) {
     const ActSet& S = eval ? h->eval : h->train;
     const bool bf16 = h->md.gemm == LC_GEMM_BF16;
     GatherArgs a;
@@ -1065,7 +1081,10 @@ hipError_t launch_gather(lc_handle* h, bool eval, int64_t k_or_base) {
     a.eval = eval ? 1 : 0;
     a.sampler = h->md.sampler;
     a.m = h->m;
-    const dim3 grid(a.dp0 / 64, a.Bp / 32, S.G);
+    a.G = S.G;
+    a.a_slot = static_cast<int64_t>(a0_slot_elems(h, S));
+    a.lab_slot = static_cast<int64_t>(S.G) * S.Bp;
+    const dim3 grid(a.dp0 / 64, a.Bp / 32, S.G * n_steps);
     if (eval) {
         if (bf16) hipLaunchKernelGGL((gather_kernel<bf16_t, float>), grid, dim3(256), 0, h->stream, a);
         else hipLaunchKernelGGL((gather_kernel<float, float>), grid, dim3(256), 0, h->stream, a);
@@ -1092,7 +1111,7 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     a.dp_out = g.dp_out;
     a.B = S.B;
     a.Bp = S.Bp;
-    a.a_in = S.a_bm[l - 1];
+    a.a_in = l == 1 ? a0_ptr(h, S, S.a_bm[0], eval) : S.a_bm[l - 1];
     a.out_bm = S.a_bm[l];
     a.out_fm = S.a_fm[l];
     a.last = l == h->L ? 1 : 0;
@@ -1101,7 +1120,7 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     a.n_chunks = g.dp_out / kColChunk;
     // softmax cross-entropy rides in the epilogue when one block sees all classes of all samples
     a.fuse_softmax = (a.last && g.d_out <= kColChunk) ? 1 : 0;
-    a.labels = S.labels;
+    a.labels = labels_ptr(S);
     a.dz_bm = eval ? nullptr : S.dz_bm[h->L];
     a.dz_fm = eval ? nullptr : S.dz_fm[h->L];
     a.loss = S.loss + static_cast<int64_t>(loss_offset) * kLossParts;
@@ -1152,9 +1171,9 @@ hipError_t launch_head(lc_handle* h) {
     a.dp_in = g.dp_in;
     a.dp_out = g.dp_out;
     a.B = S.B;
-    a.a_bm = S.a_bm[L - 1];
-    a.a_fm = S.a_fm[L - 1];
-    a.labels = S.labels;
+    a.a_bm = L == 1 ? a0_ptr(h, S, S.a_bm[0], false) : S.a_bm[L - 1];
+    a.a_fm = L == 1 ? a0_ptr(h, S, S.a_fm[0], false) : S.a_fm[L - 1];
+    a.labels = labels_ptr(S);
     a.logits = static_cast<float*>(S.a_bm[L]);
     a.dzp_bm = L > 1 ? S.dz_bm[L - 1] : nullptr;
     a.dzp_fm = L > 1 ? S.dz_fm[L - 1] : nullptr;
@@ -1186,7 +1205,7 @@ hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset) {
     const bool bf16 = !eval && h->md.gemm == LC_GEMM_BF16;
     SoftmaxArgs a;
     a.logits = static_cast<const float*>(S.a_bm[h->L]);
-    a.labels = S.labels;
+    a.labels = labels_ptr(S);
     a.dz_bm = eval ? nullptr : S.dz_bm[h->L];
     a.dz_fm = eval ? nullptr : S.dz_fm[h->L];
     a.loss = S.loss + static_cast<int64_t>(loss_offset) * kLossParts;
@@ -1219,8 +1238,8 @@ hipError_t launch_backward(lc_handle* h, int l) {
     a.dp_out = g.dp_out;
     a.B = S.B;
     a.Bp = S.Bp;
-    a.a_bm = S.a_bm[l - 1];
-    a.a_fm = S.a_fm[l - 1];
+    a.a_bm = l == 1 ? a0_ptr(h, S, S.a_bm[0], false) : S.a_bm[l - 1];
+    a.a_fm = l == 1 ? a0_ptr(h, S, S.a_fm[0], false) : S.a_fm[l - 1];
     a.dz_bm = S.dz_bm[l];
     a.dz_fm = S.dz_fm[l];
     a.dzp_bm = l > 1 ? S.dz_bm[l - 1] : nullptr;
