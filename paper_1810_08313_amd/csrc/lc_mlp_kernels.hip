@@ -61,6 +61,22 @@ __device__ __forceinline__ Frag<bf16_t> load8(const bf16_t* p) {
     return f;
 }
 
+// Marks the point where prefetched registers are consumed.  Without it the compiler moves the
+// conversion of a prefetched weight row up to its load, which makes every trip wait for the loads
+// it has just issued (loads retire in order) and turns the prefetch queue into a plain load.
+__device__ __forceinline__ void consume_here(float4& x) {
+    asm volatile("" : "+v"(x.x), "+v"(x.y), "+v"(x.z), "+v"(x.w));
+}
+__device__ __forceinline__ void consume_here(Frag<float>& f) {
+    asm volatile("" : "+v"(f.v[0]), "+v"(f.v[1]), "+v"(f.v[2]), "+v"(f.v[3]), "+v"(f.v[4]), "+v"(f.v[5]),
+                      "+v"(f.v[6]), "+v"(f.v[7]));
+}
+__device__ __forceinline__ void consume_here(Frag<bf16_t>& f) {
+    f32x4 t = __builtin_bit_cast(f32x4, f.v);
+    asm volatile("" : "+v"(t));
+    f.v = __builtin_bit_cast(bf16x8, t);
+}
+
 __device__ __forceinline__ void pack8(Frag<float>& f, const float (&x)[8]) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) f.v[e] = x[e];
@@ -123,6 +139,34 @@ __device__ __forceinline__ void store_w4(float* row, int c, int d_out, bool vec,
     if (c + 1 < d_out) row[c + 1] = v.y;
     if (c + 2 < d_out) row[c + 2] = v.z;
     if (c + 3 < d_out) row[c + 3] = v.w;
+}
+
+// Weight access mode of a kernel instance.  kWGeneric checks every element against the row end
+// (any d_out, any alignment).  The other two are for layers whose rows are 16-byte aligned and a
+// multiple of 64 columns long: every access is one unconditional 16-byte instruction, which lets
+// the compiler issue a trip's loads back to back with no control flow between them.
+constexpr int kWGeneric = 0, kWVector = 1, kWVectorStream = 2;
+
+template <int WM>
+__device__ __forceinline__ float4 load_wm(const float* row, int c, int d_out, bool vec) {
+    if constexpr (WM == kWVector) {
+        return *reinterpret_cast<const float4*>(row + c);
+    } else if constexpr (WM == kWVectorStream) {
+        const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(row + c));
+        return make_float4(t[0], t[1], t[2], t[3]);
+    } else {
+        return load_w4(row, c, d_out, vec, false);
+    }
+}
+template <int WM>
+__device__ __forceinline__ void store_wm(float* row, int c, int d_out, bool vec, float4 v) {
+    if constexpr (WM == kWVector) {
+        *reinterpret_cast<float4*>(row + c) = v;
+    } else if constexpr (WM == kWVectorStream) {
+        __builtin_nontemporal_store(f32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<f32x4*>(row + c));
+    } else {
+        store_w4(row, c, d_out, vec, false, v);
+    }
 }
 
 __device__ __forceinline__ void wave_sync_lds() {
@@ -287,15 +331,34 @@ struct FwdArgs {
     void* dz_fm;            // [G][dp_out][Bp] of OT or null
     float* loss;            // [G]
     int eval;               // 1: loss[g] = sum over valid samples; 0: mean over B
+    const void* a_in_fm;    // [G][dp_in][Bp] of OT: the same activations feature-major (AFM instances)
 };
 
 // One block = one replica x 64 output columns x MT batch tiles of 16 rows; its
 // NW wavefronts split the reduction over d_in and combine their partial tiles
 // in LDS.  Large models use MT = all batch tiles (every weight is read from
 // memory once); small ones split the batch over several blocks to fill the chip.
-template <typename OT, int MT, int NW>
+//
+// AFM instances (the block holds the whole padded batch, Bp = 16 MT) read the activations from
+// the feature-major copy.  The batch-major read hands each lane of an MFMA operand its 8
+// consecutive k of one batch row, so 16 lanes touch 16 different rows and every load
+// instruction costs the L1 sixteen cache-line lookups per 16 lanes; at B = 128 that takes about
+// as long as streaming the weights and does not overlap with it.  Feature-major, a lane reads 16
+// contiguous bytes of row k (VW = 8 bf16 or 4 fp32 batch entries), 16 lanes cover 256
+// contiguous bytes, and component t of the 8 vectors (k = 8q .. 8q+7) is the operand of tile t:
+// the same trick as for the weight columns.  Tile VW h + t then holds batch rows
+// 16 VW h + VW i + t (i = 0..15) instead of 16 mt + i; only the epilogue needs to know.
+template <typename OT, int MT, int NW, int PF, int WM, bool AFM>
 __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
-    __shared__ float red[MT * 16][kColChunk + 4];
+    constexpr int VW = 16 / sizeof(OT);
+    static_assert(!AFM || MT % VW == 0, "AFM needs whole groups of VW tiles");
+    // batch row (within the block) of accumulator row i of tile mt, and the inverse as the
+    // row of the LDS tile that holds batch row b
+    auto batch_row = [](int mt, int i) { return AFM ? 16 * VW * (mt / VW) + VW * i + mt % VW : 16 * mt + i; };
+    auto tile_row = [](int b) {
+        return AFM ? 16 * (VW * (b / (16 * VW)) + b % VW) + (b % (16 * VW)) / VW : b;
+    };
+    __shared__ __attribute__((aligned(16))) float part[NW][MT * 16][kColChunk + 4];   // one partial tile per wavefront
     const int64_t logical = xcd_logical_block(a.total_blocks);
     if (logical < 0) return;
     const int per_group = a.n_chunks * a.m_split;
@@ -308,7 +371,7 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
 
     const float* W = a.X + g * a.x_stride + a.w_off;
     const OT* A = static_cast<const OT*>(a.a_in) + (static_cast<int64_t>(g) * a.Bp + row0) * a.dp_in;
-    const bool vec = a.vec != 0, stream = a.stream != 0;
+    const bool vec = a.vec != 0;
 
     // everything the epilogue needs from memory is requested now, so that it does not add
     // dependent round trips after the reduction (these kernels are latency-bound when small)
@@ -318,8 +381,10 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
         bias_s[threadIdx.x] = c < a.d_out ? a.X[g * a.x_stride + a.b_off + c] : 0.f;
     }
     int my_label = -1;
-    if (a.fuse_softmax && threadIdx.x < MT * 16 && row0 + threadIdx.x < a.B)
-        my_label = a.labels[static_cast<int64_t>(g) * a.Bp + row0 + threadIdx.x];
+    if (a.fuse_softmax && threadIdx.x < MT * 16) {
+        const int b = row0 + batch_row(threadIdx.x / 16, threadIdx.x % 16);
+        if (b < a.B) my_label = a.labels[static_cast<int64_t>(g) * a.Bp + b];
+    }
 
     f32x4 acc[MT][4];
 #pragma unroll
@@ -327,63 +392,150 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    // The weight rows of the next PF steps are always in flight: the achieved bandwidth of this
+    // kernel is (bytes in flight) / (memory latency), and registers are the only place to hold them.
     const int n_steps = a.dp_in / 32;
-    for (int s = wave; s < n_steps; s += NW) {
-        const int k0 = s * 32 + 8 * q;
-        float4 w[8];
+    auto load_w_step = [&](int s, float4 (&w)[8]) {
+        if constexpr (WM == kWGeneric) {
+            const int k0 = s * 32 + 8 * q;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int row = k0 + e;
-            w[e] = row < a.d_in ? load_w4(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, stream)
-                                : make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int e = 0; e < 8; ++e) {
+                const int row = k0 + e;
+                w[e] = (s < n_steps && row < a.d_in)
+                           ? load_wm<WM>(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec)
+                           : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        } else {
+            // Rows past d_in meet activation columns that are zero, and steps past the end are
+            // never used: both are redirected to valid rows instead of being branched around.
+            const int k0 = (s < n_steps ? s : n_steps - 1) * 32 + 8 * q;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int row = k0 + e < a.d_in ? k0 + e : a.d_in - 1;
+                w[e] = load_wm<WM>(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec);
+            }
         }
-        Frag<OT> af[MT];
+    };
+    // Loads retire in issue order, so the activation fragments of step s are requested before the
+    // weight rows of the later steps: waiting for them then leaves those rows in flight.
+    const OT* AF = static_cast<const OT*>(a.a_in_fm) + static_cast<int64_t>(g) * a.dp_in * a.Bp;
+    auto load_a_step = [&](int s, Frag<OT> (&f)[MT]) {
+        const int k0 = (s < n_steps ? s : n_steps - 1) * 32 + 8 * q;   // past the end: any valid step, never used
+        if constexpr (!AFM) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) af[mt] = load8(A + static_cast<int64_t>(16 * mt + j) * a.dp_in + k0);
-        {
-            Frag<OT> bf;
-            float x[8];
+            for (int mt = 0; mt < MT; ++mt) f[mt] = load8(A + static_cast<int64_t>(16 * mt + j) * a.dp_in + k0);
+        } else if constexpr (sizeof(OT) == 4) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = w[e].x;
-            pack8(bf, x);
+            for (int h = 0; h < MT / 4; ++h)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][0] = mma8(af[mt], bf, acc[mt][0]);
+                for (int e = 0; e < 8; ++e) {
+                    const float4 x = *reinterpret_cast<const float4*>(AF + static_cast<int64_t>(k0 + e) * a.Bp + 64 * h + 4 * j);
+                    f[4 * h + 0].v[e] = x.x; f[4 * h + 1].v[e] = x.y; f[4 * h + 2].v[e] = x.z; f[4 * h + 3].v[e] = x.w;
+                }
+        } else {
+            // the fragments hold the raw vectors until transpose_a_step() runs at the point of use
 #pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = w[e].y;
-            pack8(bf, x);
+            for (int e = 0; e < 8; ++e) f[e] = load8(AF + static_cast<int64_t>(k0 + e) * a.Bp + 8 * j);
+        }
+    };
+    // bf16 AFM: f[e] holds k = 8q + e for batch entries 8j .. 8j+7; the operand of tile t wants
+    // batch entry 8j + t for e = 0..7, an 8 x 8 transpose of 16-bit values inside the lane
+    auto transpose_a_step = [&](Frag<OT> (&f)[MT]) {
+        if constexpr (AFM && sizeof(OT) == 2) {
+            u32x4 x[8], y[8];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][1] = mma8(af[mt], bf, acc[mt][1]);
+            for (int e = 0; e < 8; ++e) x[e] = __builtin_bit_cast(u32x4, f[e].v);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = w[e].z;
-            pack8(bf, x);
+            for (int t = 0; t < 8; ++t)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][2] = mma8(af[mt], bf, acc[mt][2]);
+                for (int d = 0; d < 4; ++d)   // dword d of tile t: (k = 2d, k = 2d + 1)
+                    y[t][d] = __builtin_amdgcn_perm(x[2 * d + 1][t / 2], x[2 * d][t / 2],
+                                                    (t & 1) ? 0x07060302u : 0x05040100u);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = w[e].w;
-            pack8(bf, x);
+            for (int t = 0; t < 8; ++t) f[t].v = __builtin_bit_cast(bf16x8, y[t]);
+        }
+    };
+    // The queue is addressed with compile-time indices (the loop body covers PF + 1 steps), so a
+    // register that a load is still filling is never copied.
+    static_assert((PF + 1) % 2 == 0, "the activation double buffer needs an even trip count");
+    float4 wq[PF + 1][8];
+    Frag<OT> af[2][MT];
+    auto multiply_step = [&](Frag<OT> (&f)[MT], float4 (&w)[8]) {
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][3] = mma8(af[mt], bf, acc[mt][3]);
+        for (int mt = 0; mt < MT; ++mt) consume_here(f[mt]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) consume_here(w[e]);
+        transpose_a_step(f);
+        Frag<OT> bf;
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = w[e].x;
+        pack8(bf, x);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt][0] = mma8(f[mt], bf, acc[mt][0]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = w[e].y;
+        pack8(bf, x);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt][1] = mma8(f[mt], bf, acc[mt][1]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = w[e].z;
+        pack8(bf, x);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt][2] = mma8(f[mt], bf, acc[mt][2]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = w[e].w;
+        pack8(bf, x);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt][3] = mma8(f[mt], bf, acc[mt][3]);
+    };
+    load_a_step(wave, af[0]);
+#pragma unroll
+    for (int p = 0; p < PF; ++p) load_w_step(wave + p * NW, wq[p]);
+    // Full groups of PF + 1 steps run without control flow (a branch inside would make the
+    // compiler drain all outstanding loads where the paths meet); the last few steps, whose
+    // weight rows are already in the queue, follow separately.
+    int s0 = wave;
+    for (; s0 + PF * NW < n_steps; s0 += NW * (PF + 1)) {
+#pragma unroll
+        for (int u = 0; u <= PF; ++u) {
+            const int s = s0 + u * NW;
+            load_a_step(s + NW, af[(u + 1) & 1]);
+            load_w_step(s + PF * NW, wq[(u + PF) % (PF + 1)]);
+            multiply_step(af[u & 1], wq[u]);
+            __builtin_amdgcn_sched_barrier(0);   // keep the next step's loads below this step's products
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+        const int s = s0 + u * NW;
+        if (s < n_steps) {   // uniform over the wavefront
+            load_a_step(s + NW, af[(u + 1) & 1]);
+            multiply_step(af[u & 1], wq[u]);
         }
     }
 
-    // combine the wavefronts' partial tiles in a fixed order
-    for (int w = 0; w < NW; ++w) {
-        if (wave == w) {
+    // combine the wavefronts' partial tiles: every wavefront parks its own, then all threads add
+    // them up in wavefront order (the order fixes the rounding) into the first one
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float4* p = reinterpret_cast<float4*>(&red[16 * mt + 4 * q + r][4 * j]);
-                    float4 v = make_float4(acc[mt][0][r], acc[mt][1][r], acc[mt][2][r], acc[mt][3][r]);
-                    if (w > 0) {
-                        const float4 o = *p;
-                        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
-                    }
-                    *p = v;
-                }
+        for (int r = 0; r < 4; ++r)
+            *reinterpret_cast<float4*>(&part[wave][16 * mt + 4 * q + r][4 * j]) =
+                make_float4(acc[mt][0][r], acc[mt][1][r], acc[mt][2][r], acc[mt][3][r]);
+    __syncthreads();
+    for (int f = threadIdx.x; f < MT * 16 * (kColChunk / 4); f += NW * 64) {
+        const int row = f / (kColChunk / 4), c4 = (f % (kColChunk / 4)) * 4;
+        float4 v = *reinterpret_cast<const float4*>(&part[0][row][c4]);
+#pragma unroll
+        for (int w = 1; w < NW; ++w) {
+            const float4 o = *reinterpret_cast<const float4*>(&part[w][row][c4]);
+            v.x = o.x + v.x; v.y = o.y + v.y; v.z = o.z + v.z; v.w = o.w + v.w;
         }
-        __syncthreads();
+        *reinterpret_cast<float4*>(&part[0][row][c4]) = v;
     }
+    __syncthreads();
+    float (&red)[MT * 16][kColChunk + 4] = part[0];
 
     // epilogue: bias, ReLU, both layouts; only valid (b, c) are written so the
     // zero padding of the activation buffers is preserved
@@ -391,7 +543,7 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
     if (a.last) {
         float* out = static_cast<float*>(a.out_bm) + static_cast<int64_t>(g) * a.Bp * a.dp_out;
         for (int e = threadIdx.x; e < MT * 16 * kColChunk; e += nthr) {
-            const int bl = e / kColChunk, b = row0 + bl, c = c0 + e % kColChunk;
+            const int bl = e / kColChunk, b = row0 + batch_row(bl / 16, bl % 16), c = c0 + e % kColChunk;
             if (b < a.B && c < a.d_out) {
                 const float z = red[bl][e % kColChunk] + bias_s[e % kColChunk];
                 out[static_cast<int64_t>(b) * a.dp_out + c] = z;
@@ -406,7 +558,7 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
             const int t = threadIdx.x;
             float nll = 0.f;
             if (t < 128) {
-                const int b = row0 + t;
+                const int b = row0 + batch_row(t / 16, t % 16);
                 if (t < MT * 16 && b < a.B && my_label >= 0) {
                     const int y = my_label;
                     const float* z = red[t];
@@ -441,7 +593,7 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
     } else {
         OT* obm = static_cast<OT*>(a.out_bm) + static_cast<int64_t>(g) * a.Bp * a.dp_out;
         for (int e = threadIdx.x; e < MT * 16 * kColChunk; e += nthr) {
-            const int bl = e / kColChunk, b = row0 + bl, c = c0 + e % kColChunk;
+            const int bl = e / kColChunk, b = row0 + batch_row(bl / 16, bl % 16), c = c0 + e % kColChunk;
             if (b < a.B && c < a.d_out) {
                 const float z = red[bl][e % kColChunk] + bias_s[e % kColChunk];
                 obm[static_cast<int64_t>(b) * a.dp_out + c] = static_cast<OT>(z > 0.f ? z : 0.f);
@@ -452,7 +604,7 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
             for (int e = threadIdx.x; e < MT * 16 * kColChunk; e += nthr) {
                 const int cl = e / (MT * 16), bl = e % (MT * 16), b = row0 + bl, c = c0 + cl;
                 if (b < a.B && c < a.d_out) {
-                    const float z = red[bl][cl] + bias_s[cl];
+                    const float z = red[tile_row(bl)][cl] + bias_s[cl];
                     ofm[static_cast<int64_t>(c) * a.Bp + b] = static_cast<OT>(z > 0.f ? z : 0.f);
                 }
             }
@@ -549,7 +701,7 @@ struct BwdArgs {
 // in memory; dA is complete when the wavefront has walked its rows, so nothing
 // is reduced across workgroups.  When dA is not needed (first layer) the
 // columns may additionally be split over several workgroups.
-template <typename OT, int NT>
+template <typename OT, int NT, int WM>
 __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
     constexpr int kPad = sizeof(OT) == 2 ? 8 : 4;
     constexpr int Bp = 16 * NT;
@@ -569,7 +721,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 15, q = lane >> 4;
     const int k0 = (rb * 4 + wave) * kRowsPerWave;   // < dp_in: the grid covers dp_in / 64 row blocks exactly
-    const bool vec = a.vec != 0, stream = a.stream != 0;
+    const bool vec = a.vec != 0;
     const bool need_da = a.dzp_bm != nullptr;
 
     float* W = a.X + g * a.x_stride + a.w_off;
@@ -624,11 +776,19 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int row = k0 + 4 * q + r;
-            if (row < a.d_in) {
-                ww[r] = load_w4(Wr + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, stream);
-                vv[r] = load_w4(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, stream);
+            if constexpr (WM == kWGeneric) {
+                if (row < a.d_in) {
+                    ww[r] = load_wm<WM>(Wr + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec);
+                    vv[r] = load_wm<WM>(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec);
+                } else {
+                    ww[r] = vv[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
             } else {
-                ww[r] = vv[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+                // rows past d_in read the last row instead (no branch between the loads); their
+                // weights are zeroed when used and they are never stored
+                const int rr = row < a.d_in ? row : a.d_in - 1;
+                ww[r] = load_wm<WM>(Wr + static_cast<int64_t>(rr) * a.d_out, c0 + 4 * j, a.d_out, vec);
+                vv[r] = load_wm<WM>(Vw + static_cast<int64_t>(rr) * a.d_out, c0 + 4 * j, a.d_out, vec);
             }
         }
         // the dZ^T slice is one contiguous run of 64 * Bp elements
@@ -697,7 +857,11 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         if (need_da) {
             // old weights, in operand precision, to LDS in natural column order
 #pragma unroll
-            for (int r = 0; r < 4; ++r) store4<OT>(&wlds[wave][4 * q + r][4 * j], w[r].x, w[r].y, w[r].z, w[r].w);
+            for (int r = 0; r < 4; ++r) {
+                const bool in = WM == kWGeneric || k0 + 4 * q + r < a.d_in;
+                store4<OT>(&wlds[wave][4 * q + r][4 * j], in ? w[r].x : 0.f, in ? w[r].y : 0.f, in ? w[r].z : 0.f,
+                           in ? w[r].w : 0.f);
+            }
         }
         // update and store
 #pragma unroll
@@ -713,8 +877,8 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
             w[r].z -= a.lr * v[r].z;
             w[r].w -= a.lr * v[r].w;
             if (row < a.d_in) {
-                store_w4(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, stream, v[r]);
-                store_w4(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, stream, w[r]);
+                store_wm<WM>(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, v[r]);
+                store_wm<WM>(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, w[r]);
             }
         }
         if (need_da) {
@@ -1019,27 +1183,55 @@ __global__ __launch_bounds__(512) void head_kernel(HeadArgs a) {
 
 // ------------------------------------------------------------------ dispatch
 
-template <typename OT, int NW>
-hipError_t launch_fwd_mt(const FwdArgs& a, int mt, unsigned grid, hipStream_t s) {
+// Rows that are 16-byte aligned and a whole number of 64-column chunks long need no per-element checks.
+int weight_mode(bool vec, bool stream, int d_out) {
+    if (!vec || d_out % kColChunk != 0) return kWGeneric;
+    return stream ? kWVectorStream : kWVector;
+}
+
+// Batch tiles per block (MT), wavefronts per block (NW) and weight steps kept in flight (PF).
+// The accumulators of a full 128-row batch leave no registers for prefetching at two
+// wavefronts per SIMD, so that case runs four wavefronts per block with a deeper queue.
+template <typename OT, int WM>
+hipError_t launch_fwd_cfg(const FwdArgs& a, int mt, bool wide, bool afm, unsigned grid, hipStream_t s) {
+#define LC_FWD(MT_, NW_, PF_, AFM_) \
+    hipLaunchKernelGGL((forward_kernel<OT, MT_, NW_, PF_, WM, AFM_>), dim3(grid), dim3(NW_ * 64), 0, s, a)
     switch (mt) {
-        case 1: hipLaunchKernelGGL((forward_kernel<OT, 1, NW>), dim3(grid), dim3(NW * 64), 0, s, a); break;
-        case 2: hipLaunchKernelGGL((forward_kernel<OT, 2, NW>), dim3(grid), dim3(NW * 64), 0, s, a); break;
-        case 4: hipLaunchKernelGGL((forward_kernel<OT, 4, NW>), dim3(grid), dim3(NW * 64), 0, s, a); break;
-        case 8: hipLaunchKernelGGL((forward_kernel<OT, 8, NW>), dim3(grid), dim3(NW * 64), 0, s, a); break;
+        case 1: if (wide) LC_FWD(1, 8, 3, false); else LC_FWD(1, 4, 3, false); break;
+        case 2: if (wide) LC_FWD(2, 8, 3, false); else LC_FWD(2, 4, 3, false); break;
+        case 4: if (wide) LC_FWD(4, 8, 1, false); else LC_FWD(4, 4, 3, false); break;
+        case 8: if (afm) LC_FWD(8, 4, 1, true); else LC_FWD(8, 4, 1, false); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef LC_FWD
+    return hipGetLastError();
+}
+template <typename OT>
+hipError_t launch_fwd_wm(const FwdArgs& a, int mt, bool wide, bool afm, unsigned grid, hipStream_t s) {
+    switch (weight_mode(a.vec != 0, a.stream != 0, a.d_out)) {
+        case kWVector: return launch_fwd_cfg<OT, kWVector>(a, mt, wide, afm, grid, s);
+        case kWVectorStream: return launch_fwd_cfg<OT, kWVectorStream>(a, mt, wide, afm, grid, s);
+        default: return launch_fwd_cfg<OT, kWGeneric>(a, mt, wide, afm, grid, s);
+    }
+}
+
+template <typename OT, int WM>
+hipError_t launch_bwd_nt(const BwdArgs& a, int nt, unsigned grid, hipStream_t s) {
+    switch (nt) {
+        case 2: hipLaunchKernelGGL((backward_kernel<OT, 2, WM>), dim3(grid), dim3(256), 0, s, a); break;
+        case 4: hipLaunchKernelGGL((backward_kernel<OT, 4, WM>), dim3(grid), dim3(256), 0, s, a); break;
+        case 8: hipLaunchKernelGGL((backward_kernel<OT, 8, WM>), dim3(grid), dim3(256), 0, s, a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
-
 template <typename OT>
-hipError_t launch_bwd_nt(const BwdArgs& a, int nt, unsigned grid, hipStream_t s) {
-    switch (nt) {
-        case 2: hipLaunchKernelGGL((backward_kernel<OT, 2>), dim3(grid), dim3(256), 0, s, a); break;
-        case 4: hipLaunchKernelGGL((backward_kernel<OT, 4>), dim3(grid), dim3(256), 0, s, a); break;
-        case 8: hipLaunchKernelGGL((backward_kernel<OT, 8>), dim3(grid), dim3(256), 0, s, a); break;
-        default: return hipErrorInvalidValue;
+hipError_t launch_bwd_wm(const BwdArgs& a, int nt, unsigned grid, hipStream_t s) {
+    switch (weight_mode(a.vec != 0, a.stream != 0, a.d_out)) {
+        case kWVector: return launch_bwd_nt<OT, kWVector>(a, nt, grid, s);
+        case kWVectorStream: return launch_bwd_nt<OT, kWVectorStream>(a, nt, grid, s);
+        default: return launch_bwd_nt<OT, kWGeneric>(a, nt, grid, s);
     }
-    return hipGetLastError();
 }
 
 inline int mt_for(int Bp) { return Bp / 16; }  // Bp is 32, 64 or 128
@@ -1139,8 +1331,12 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     const bool wide = a.total_blocks * 4 < 2048 && g.dp_in >= 512;
     if (!eval) timing_start(h, kTimeFwd);
     hipError_t e;
-    if (bf16) e = wide ? launch_fwd_mt<bf16_t, 8>(a, mt, grid, h->stream) : launch_fwd_mt<bf16_t, 4>(a, mt, grid, h->stream);
-    else e = wide ? launch_fwd_mt<float, 8>(a, mt, grid, h->stream) : launch_fwd_mt<float, 4>(a, mt, grid, h->stream);
+    // whole padded batch in one block and a feature-major copy of the input at hand
+    const void* in_fm = eval ? nullptr : (l == 1 ? a0_ptr(h, S, S.a_fm[0], false) : S.a_fm[l - 1]);
+    const bool afm = in_fm != nullptr && a.m_split == 1 && mt * 16 == S.Bp && mt == 8;
+    a.a_in_fm = in_fm;
+    if (bf16) e = launch_fwd_wm<bf16_t>(a, mt, wide, afm, grid, h->stream);
+    else e = launch_fwd_wm<float>(a, mt, wide, afm, grid, h->stream);
     if (!eval) timing_stop(h, kTimeFwd);
     return e;
 }
@@ -1260,8 +1456,8 @@ hipError_t launch_backward(lc_handle* h, int l) {
     a.total_blocks = static_cast<int64_t>(S.G) * a.n_row_blocks * a.col_split;
     const unsigned grid = xcd_grid(a.total_blocks);
     timing_start(h, kTimeBwd);
-    const hipError_t e = bf16 ? launch_bwd_nt<bf16_t>(a, S.Bp / 16, grid, h->stream)
-                              : launch_bwd_nt<float>(a, S.Bp / 16, grid, h->stream);
+    const hipError_t e = bf16 ? launch_bwd_wm<bf16_t>(a, S.Bp / 16, grid, h->stream)
+                              : launch_bwd_wm<float>(a, S.Bp / 16, grid, h->stream);
     timing_stop(h, kTimeBwd);
     return e;
 }

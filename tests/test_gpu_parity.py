@@ -123,6 +123,11 @@ SHAPES = [
     ([200, 128, 10], 3, 128),
     # more classes than one 64-column tile: separate softmax kernel, two-chunk last layer
     ([40, 50, 70], 2, 16),
+    # enough replicas x column tiles that one block keeps the whole 128-row batch (activations
+    # are then read feature-major, tiles hold interleaved batch rows), ragged batch
+    ([100, 512, 24, 10], 32, 120),
+    # the same in the last layer, with the loss and dZ_L formed in the forward epilogue
+    ([200, 10], 256, 128),
 ]
 
 
