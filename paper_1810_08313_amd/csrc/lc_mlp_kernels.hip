@@ -112,6 +112,18 @@ __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, float a, float b, floa
     *reinterpret_cast<bf16x4*>(p) = v;
 }
 
+// 8 consecutive outputs at a 16-byte aligned address
+__device__ __forceinline__ void store8(float* p, const float (&y)[8]) {
+    *reinterpret_cast<float4*>(p) = make_float4(y[0], y[1], y[2], y[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(y[4], y[5], y[6], y[7]);
+}
+__device__ __forceinline__ void store8(bf16_t* p, const float (&y)[8]) {
+    bf16x8 v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = static_cast<bf16_t>(y[i]);
+    *reinterpret_cast<bf16x8*>(p) = v;
+}
+
 // Four consecutive floats of a weight row, zero outside [0, d_out).  When the
 // state of all replicas is far larger than the caches, each weight is touched
 // once per kernel and the loads and stores carry the non-temporal hint; small
@@ -358,6 +370,7 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
     auto tile_row = [](int b) {
         return AFM ? 16 * (VW * (b / (16 * VW)) + b % VW) + (b % (16 * VW)) / VW : b;
     };
+    static_assert(NW * MT <= 32, "the partial tiles must fit in LDS (139 KB at 32 tiles)");
     __shared__ __attribute__((aligned(16))) float part[NW][MT * 16][kColChunk + 4];   // one partial tile per wavefront
     const int64_t logical = xcd_logical_block(a.total_blocks);
     if (logical < 0) return;
@@ -591,21 +604,45 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
                     a.eval ? lred[0] : lred[0] / static_cast<float>(a.B);
         }
     } else {
+        // 8 outputs per thread and pass, stored as one vector where all 8 are valid: along the
+        // columns for the batch-major copy, along the batch for the feature-major one
         OT* obm = static_cast<OT*>(a.out_bm) + static_cast<int64_t>(g) * a.Bp * a.dp_out;
-        for (int e = threadIdx.x; e < MT * 16 * kColChunk; e += nthr) {
-            const int bl = e / kColChunk, b = row0 + batch_row(bl / 16, bl % 16), c = c0 + e % kColChunk;
-            if (b < a.B && c < a.d_out) {
-                const float z = red[bl][e % kColChunk] + bias_s[e % kColChunk];
-                obm[static_cast<int64_t>(b) * a.dp_out + c] = static_cast<OT>(z > 0.f ? z : 0.f);
+        for (int e = threadIdx.x; e < MT * 16 * (kColChunk / 8); e += nthr) {
+            const int bl = e / (kColChunk / 8), cl = (e % (kColChunk / 8)) * 8;
+            const int b = row0 + batch_row(bl / 16, bl % 16), c = c0 + cl;
+            if (b >= a.B || c >= a.d_out) continue;
+            const float4 z0 = *reinterpret_cast<const float4*>(&red[bl][cl]);
+            const float4 z1 = *reinterpret_cast<const float4*>(&red[bl][cl + 4]);
+            float y[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                y[i] += bias_s[cl + i];
+                y[i] = y[i] > 0.f ? y[i] : 0.f;
+            }
+            OT* dst = obm + static_cast<int64_t>(b) * a.dp_out + c;
+            if (c + 8 <= a.d_out) {
+                store8(dst, y);
+            } else {
+                for (int i = 0; c + i < a.d_out; ++i) dst[i] = static_cast<OT>(y[i]);
             }
         }
         if (a.out_fm) {
             OT* ofm = static_cast<OT*>(a.out_fm) + static_cast<int64_t>(g) * a.dp_out * a.Bp;
-            for (int e = threadIdx.x; e < MT * 16 * kColChunk; e += nthr) {
-                const int cl = e / (MT * 16), bl = e % (MT * 16), b = row0 + bl, c = c0 + cl;
-                if (b < a.B && c < a.d_out) {
-                    const float z = red[tile_row(bl)][cl] + bias_s[cl];
-                    ofm[static_cast<int64_t>(c) * a.Bp + b] = static_cast<OT>(z > 0.f ? z : 0.f);
+            for (int e = threadIdx.x; e < MT * 16 * (kColChunk / 8); e += nthr) {
+                const int cl = e / (MT * 2), bl = (e % (MT * 2)) * 8;
+                const int b = row0 + bl, c = c0 + cl;
+                if (b >= a.B || c >= a.d_out) continue;
+                float y[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float z = red[tile_row(bl + i)][cl] + bias_s[cl];
+                    y[i] = z > 0.f ? z : 0.f;
+                }
+                OT* dst = ofm + static_cast<int64_t>(c) * a.Bp + b;
+                if (b + 8 <= a.B) {
+                    store8(dst, y);
+                } else {
+                    for (int i = 0; b + i < a.B; ++i) dst[i] = static_cast<OT>(y[i]);
                 }
             }
         }
