@@ -44,7 +44,8 @@ typedef enum {
     LC_ERR_WORKSPACE = -5,  /* scratch buffer too small */
     LC_ERR_HIP = -6,        /* a HIP call failed; lc_last_hip_error() has the code */
     LC_ERR_NONFINITE = -7,  /* the evaluated loss is not finite */
-    LC_ERR_UNSUPPORTED = -8 /* shape outside what the kernels handle */
+    LC_ERR_UNSUPPORTED = -8, /* shape outside what the kernels handle */
+    LC_ERR_SYNC = -9         /* a replica-wide barrier of the resident step kernel timed out */
 } lc_status;
 
 typedef enum { LC_KIND_QUAD = 0, LC_KIND_MLP = 1 } lc_kind;
@@ -153,6 +154,27 @@ int lc_average(lc_handle* h);
  * caller who reads X directly must call lc_materialize() first.  Turning the mode off materialises. */
 int lc_set_lazy_broadcast(lc_handle* h, int on);
 int lc_materialize(lc_handle* h);
+
+/* Resident local steps (Sec. 2: a worker's tau local updates touch only its own model).  For
+ * two-layer LC_KIND_MLP models with at most 16 classes, B <= 64, padded widths d0 <= 1024 and
+ * d1 <= 256, and m * ceil64(d1) / 16 <= 256, lc_local_steps() runs up to 8 consecutive steps as
+ * ONE kernel: each workgroup keeps a 16-unit slice of the first layer and its momentum on chip
+ * (LDS and registers) for all of them, and the workgroups of a replica meet once per step at a
+ * barrier in device memory to exchange the hidden activations.  Same arithmetic as the
+ * launch-per-layer path up to the summation order (results agree to rounding, not bit for bit).
+ * on = 0 selects the launch-per-layer path for every shape; the default is on.  Shapes outside
+ * the limits always take the launch-per-layer path.  The barrier wait is bounded: if it ever
+ * times out the kernel still terminates, and the next synchronising call (lc_loss,
+ * lc_get_state, lc_get_local_losses) returns LC_ERR_SYNC; the state is then undefined. */
+int lc_set_resident(lc_handle* h, int on);
+/* 1 if lc_local_steps() of this (attached) handle takes the resident step kernel, else 0. */
+int lc_resident_active(const lc_handle* h);
+
+/* How many times a workgroup of the resident step kernel re-reads a replica's arrival counter
+ * before it gives up waiting (default 400000, several hundred milliseconds).  0 makes every
+ * wait give up at once: the kernel then runs to its end on incomplete data and the next
+ * synchronising call reports LC_ERR_SYNC -- the way to exercise that error path.  polls >= 0. */
+int lc_set_barrier_polls(lc_handle* h, int polls);
 
 /* Training loss of the averaged model F(x_bar) on the first E samples (the
  * quantity the basic update rule of Sec. 4.2 reads).  Always evaluated with

@@ -83,6 +83,12 @@ def lib() -> C.CDLL:
     L.lc_average.argtypes = [vp]
     L.lc_set_lazy_broadcast.restype = C.c_int
     L.lc_set_lazy_broadcast.argtypes = [vp, C.c_int]
+    L.lc_set_resident.restype = C.c_int
+    L.lc_set_resident.argtypes = [vp, C.c_int]
+    L.lc_resident_active.restype = C.c_int
+    L.lc_resident_active.argtypes = [vp]
+    L.lc_set_barrier_polls.restype = C.c_int
+    L.lc_set_barrier_polls.argtypes = [vp, C.c_int]
     L.lc_materialize.restype = C.c_int
     L.lc_materialize.argtypes = [vp]
     L.lc_loss.restype = C.c_int
@@ -259,6 +265,17 @@ class LocalSGD:
 
     def set_lazy_broadcast(self, on: bool) -> None:
         self._check(self._L.lc_set_lazy_broadcast(self._h, int(bool(on))), "lc_set_lazy_broadcast")
+
+    def set_resident(self, on: bool) -> None:
+        self._check(self._L.lc_set_resident(self._h, int(bool(on))), "lc_set_resident")
+
+    def resident_active(self) -> bool:
+        rc = self._L.lc_resident_active(self._h)
+        self._check(min(rc, 0), "lc_resident_active")
+        return rc == 1
+
+    def set_barrier_polls(self, polls: int) -> None:
+        self._check(self._L.lc_set_barrier_polls(self._h, int(polls)), "lc_set_barrier_polls")
 
     def materialize(self) -> None:
         self._check(self._L.lc_materialize(self._h), "lc_materialize")

@@ -120,6 +120,13 @@ size_t carve(lc_handle* h, char* base) {
         const int passes = eval ? (h->md.E + per_pass - 1) / per_pass : 1;
         S.loss = static_cast<float*>(c.take(sizeof(float) * static_cast<size_t>(S.G) * passes * kLossParts));
     }
+    if (resident_shape_ok(h)) {
+        h->res_a1x = static_cast<float*>(c.take(sizeof(float) * 2 * resident_exchange_floats(h)));
+        h->res_ctr = static_cast<unsigned*>(c.take(sizeof(unsigned) * 128));
+    } else {
+        h->res_a1x = nullptr;
+        h->res_ctr = nullptr;
+    }
     h->n_partial = 0;
     h->partial = nullptr;
     return static_cast<size_t>(round_up(static_cast<int64_t>(c.off), 256));
@@ -172,6 +179,18 @@ int one_local_step(lc_handle* h) {
     return LC_OK;
 }
 
+// Reads and clears the error flag of the resident step kernel.  Call after a stream synchronise.
+int check_resident(lc_handle* h) {
+    if (!h->res_used || !h->res_ctr) return LC_OK;
+    unsigned flag = 0;
+    LC_HIP(h, hipMemcpyAsync(&flag, h->res_ctr + 64, sizeof(unsigned), hipMemcpyDeviceToHost, h->stream));
+    LC_HIP(h, hipStreamSynchronize(h->stream));
+    h->res_used = false;
+    if (flag == 0) return LC_OK;
+    LC_HIP(h, hipMemsetAsync(h->res_ctr + 64, 0, sizeof(unsigned), h->stream));
+    return LC_ERR_SYNC;
+}
+
 }  // namespace
 
 extern "C" {
@@ -187,6 +206,7 @@ const char* lc_strerror(int status) {
         case LC_ERR_HIP: return "HIP call failed";
         case LC_ERR_NONFINITE: return "loss is not finite";
         case LC_ERR_UNSUPPORTED: return "shape not supported";
+        case LC_ERR_SYNC: return "replica barrier timed out in the resident step kernel";
         default: return "unknown status";
     }
 }
@@ -252,6 +272,11 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     h->scratch_bytes = 0;
     h->stream = nullptr;
     h->last_hip = 0;
+    h->res_a1x = nullptr;
+    h->res_ctr = nullptr;
+    h->res_on = true;
+    h->res_used = false;
+    h->res_spin_limit = 400000;   // several hundred milliseconds of polling
     h->timing_which = kTimeNone;
     h->ev_used = 0;
     h->bm_on = false;
@@ -316,6 +341,16 @@ int lc_local_steps(lc_handle* h, int tau) {
         // mini-batch selection does not depend on the weights: one launch prepares the inputs
         // of the next n steps
         if (h->md.kind == LC_KIND_MLP) LC_HIP(h, launch_gather(h, false, h->k, n));
+        if (h->res_on && h->res_a1x) {
+            // small two-layer model: the n steps are one launch with the weights held on chip
+            LC_HIP(h, launch_resident(h, n));
+            h->train.cur_slot = n - 1;
+            h->k += n;
+            h->v_cleared = false;
+            h->lazy_rows = false;
+            h->res_used = true;
+            continue;
+        }
         for (int t = 0; t < n; ++t) {
             h->train.cur_slot = t;
             const int r = one_local_step(h);
@@ -354,6 +389,24 @@ int lc_set_lazy_broadcast(lc_handle* h, int on) {
         if (rc != LC_OK) return rc;
     }
     h->lazy_enabled = on != 0;
+    return LC_OK;
+}
+
+int lc_set_resident(lc_handle* h, int on) {
+    if (!h) return LC_ERR_ARG;
+    h->res_on = on != 0;
+    return LC_OK;
+}
+
+int lc_resident_active(const lc_handle* h) {
+    if (!h) return LC_ERR_ARG;
+    if (!h->attached) return LC_ERR_STATE;
+    return (h->res_on && h->res_a1x) ? 1 : 0;
+}
+
+int lc_set_barrier_polls(lc_handle* h, int polls) {
+    if (!h || polls < 0) return LC_ERR_ARG;
+    h->res_spin_limit = polls;
     return LC_OK;
 }
 
@@ -442,6 +495,8 @@ int lc_loss(lc_handle* h, double* out) {
         F /= static_cast<double>(E);
     }
     *out = F;
+    const int src = check_resident(h);
+    if (src != LC_OK) return src;
     return isfinite(F) ? LC_OK : LC_ERR_NONFINITE;
 }
 
@@ -633,7 +688,7 @@ int lc_get_state(lc_handle* h, float* X_host, float* V_host, int64_t* k) {
     LC_HIP(h, hipStreamSynchronize(h->stream));
     if (V_host && h->v_cleared) memset(V_host, 0, row * static_cast<size_t>(h->m));   // cleared, not yet rewritten
     if (k) *k = h->k;
-    return LC_OK;
+    return check_resident(h);
 }
 
 int lc_set_state(lc_handle* h, const float* X_host, const float* V_host, int64_t k) {
@@ -679,7 +734,7 @@ int lc_get_local_losses(lc_handle* h, float* losses_host) {
         losses_host[i] = sum;
     }
     free(parts);
-    return LC_OK;
+    return check_resident(h);
 }
 
 int lc_get_last_indices(lc_handle* h, int32_t* idx_host) {

@@ -85,6 +85,12 @@ struct lc_handle {
     bool lazy_enabled, lazy_rows;
     int loss_parts_train, loss_parts_eval;   // how many of the kLossParts slots the last launch wrote
     bool lazy_enabled_step;   // set only while lc_average runs its reduce-only form
+    // resident local steps (small two-layer models): exchange buffer, barrier counters, switches
+    float* res_a1x;         // [2 layouts][2 parities][m][Bp][dp1], null when the shape does not qualify
+    unsigned* res_ctr;      // [64] arrival counters, [64] error flag
+    bool res_on;            // lc_set_resident
+    bool res_used;          // a resident launch has run since the error flag was last read
+    int res_spin_limit;     // polls a barrier wait may take
     double* partial;        // reduction partials
     int n_partial;
     int last_hip;
@@ -112,6 +118,11 @@ hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset);
 hipError_t launch_backward(lc_handle* h, int l);
 bool head_is_fused(const lc_handle* h);   // last layer: forward + softmax + backward in one kernel
 hipError_t launch_head(lc_handle* h);
+
+// resident path (weights stay in LDS over a run of local steps)
+bool resident_shape_ok(const lc_handle* h);
+size_t resident_exchange_floats(const lc_handle* h);   // per layout
+hipError_t launch_resident(lc_handle* h, int n_steps);  // the steps gathered into slots 0 .. n_steps-1
 
 // timing helpers used by the launchers
 void timing_start(lc_handle* h, int which);

@@ -1,0 +1,444 @@
+// Local steps of small two-layer models with the weights resident on chip.
+//
+// Between two averaging steps a PASGD worker touches nothing but its own model (Sec. 2:
+// tau local mini-batch SGD updates, then one averaging step).  When a replica's first layer,
+// cut into slices of 16 hidden units, fits the LDS of the compute units, a whole run of local
+// steps is one kernel launch: every workgroup loads its slice of W_1 (into LDS) and of the
+// momentum V_1 (into registers) once, takes all the steps on them, and writes them back once.
+// The streaming kernels need four launches per step and move W and V through the memory
+// system in every one of them; at this size those launches, not the arithmetic, are the cost.
+//
+// Work split for a model d0 -> d1 -> d2 (d2 <= 16), replica g, workgroup cb of NB = dp1 / 16:
+//   owns   hidden units C = [16 cb, 16 cb + 16): columns C of W_1, V_1 and entries C of b_1;
+//   keeps  a full private copy of W_2, V_2, b_2 (d1 x d2 is tiny), updated identically by
+//          every workgroup of the replica, so the second layer needs no exchange at all.
+// One step:
+//   (1) A_1[:, C] = ReLU(A_0 W_1[:, C] + b_1[C])          MFMA, K split over the 4 wavefronts
+//   (2) publish the slice, replica-wide barrier, every workgroup then sees all of A_1
+//   (3) Z_2 = A_1 W_2 + b_2, softmax cross-entropy, dZ_2   (redundantly in every workgroup)
+//   (4) dZ_1[:, C] = (dZ_2 W_2[C, :]^T) .* [A_1[:, C] > 0]  with the weights of before the update
+//   (5) dW_2 = A_1^T dZ_2, db_2 and the momentum update of the private copy
+//   (6) dW_1[:, C] = A_0^T dZ_1[:, C], db_1[C] and the momentum update of the slice
+// The only communication is the A_1 slice (Bp x 16 values per workgroup and step), double
+// buffered by step parity so that a fast workgroup never overwrites what a slow one still reads.
+//
+// The barrier is a counter per replica in device memory: arrive with an agent-scope release,
+// poll with relaxed loads, then an agent-scope acquire.  All workgroups of a launch are
+// co-resident (the launcher refuses grids above one workgroup per compute unit), and the
+// poll loop is bounded: a workgroup that runs out of polls raises the error flag, stops
+// waiting for good and finishes its steps, so the grid always drains.
+#include "lc_internal.h"
+#include "lc_mma.h"
+
+namespace lc {
+
+namespace {
+
+constexpr int kResMaxD0 = 1024;   // padded input width the LDS slice is sized for
+constexpr int kResMaxD1 = 256;    // padded hidden width (private W_2^T copy)
+constexpr int kResK1P = kResMaxD0 + 4;
+constexpr int kResK2P = kResMaxD1 + 4;
+constexpr int kResWaves = 16;                    // wavefronts per workgroup: four per SIMD hide each other's waits
+constexpr int kResThreads = kResWaves * 64;
+constexpr int kResTiles = kResMaxD0 / 16 / kResWaves;   // 16-row tiles of W_1 per wavefront
+
+struct ResArgs {
+    float* X;
+    float* V;
+    int64_t x_stride;
+    const float* Xr;      // where the weights are read at the start: X, or the one averaged model
+    int64_t xr_stride;
+    int64_t w1_off, b1_off, w2_off, b2_off;
+    int d0, d1, d2, dp0, dp1;
+    int B, G, NB;
+    const void* a0_bm;    // [slots][G][Bp][dp0] of OT
+    const void* a0_fm;    // [slots][G][dp0][Bp] of OT
+    int64_t a0_slot;      // elements per slot
+    const int32_t* labels;  // [slots][G][Bp]
+    int slot0, n_steps;
+    float lr, beta_first, beta, wd;
+    int vec;              // rows of W_1 may be accessed 16 bytes at a time
+    float* a1x_bm;        // [2][G][Bp][dp1]  exchange buffer, batch-major
+    float* a1x_fm;        // [2][G][dp1][Bp]  the same, feature-major
+    unsigned* ctr;        // [G] arrivals, zero at launch
+    unsigned* err;        // set to 1 when a barrier wait ran out of polls
+    int spin_limit;       // polls one barrier wait may take
+    float* loss;          // [G][kLossParts], slot 0 written
+};
+
+__device__ __forceinline__ float round_operand(float x, bf16_t) { return static_cast<float>(static_cast<bf16_t>(x)); }
+__device__ __forceinline__ float round_operand(float x, float) { return x; }
+
+template <typename OT, int MT>
+__global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
+    constexpr int Bp = 16 * MT;
+    constexpr int NS = Bp / 32;   // 32-wide steps over the batch
+    constexpr int KP = kResWaves / MT;   // wavefronts that share one batch tile and split the reduction
+    __shared__ __attribute__((aligned(16))) float w1s[16][kResK1P];    // W_1[:, C]^T
+    __shared__ __attribute__((aligned(16))) float w2s[16][kResK2P];    // W_2^T (row = class)
+    __shared__ __attribute__((aligned(16))) float v2s[16][kResK2P];
+    __shared__ __attribute__((aligned(16))) float part[KP][Bp][17];
+    __shared__ float a1s[Bp][17];                                       // own slice of A_1
+    __shared__ float z2s[Bp][17];                                       // logits, then dZ_2
+    __shared__ __attribute__((aligned(16))) OT dz2t[16][Bp + 8];        // dZ_2^T
+    __shared__ __attribute__((aligned(16))) OT dz1t[16][Bp + 8];        // dZ_1[:, C]^T
+    __shared__ float b1s[16], vb1s[16], b2s[16], vb2s[16];
+    __shared__ float lred[Bp];
+    __shared__ float colsum1[kResWaves][16], colsum2[kResWaves][16];
+
+    const int64_t logical = xcd_logical_block(static_cast<int64_t>(a.G) * a.NB);
+    if (logical < 0) return;
+    const int g = static_cast<int>(logical / a.NB), cb = static_cast<int>(logical % a.NB);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 15, q = lane >> 4;
+    const int c_base = 16 * cb;
+    const int n_kt = a.dp0 / 16;
+    const bool vec = a.vec != 0;
+
+    float* Xg = a.X + g * a.x_stride;
+    float* Vg = a.V + g * a.x_stride;
+    const float* Xrg = a.Xr + g * a.xr_stride;
+    // ---- load the resident state
+    f32x4 v1[kResTiles];   // V_1 at rows 16 kt + j, columns c_base + 4 q .. + 3, kt = wave + 16 i
+#pragma unroll
+    for (int i = 0; i < kResTiles; ++i) {
+        const int kt = wave + kResWaves * i;
+        v1[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (kt < n_kt) {
+            const int k = 16 * kt + j, c = c_base + 4 * q;
+            float4 w = make_float4(0.f, 0.f, 0.f, 0.f), v = w;
+            if (k < a.d0) {
+                w = load_w4(Xrg + a.w1_off + static_cast<int64_t>(k) * a.d1, c, a.d1, vec, false);
+                v = load_w4(Vg + a.w1_off + static_cast<int64_t>(k) * a.d1, c, a.d1, vec, false);
+            }
+            w1s[4 * q + 0][k] = w.x; w1s[4 * q + 1][k] = w.y; w1s[4 * q + 2][k] = w.z; w1s[4 * q + 3][k] = w.w;
+            v1[i] = f32x4{v.x, v.y, v.z, v.w};
+        }
+    }
+    for (int e = tid; e < 16 * a.dp1; e += kResThreads) {
+        const int k = e / 16, c2 = e % 16;
+        const bool in = k < a.d1 && c2 < a.d2;
+        w2s[c2][k] = in ? Xrg[a.w2_off + static_cast<int64_t>(k) * a.d2 + c2] : 0.f;
+        v2s[c2][k] = in ? Vg[a.w2_off + static_cast<int64_t>(k) * a.d2 + c2] : 0.f;
+    }
+    if (tid < 16) {
+        const bool in1 = c_base + tid < a.d1, in2 = tid < a.d2;
+        b1s[tid] = in1 ? Xrg[a.b1_off + c_base + tid] : 0.f;
+        vb1s[tid] = in1 ? Vg[a.b1_off + c_base + tid] : 0.f;
+        b2s[tid] = in2 ? Xrg[a.b2_off + tid] : 0.f;
+        vb2s[tid] = in2 ? Vg[a.b2_off + tid] : 0.f;
+    }
+    __syncthreads();
+    bool gave_up = false;   // thread 0: a barrier wait ran out of polls
+    for (int s = 0; s < a.n_steps; ++s) {
+        const float beta = s == 0 ? a.beta_first : a.beta;
+        const int slot = a.slot0 + s;
+        const OT* A0 = static_cast<const OT*>(a.a0_bm) + slot * a.a0_slot + static_cast<int64_t>(g) * Bp * a.dp0;
+        const OT* A0T = static_cast<const OT*>(a.a0_fm) + slot * a.a0_slot + static_cast<int64_t>(g) * a.dp0 * Bp;
+        const int32_t* lab = a.labels + (static_cast<int64_t>(slot) * a.G + g) * Bp;
+        const int par = s & 1;
+        float* xbm = a.a1x_bm + (static_cast<int64_t>(par) * a.G + g) * Bp * a.dp1;
+        float* xfm = a.a1x_fm + (static_cast<int64_t>(par) * a.G + g) * a.dp1 * Bp;
+        // ---- (1) Z_1[:, C]: wavefront (mt, kpart) takes batch tile mt and the 32-wide k steps
+        //      kpart, kpart + KP, ...
+        const int mt = wave % MT, kpart = wave / MT;
+        {
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            const OT* arow = A0 + static_cast<int64_t>(16 * mt + j) * a.dp0 + 8 * q;
+            const int n_st = a.dp0 / 32;
+            Frag<OT> af = load8(arow + 32 * (kpart < n_st ? kpart : 0));
+            for (int st = kpart; st < n_st; st += KP) {
+                const int k0 = 32 * st + 8 * q;
+                const int nx = st + KP < n_st ? st + KP : st;
+                const Frag<OT> af_next = load8(arow + 32 * nx);   // next step's operand in flight
+                const float4 x0 = *reinterpret_cast<const float4*>(&w1s[j][k0]);
+                const float4 x1 = *reinterpret_cast<const float4*>(&w1s[j][k0 + 4]);
+                const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+                Frag<OT> bf;
+                pack8(bf, x);
+                acc = mma8(af, bf, acc);
+                af = af_next;
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[kpart][16 * mt + 4 * q + r][j] = acc[r];
+        }
+        __syncthreads();
+        for (int e = tid; e < Bp * 16; e += kResThreads) {
+            const int b = e / 16, c = e % 16;
+            float z = part[0][b][c];
+#pragma unroll
+            for (int p = 1; p < KP; ++p) z += part[p][b][c];
+            z += b1s[c];
+            float act = 0.f;
+            if (b < a.B && c_base + c < a.d1) act = round_operand(z > 0.f ? z : 0.f, OT());
+            a1s[b][c] = act;
+            xbm[static_cast<int64_t>(b) * a.dp1 + c_base + c] = act;
+            xfm[static_cast<int64_t>(c_base + c) * Bp + b] = act;
+        }
+
+        // ---- (2) replica-wide barrier
+        __syncthreads();
+        if (tid == 0 && a.NB > 1) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            __hip_atomic_fetch_add(&a.ctr[g], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned target = static_cast<unsigned>(s + 1) * static_cast<unsigned>(a.NB);
+            int polls = 0;
+            while (!gave_up) {
+                const unsigned seen = __hip_atomic_load(&a.ctr[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (static_cast<int>(seen - target) >= 0) break;
+                if (++polls > a.spin_limit) {
+                    gave_up = true;
+                    atomicExch(a.err, 1u);
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        }
+        __syncthreads();
+        // ---- (3) logits: wavefront (mt, kpart) again, partial sums over its share of d1; then
+        //      softmax cross-entropy and dZ_2, one thread per sample
+        {
+            f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
+            const float* arow = xbm + static_cast<int64_t>(16 * mt + j) * a.dp1 + 8 * q;
+            for (int st = kpart; st < a.dp1 / 32; st += KP) {
+                const int k0 = 32 * st + 8 * q;
+                const float4 y0 = *reinterpret_cast<const float4*>(arow + 32 * st);
+                const float4 y1 = *reinterpret_cast<const float4*>(arow + 32 * st + 4);
+                const float y[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
+                const float4 x0 = *reinterpret_cast<const float4*>(&w2s[j][k0]);
+                const float4 x1 = *reinterpret_cast<const float4*>(&w2s[j][k0 + 4]);
+                const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+                Frag<OT> bf, af;
+                pack8(bf, x);
+                pack8(af, y);
+                z = mma8(af, bf, z);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[kpart][16 * mt + 4 * q + r][j] = z[r];
+        }
+        __syncthreads();
+        // one thread per (sample, class): 16-lane groups hold a sample's logits
+        if (tid < Bp * 16) {
+            const int b = tid >> 4, c = tid & 15;
+            float z = part[0][b][c];
+#pragma unroll
+            for (int p = 1; p < KP; ++p) z += part[p][b][c];
+            z += b2s[c];
+            const int y = b < a.B ? lab[b] : -1;
+            const bool valid = c < a.d2;
+            float zmax = valid ? z : -INFINITY;
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o, 16));
+            const float ex = valid ? expf(z - zmax) : 0.f;
+            float sum = ex;
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 16);
+            const float zy = __shfl(z, y >= 0 ? y : 0, 16);
+            float dz = 0.f;
+            if (y >= 0 && valid)
+                dz = round_operand((ex * (1.f / sum) - (c == y ? 1.f : 0.f)) * (1.f / static_cast<float>(a.B)), OT());
+            z2s[b][c] = dz;
+            dz2t[c][b] = static_cast<OT>(dz);
+            if (c == 0) lred[b] = y >= 0 ? -(zy - zmax - logf(sum)) : 0.f;
+        }
+        __syncthreads();
+        if (cb == 0 && wave == 0) {
+            float v = lane < Bp ? lred[lane] : 0.f;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+            if (lane == 0) a.loss[static_cast<int64_t>(g) * kLossParts] = v / static_cast<float>(a.B);
+        }
+        // ---- (4) dZ_1[:, C] from the second layer's weights of before this step's update, and the
+        //      column sums of dZ_1[:, C] and dZ_2 (bias gradients): first over each wavefront's
+        //      four samples, then over the wavefronts
+        if (tid < Bp * 16) {
+            const int b = tid >> 4, c = tid & 15;
+            float sum = 0.f;
+            for (int c2 = 0; c2 < a.d2; ++c2) sum += z2s[b][c2] * round_operand(w2s[c2][c_base + c], OT());
+            const OT d = static_cast<OT>(a1s[b][c] > 0.f ? sum : 0.f);   // rounds in bf16 mode
+            dz1t[c][b] = d;
+            float s1 = to_f32(d), s2 = z2s[b][c];
+            s1 += __shfl_xor(s1, 16, 64); s1 += __shfl_xor(s1, 32, 64);
+            s2 += __shfl_xor(s2, 16, 64); s2 += __shfl_xor(s2, 32, 64);
+            if (lane < 16) {
+                colsum1[wave][lane] = s1;
+                colsum2[wave][lane] = s2;
+            }
+        }
+        __syncthreads();
+        // ---- bias updates (one thread per entry)
+        if (tid < 32) {
+            const int c = tid & 15;
+            float db = 0.f;
+            for (int w = 0; w < Bp / 4; ++w) db += tid < 16 ? colsum1[w][c] : colsum2[w][c];
+            if (tid < 16) {
+                if (c_base + c < a.d1) {
+                    const float vb = beta * vb1s[c] + (db + a.wd * b1s[c]);
+                    vb1s[c] = vb;
+                    b1s[c] -= a.lr * vb;
+                }
+            } else if (c < a.d2) {
+                const float vb = beta * vb2s[c] + (db + a.wd * b2s[c]);
+                vb2s[c] = vb;
+                b2s[c] -= a.lr * vb;
+            }
+        }
+        // ---- (5) dW_2 = A_1^T dZ_2 and the update of the private copy; tile kt = 16 rows of W_2
+        for (int kt = wave; kt < a.dp1 / 16; kt += kResWaves) {
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int st = 0; st < NS; ++st) {
+                const int b0 = 32 * st + 8 * q;
+                const float* ar = xfm + static_cast<int64_t>(16 * kt + j) * Bp + b0;
+                const float4 y0 = *reinterpret_cast<const float4*>(ar);
+                const float4 y1 = *reinterpret_cast<const float4*>(ar + 4);
+                const float y[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
+                Frag<OT> af;
+                pack8(af, y);
+                const Frag<OT> bf = *reinterpret_cast<const Frag<OT>*>(&dz2t[j][b0]);
+                acc = mma8(af, bf, acc);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int k = 16 * kt + 4 * q + r;
+                if (k < a.d1 && j < a.d2) {
+                    const float w = w2s[j][k];
+                    const float v = beta * v2s[j][k] + (acc[r] + a.wd * w);
+                    v2s[j][k] = v;
+                    w2s[j][k] = w - a.lr * v;
+                }
+            }
+        }
+        // ---- (6) dW_1[:, C] = A_0^T dZ_1[:, C] and the update of the slice
+#pragma unroll
+        for (int i = 0; i < kResTiles; ++i) {
+            const int kt = wave + kResWaves * i;
+            if (kt < n_kt) {
+                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int st = 0; st < NS; ++st) {
+                    const int b0 = 32 * st + 8 * q;
+                    const Frag<OT> af = *reinterpret_cast<const Frag<OT>*>(&dz1t[j][b0]);
+                    const Frag<OT> bf = load8(A0T + static_cast<int64_t>(16 * kt + j) * Bp + b0);
+                    acc = mma8(af, bf, acc);
+                }
+                const int k = 16 * kt + j;
+                // rows k >= d0 and columns beyond d1 have zero gradient, weight and momentum,
+                // and stay zero under the update
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float w = w1s[4 * q + r][k];
+                    const float v = beta * v1[i][r] + (acc[r] + a.wd * w);
+                    v1[i][r] = v;
+                    w1s[4 * q + r][k] = w - a.lr * v;
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- write the state back
+#pragma unroll
+    for (int i = 0; i < kResTiles; ++i) {
+        const int kt = wave + kResWaves * i;
+        if (kt < n_kt) {
+            const int k = 16 * kt + j, c = c_base + 4 * q;
+            if (k < a.d0) {
+                const float4 w = make_float4(w1s[4 * q + 0][k], w1s[4 * q + 1][k], w1s[4 * q + 2][k], w1s[4 * q + 3][k]);
+                const float4 v = make_float4(v1[i][0], v1[i][1], v1[i][2], v1[i][3]);
+                store_w4(Xg + a.w1_off + static_cast<int64_t>(k) * a.d1, c, a.d1, vec, false, w);
+                store_w4(Vg + a.w1_off + static_cast<int64_t>(k) * a.d1, c, a.d1, vec, false, v);
+            }
+        }
+    }
+    if (tid < 16 && c_base + tid < a.d1) {
+        Xg[a.b1_off + c_base + tid] = b1s[tid];
+        Vg[a.b1_off + c_base + tid] = vb1s[tid];
+    }
+    if (cb == 0) {
+        for (int e = tid; e < a.d1 * a.d2; e += kResThreads) {
+            const int k = e / a.d2, c2 = e % a.d2;
+            Xg[a.w2_off + e] = w2s[c2][k];
+            Vg[a.w2_off + e] = v2s[c2][k];
+        }
+        if (tid < a.d2) {
+            Xg[a.b2_off + tid] = b2s[tid];
+            Vg[a.b2_off + tid] = vb2s[tid];
+        }
+    }
+}
+
+}  // namespace
+
+size_t resident_exchange_floats(const lc_handle* h) {
+    // two step parities x (replicas x padded batch x padded hidden width)
+    return 2 * static_cast<size_t>(h->m) * h->train.Bp * h->layer[1].dp_out;
+}
+
+// Two layers, at most 16 classes and 64 samples, widths within the LDS budget, and few enough
+// workgroups that all of them are on the chip at the same time (one per compute unit).
+bool resident_shape_ok(const lc_handle* h) {
+    if (h->md.kind != LC_KIND_MLP || h->L != 2) return false;
+    if (h->layer[2].d_out > 16 || h->md.B > 64) return false;
+    if (h->layer[1].dp_in > kResMaxD0 || h->layer[1].dp_out > kResMaxD1) return false;
+    return static_cast<int64_t>(h->m) * (h->layer[1].dp_out / 16) <= 256;
+}
+
+hipError_t launch_resident(lc_handle* h, int n_steps) {
+    const ActSet& S = h->train;
+    const bool bf16 = h->md.gemm == LC_GEMM_BF16;
+    ResArgs a;
+    a.X = h->X;
+    a.V = h->V;
+    a.x_stride = h->Ps;
+    a.Xr = h->lazy_rows ? h->xbar : h->X;
+    a.xr_stride = h->lazy_rows ? 0 : h->Ps;
+    a.w1_off = h->layer[1].w_off;
+    a.b1_off = h->layer[1].b_off;
+    a.w2_off = h->layer[2].w_off;
+    a.b2_off = h->layer[2].b_off;
+    a.d0 = h->layer[1].d_in;
+    a.d1 = h->layer[1].d_out;
+    a.d2 = h->layer[2].d_out;
+    a.dp0 = h->layer[1].dp_in;
+    a.dp1 = h->layer[1].dp_out;
+    a.B = S.B;
+    a.G = S.G;
+    a.NB = a.dp1 / 16;
+    a.a0_bm = S.a_bm[0];
+    a.a0_fm = S.a_fm[0];
+    a.a0_slot = static_cast<int64_t>(S.G) * S.Bp * a.dp0;
+    a.labels = S.labels;
+    a.slot0 = 0;
+    a.n_steps = n_steps;
+    a.lr = h->md.lr;
+    a.beta_first = effective_beta(h);
+    a.beta = h->md.beta;
+    a.wd = h->md.wd;
+    a.vec = (a.d1 % 4 == 0 && a.w1_off % 4 == 0) ? 1 : 0;
+    a.a1x_bm = h->res_a1x;
+    a.a1x_fm = h->res_a1x + resident_exchange_floats(h);
+    a.ctr = h->res_ctr;
+    a.err = h->res_ctr + 64;
+    a.spin_limit = h->res_spin_limit;
+    a.loss = S.loss;
+    if (n_steps < 1 || n_steps > S.slots) return hipErrorInvalidValue;
+    const int64_t total = static_cast<int64_t>(a.G) * a.NB;
+    if (total > 256 || a.G > 64 || !h->res_a1x) return hipErrorInvalidValue;
+    hipError_t e = hipMemsetAsync(h->res_ctr, 0, sizeof(unsigned) * 64, h->stream);
+    if (e != hipSuccess) return e;
+    const unsigned grid = static_cast<unsigned>((total + kXcds - 1) / kXcds * kXcds);
+    if (S.Bp != 32 && S.Bp != 64) return hipErrorInvalidValue;
+    timing_start(h, kTimeBwd);
+    if (S.Bp == 32) {
+        if (bf16) hipLaunchKernelGGL((resident_kernel<bf16_t, 2>), dim3(grid), dim3(kResThreads), 0, h->stream, a);
+        else hipLaunchKernelGGL((resident_kernel<float, 2>), dim3(grid), dim3(kResThreads), 0, h->stream, a);
+    } else {
+        if (bf16) hipLaunchKernelGGL((resident_kernel<bf16_t, 4>), dim3(grid), dim3(kResThreads), 0, h->stream, a);
+        else hipLaunchKernelGGL((resident_kernel<float, 4>), dim3(grid), dim3(kResThreads), 0, h->stream, a);
+    }
+    h->loss_parts_train = 1;
+    timing_stop(h, kTimeBwd);
+    return hipGetLastError();
+}
+
+}  // namespace lc

@@ -91,7 +91,8 @@ def _assert_close(got, want, dims, tol, what, gates=None):
         assert err < t, f"{what} {name}: rel err {err:.3e} >= {t}"
 
 
-def _problem(pkg, orc, dims, m, B, N=400, lr=0.1, beta=0.9, wd=0.0, bf16=False, seed=11, E=None, mean_sd=1.0):
+def _problem(pkg, orc, dims, m, B, N=400, lr=0.1, beta=0.9, wd=0.0, bf16=False, seed=11, E=None, mean_sd=1.0,
+             resident=True):
     data, labels = synth.gaussian_mixture(seed, N, dims[0], dims[-1], mean_sd=mean_sd)
     if bf16:
         data = synth.bf16_representable(data)
@@ -105,6 +106,7 @@ def _problem(pkg, orc, dims, m, B, N=400, lr=0.1, beta=0.9, wd=0.0, bf16=False, 
     gmd = pkg.make_model(pkg.KIND_MLP, dims, B=B, N=N, E=E, lr=lr, beta=beta, wd=wd, bf16=bf16)
     ref = orc.Run(m, omd, seed, x1, data, labels)
     run = pkg.LocalSGD(m, gmd, seed, x1, data, labels)
+    run.set_resident(resident)   # False: launch-per-layer kernels also where the resident kernel applies
     return ref, run
 
 
@@ -235,11 +237,21 @@ def test_update_from_grad_and_fused_average(pkg, orc, m, P):
 
 # ------------------------------------------------------------- one local step
 
+def _resident_shape(dims, m, B):
+    """Shapes lc_set_resident documents as taking the resident step kernel."""
+    up64 = lambda d: (d + 63) // 64 * 64
+    return (len(dims) == 3 and dims[2] <= 16 and B <= 64 and up64(dims[0]) <= 1024 and up64(dims[1]) <= 256
+            and m * up64(dims[1]) // 16 <= 256)
+
+
+@pytest.mark.parametrize("resident", [True, False])
 @pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("dims,m,B", SHAPES)
-def test_one_local_step(pkg, orc, dims, m, B, bf16):
-    _say(f"one step dims={dims} m={m} B={B} bf16={bf16}")
-    ref, run = _problem(pkg, orc, dims, m, B, wd=1e-3, bf16=bf16)
+def test_one_local_step(pkg, orc, dims, m, B, bf16, resident):
+    if not resident and not _resident_shape(dims, m, B):
+        pytest.skip("only one engine handles this shape")
+    _say(f"one step dims={dims} m={m} B={B} bf16={bf16} resident={resident}")
+    ref, run = _problem(pkg, orc, dims, m, B, wd=1e-3, bf16=bf16, resident=resident)
     x1 = ref.X[0].copy()
     data = ref._keep[1]
     ref.local_steps(1)
@@ -295,6 +307,82 @@ def test_plain_sgd_without_momentum_and_repeatability(pkg, orc):
         run.close()
     assert np.array_equal(outs[0][0].view(np.uint32), outs[1][0].view(np.uint32))   # bit-identical reruns
     assert np.array_equal(outs[0][1].view(np.uint32), outs[1][1].view(np.uint32))
+
+
+RESIDENT_CASES = [
+    # dims, m, B: unaligned rows and a ragged batch; two column slices and one; the 2-layer configuration
+    ([67, 129, 10], 3, 33),
+    ([96, 64, 16], 5, 64),
+    ([784, 256, 10], 8, 64),
+]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("dims,m,B", RESIDENT_CASES)
+def test_resident_rounds_against_oracle_and_layer_kernels(pkg, orc, dims, m, B, bf16):
+    """Runs of local steps inside one launch (5 steps, then 11 = 8 + 3 in two launches) with
+    averaging in between, deferred broadcast on: against the oracle, and against the
+    launch-per-layer kernels (same arithmetic, other summation order)."""
+    assert _resident_shape(dims, m, B)
+    _say(f"resident rounds dims={dims} m={m} B={B} bf16={bf16}")
+    tol = TOL16 if bf16 else TOL32
+    ref, run = _problem(pkg, orc, dims, m, B, wd=5e-4, bf16=bf16, lr=0.05)
+    _, lay = _problem(pkg, orc, dims, m, B, wd=5e-4, bf16=bf16, lr=0.05, resident=False)
+    run.set_lazy_broadcast(True)
+    lay.set_lazy_broadcast(True)
+    done = 0
+    for tau in (5, 11):
+        ref.local_steps(tau)
+        run.local_steps(tau)
+        lay.local_steps(tau)
+        done += tau
+        X, V, k = run.get_state()
+        Xl, Vl, _ = lay.get_state()
+        assert k == ref.k == done
+        # several steps amplify rounding differences a little: compare on the scale of the state
+        _assert_close(X, ref.X, dims, tol * 4, f"X after {done}")
+        _assert_close(V, ref.V, dims, tol * 8, f"V after {done}")
+        _assert_close(X, Xl, dims, tol * 4, f"X vs layer kernels after {done}")
+        ll = run.local_losses()
+        assert np.abs(ll - ref.last_losses).max() < 4 * tol * max(np.abs(ref.last_losses).max(), 1e-3)
+        ref.average()
+        run.average()
+        lay.average()
+        assert abs(run.loss() - ref.loss()) < 4 * tol * max(ref.loss(), 1e-3)
+    X, V, _ = run.get_state()
+    for i in range(1, m):
+        assert np.array_equal(X[i].view(np.uint32), X[0].view(np.uint32))
+    run.close()
+    lay.close()
+
+
+def test_resident_repeatable_and_barrier_timeout_reported(pkg, orc):
+    dims, m, B = [96, 64, 10], 4, 32
+    _say("resident repeatability, forced barrier time-out")
+    outs = []
+    for rep in range(2):
+        _, run = _problem(pkg, orc, dims, m, B)
+        run.local_steps(6)
+        outs.append(run.get_state())
+        run.close()
+    assert np.array_equal(outs[0][0].view(np.uint32), outs[1][0].view(np.uint32))   # bit-identical reruns
+    assert np.array_equal(outs[0][1].view(np.uint32), outs[1][1].view(np.uint32))
+    # a wait that may not poll at all gives up: the kernel still ends, and the error is reported once
+    ref, run = _problem(pkg, orc, dims, m, B)
+    x1 = ref.X.copy()
+    run.set_barrier_polls(0)
+    run.local_steps(3)
+    with pytest.raises(pkg.LcError) as ei:
+        run.get_state()
+    assert ei.value.status == -9
+    run.set_barrier_polls(400000)
+    run.set_state(x1, np.zeros_like(x1), 0)
+    ref.local_steps(3)
+    run.local_steps(3)
+    X, V, k = run.get_state()
+    assert k == 3
+    _assert_close(X, ref.X, dims, TOL32 * 4, "X after recovery")
+    run.close()
 
 
 # --------------------------------------------------------------- loss + driver
