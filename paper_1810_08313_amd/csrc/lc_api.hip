@@ -276,6 +276,7 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     h->res_ctr = nullptr;
     h->res_on = true;
     h->res_used = false;
+    h->res_arrivals = 0;
     h->res_spin_limit = 400000;   // several hundred milliseconds of polling
     h->timing_which = kTimeNone;
     h->ev_used = 0;
@@ -318,6 +319,7 @@ int lc_attach(lc_handle* h, void* X, void* V, void* scratch, size_t scratch_byte
     h->stream = static_cast<hipStream_t>(stream);
     (void)carve(h, h->scratch);
     LC_HIP(h, hipMemsetAsync(scratch, 0, need, h->stream));
+    h->res_arrivals = 0;
     LC_HIP(h, hipStreamSynchronize(h->stream));
     h->attached = true;
     return LC_OK;

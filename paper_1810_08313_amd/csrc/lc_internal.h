@@ -88,6 +88,7 @@ struct lc_handle {
     // resident local steps (small two-layer models): exchange buffer, barrier counters, switches
     float* res_a1x;         // [2 layouts][2 parities][m][Bp][dp1], null when the shape does not qualify
     unsigned* res_ctr;      // [64] arrival counters, [64] error flag
+    unsigned res_arrivals;  // value of every counter once the queued launches have run (zeroed with the scratch at attach)
     bool res_on;            // lc_set_resident
     bool res_used;          // a resident launch has run since the error flag was last read
     int res_spin_limit;     // polls a barrier wait may take

@@ -60,7 +60,8 @@ struct ResArgs {
     int vec;              // rows of W_1 may be accessed 16 bytes at a time
     float* a1x_bm;        // [2][G][Bp][dp1]  exchange buffer, batch-major
     float* a1x_fm;        // [2][G][dp1][Bp]  the same, feature-major
-    unsigned* ctr;        // [G] arrivals, zero at launch
+    unsigned* ctr;        // [G] arrivals since attach (every workgroup arrives once per step, whatever happens)
+    unsigned ctr_base;    // their value when this launch starts
     unsigned* err;        // set to 1 when a barrier wait ran out of polls
     int spin_limit;       // polls one barrier wait may take
     float* loss;          // [G][kLossParts], slot 0 written
@@ -172,8 +173,9 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
             float act = 0.f;
             if (b < a.B && c_base + c < a.d1) act = round_operand(z > 0.f ? z : 0.f, OT());
             a1s[b][c] = act;
-            xbm[static_cast<int64_t>(b) * a.dp1 + c_base + c] = act;
-            xfm[static_cast<int64_t>(c_base + c) * Bp + b] = act;
+            // written through to device scope right away, so the release below finds nothing to write back
+            __hip_atomic_store(&xbm[static_cast<int64_t>(b) * a.dp1 + c_base + c], act, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&xfm[static_cast<int64_t>(c_base + c) * Bp + b], act, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
 
         // ---- (2) replica-wide barrier
@@ -181,7 +183,7 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
         if (tid == 0 && a.NB > 1) {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
             __hip_atomic_fetch_add(&a.ctr[g], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const unsigned target = static_cast<unsigned>(s + 1) * static_cast<unsigned>(a.NB);
+            const unsigned target = a.ctr_base + static_cast<unsigned>(s + 1) * static_cast<unsigned>(a.NB);
             int polls = 0;
             while (!gave_up) {
                 const unsigned seen = __hip_atomic_load(&a.ctr[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -418,14 +420,13 @@ hipError_t launch_resident(lc_handle* h, int n_steps) {
     a.a1x_bm = h->res_a1x;
     a.a1x_fm = h->res_a1x + resident_exchange_floats(h);
     a.ctr = h->res_ctr;
+    a.ctr_base = h->res_arrivals;
     a.err = h->res_ctr + 64;
     a.spin_limit = h->res_spin_limit;
     a.loss = S.loss;
     if (n_steps < 1 || n_steps > S.slots) return hipErrorInvalidValue;
     const int64_t total = static_cast<int64_t>(a.G) * a.NB;
     if (total > 256 || a.G > 64 || !h->res_a1x) return hipErrorInvalidValue;
-    hipError_t e = hipMemsetAsync(h->res_ctr, 0, sizeof(unsigned) * 64, h->stream);
-    if (e != hipSuccess) return e;
     const unsigned grid = static_cast<unsigned>((total + kXcds - 1) / kXcds * kXcds);
     if (S.Bp != 32 && S.Bp != 64) return hipErrorInvalidValue;
     timing_start(h, kTimeBwd);
@@ -437,6 +438,7 @@ hipError_t launch_resident(lc_handle* h, int n_steps) {
         else hipLaunchKernelGGL((resident_kernel<float, 4>), dim3(grid), dim3(kResThreads), 0, h->stream, a);
     }
     h->loss_parts_train = 1;
+    h->res_arrivals += static_cast<unsigned>(n_steps) * static_cast<unsigned>(a.NB);   // wraps like the counters do
     timing_stop(h, kTimeBwd);
     return hipGetLastError();
 }
