@@ -24,6 +24,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_FP32_PEAK_TFLOPS = 157.3
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 DEFAULT_STEPS = {"cfg1": 2000, "cfg2": 2000, "cfg3": 200, "cfg4": 40, "cfg5a": 50, "cfg5b": 20}
 DEFAULT_WARMUP = {"cfg1": 100, "cfg2": 100, "cfg3": 20, "cfg4": 5, "cfg5a": 5, "cfg5b": 3}
@@ -51,6 +53,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the averaging-stress figures")
     ap.add_argument("--eager", action="store_true", help="write the average to every row at once (no deferred broadcast)")
+    ap.add_argument("--layer-kernels", action="store_true",
+                    help="launch-per-layer kernels also where the resident step kernel applies")
     return ap.parse_args()
 
 
@@ -70,6 +74,8 @@ def bench_mlp(args, pkg, synth):
     md = pkg.make_model(pkg.KIND_MLP, w.dims, B=w.B, N=w.N, E=w.E, lr=w.lr, beta=w.beta, wd=w.wd, bf16=w.bf16)
     run = pkg.LocalSGD(w.m, md, w.seed, w.x1, w.data, w.labels)
     run.set_lazy_broadcast(not args.eager)   # bit-identical results; see lc_set_lazy_broadcast
+    run.set_resident(not args.layer_kernels)
+    resident = run.resident_active()
     interval = w.interval if adaptive else 0
 
     run.run(W, tau0, adaptive=False) if W > 0 else None
@@ -87,17 +93,35 @@ def bench_mlp(args, pkg, synth):
     run.run(K2, tau0, adaptive=False)
     launches, total_ms = run.timing_read()
     run.timing_begin(TIME_NONE)
-    bytes_per_iter = 16.0 * w.m * w.P                    # read W,V + write W,V of every replica, fp32
-    per_launch_bytes = bytes_per_iter * K2 / launches
     avg_launch_ms = total_ms / launches
-    achieved = per_launch_bytes / (avg_launch_ms * 1e-3) / 1e9
-    roof = {"bound": "hbm", "kernel": "backward_kernel (dA + dW + momentum update, all layers)",
-            "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": PMC[name]["traffic"] if name in PMC and args.tau is None else None,
-            "launches": launches, "avg_launch_us": round(avg_launch_ms * 1e3, 2),
-            "algorithmic_bytes_per_launch": per_launch_bytes,
-            "mfma_busy_pct": round(PMC[name]["mfma_busy_pct"], 2) if name in PMC else None}
+    if resident:
+        # small two-layer model, weights on chip: the launch is priced against the matrix cores.
+        # Algorithmic flops of one replica-step: forward 2 B (d0 d1 + d1 d2), weight gradients the
+        # same again, hidden-layer delta 2 B d1 d2 (copies that workgroups compute redundantly
+        # are not counted).
+        d0, d1, d2 = w.dims
+        flops_step = 2.0 * w.B * (2 * d0 * d1 + 3 * d1 * d2)
+        per_launch_flops = flops_step * w.m * K2 / launches
+        achieved = per_launch_flops / (avg_launch_ms * 1e-3) / 1e12
+        peak = MFMA_BF16_PEAK_TFLOPS if w.bf16 else MFMA_FP32_PEAK_TFLOPS
+        roof = {"bound": "mfma", "kernel": "resident_kernel (all layers of %d local steps per launch, weights in LDS)"
+                % round(K2 / launches),
+                "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                "traffic": None, "launches": launches, "avg_launch_us": round(avg_launch_ms * 1e3, 2),
+                "algorithmic_flops_per_launch": per_launch_flops,
+                "workgroups": w.m * ((d1 + 63) // 64 * 64 // 16), "compute_units": 256}
+    else:
+        bytes_per_iter = 16.0 * w.m * w.P                    # read W,V + write W,V of every replica, fp32
+        per_launch_bytes = bytes_per_iter * K2 / launches
+        achieved = per_launch_bytes / (avg_launch_ms * 1e-3) / 1e9
+        pmc = PMC.get(name) if args.tau is None else None
+        roof = {"bound": "hbm", "kernel": "backward_kernel (dA + dW + momentum update, all layers)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": pmc["traffic"] if pmc else None,
+                "launches": launches, "avg_launch_us": round(avg_launch_ms * 1e3, 2),
+                "algorithmic_bytes_per_launch": per_launch_bytes,
+                "mfma_busy_pct": round(pmc["mfma_busy_pct"], 2) if pmc else None}
     final_loss = run.loss()
     run.close()
     cfg = {"workload": f"{name}: MLP {'-'.join(map(str, w.dims))}, m={w.m}, B={w.B}, "
@@ -105,7 +129,7 @@ def bench_mlp(args, pkg, synth):
                        f"{', interval=%d' % interval if adaptive else ''}, lr={w.lr}, momentum={w.beta}",
            "m": w.m, "P": w.P, "batch_per_replica": w.B, "tau0": tau0, "adaptive": adaptive,
            "averaging_rounds": rounds, "tau_schedule": sched[:16], "final_loss": round(final_loss, 6),
-           "deferred_broadcast": not args.eager}
+           "deferred_broadcast": not args.eager, "resident_step_kernel": resident}
     return dict(value=w.m * K / sec, sec=sec, K=K, W=W, roofline=roof, config=cfg,
                 dtype="bf16" if w.bf16 else "f32", workload=w, tau0=tau0)
 
