@@ -31,15 +31,21 @@ DEFAULT_STEPS = {"cfg1": 2000, "cfg2": 2000, "cfg3": 200, "cfg4": 40, "cfg5a": 5
 DEFAULT_WARMUP = {"cfg1": 100, "cfg2": 100, "cfg3": 20, "cfg4": 5, "cfg5a": 5, "cfg5b": 3}
 FLAT = {"cfg5a": (16, 25_600_000), "cfg5b": (8, 138_000_000)}
 
-# HBM bytes per launch of the dominant kernel (backward + fused update, averaged over the layers'
-# launches of one iteration) and its MFMA busy share, from rocprofv3 --pmc runs of this script:
-# FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (calibration on the plain streaming update kernel) and
-# SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE / 8 XCDs x 1024 SIMDs).  Summaries with the commands
-# are in profiles/pmc_traffic_mfma_<workload>.txt.
+# HBM bytes per launch of the dominant kernel and its MFMA busy share, from rocprofv3 --pmc runs of
+# this script: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (calibration on the plain streaming update
+# kernel) and SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE / 8 XCDs x 1024 SIMDs).  For the
+# launch-per-layer path the dominant kernel is the backward kernel (figures averaged over the
+# layers' launches of one iteration, the busy share weighted by launch duration); for the resident
+# path it is the one kernel.  Summaries with the commands are in profiles/pmc_traffic_mfma_<workload>.txt.
 PMC = {
-    "cfg2": {"traffic": (28.156e6 + 2.381e6) / 2, "mfma_busy_pct": (7.77 + 1.13) / 2},
-    "cfg3": {"traffic": (822.645e6 + 2 * 152.948e6) / 3, "mfma_busy_pct": (3.12 * 157 + 3.42 * 2 * 60) / (157 + 120)},
-    "cfg4": {"traffic": (6466.381e6 + 3 * 2909.427e6) / 4, "mfma_busy_pct": (0.81 * 1287 + 1.61 * 3 * 580) / (1287 + 1740)},
+    "cfg2": {"traffic": (28.105e6 + 2.381e6) / 2, "mfma_busy_pct": (8.34 * 9.2 + 1.16 * 8.8) / 18.0},
+    "cfg3": {"traffic": (822.271e6 + 288.509e6 + 15.963e6) / 3,
+             "mfma_busy_pct": (3.20 * 152.6 + 4.35 * 71.6 + 1.10 * 10.3) / 234.5},
+    "cfg4": {"traffic": (6463.755e6 + 2 * 4335.111e6 + 46.455e6) / 4,
+             "mfma_busy_pct": (0.82 * 1280 + 1.65 * 1160 + 1.19 * 20) / 2460},
+}
+PMC_RESIDENT = {
+    "cfg2": {"traffic": 56.525e6, "mfma_busy_pct": 13.55},   # per launch of 5 local steps
 }
 
 
@@ -107,8 +113,10 @@ def bench_mlp(args, pkg, synth):
         roof = {"bound": "mfma", "kernel": "resident_kernel (all layers of %d local steps per launch, weights in LDS)"
                 % round(K2 / launches),
                 "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                "traffic": None, "launches": launches, "avg_launch_us": round(avg_launch_ms * 1e3, 2),
+                "traffic": PMC_RESIDENT[name]["traffic"] if name in PMC_RESIDENT and args.tau is None else None,
+                "launches": launches, "avg_launch_us": round(avg_launch_ms * 1e3, 2),
                 "algorithmic_flops_per_launch": per_launch_flops,
+                "mfma_busy_pct": PMC_RESIDENT[name]["mfma_busy_pct"] if name in PMC_RESIDENT else None,
                 "workgroups": w.m * ((d1 + 63) // 64 * 64 // 16), "compute_units": 256}
     else:
         bytes_per_iter = 16.0 * w.m * w.P                    # read W,V + write W,V of every replica, fp32
