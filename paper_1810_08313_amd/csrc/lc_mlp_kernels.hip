@@ -1321,10 +1321,14 @@ hipError_t launch_backward(lc_handle* h, int l) {
     a.stream = h->stream_weights ? 1 : 0;
     a.n_row_blocks = g.dp_in / 64;
     a.col_split = 1;
-    if (l == 1) {  // no dA: the columns can be shared out to fill the chip
+    if (l == 1) {
+        // no dA: the columns can be shared out, to fill the chip and to keep the walk of a
+        // workgroup short (measured: walks of 2-4 trips stream faster than long ones, a single
+        // trip loses the load-ahead)
         const int n_cc = (g.d_out + kColChunk - 1) / kColChunk;
         const int64_t base = static_cast<int64_t>(S.G) * a.n_row_blocks;
         int want = static_cast<int>((1024 + base - 1) / base);
+        if (want < n_cc / 4) want = n_cc / 4;
         a.col_split = want < 1 ? 1 : (want > n_cc ? n_cc : want);
     }
     a.total_blocks = static_cast<int64_t>(S.G) * a.n_row_blocks * a.col_split;
