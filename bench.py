@@ -105,8 +105,14 @@ def bench_mlp(args, pkg, synth):
         # Algorithmic flops of one replica-step: forward 2 B (d0 d1 + d1 d2), weight gradients the
         # same again, hidden-layer delta 2 B d1 d2 (copies that workgroups compute redundantly
         # are not counted).
-        d0, d1, d2 = w.dims
-        flops_step = 2.0 * w.B * (2 * d0 * d1 + 3 * d1 * d2)
+        if len(w.dims) == 3:
+            d0, d1, d2 = w.dims
+            flops_step = 2.0 * w.B * (2 * d0 * d1 + 3 * d1 * d2)
+            workgroups = w.m * ((d1 + 63) // 64 * 64 // 16)
+        else:   # softmax regression: forward and weight gradient only, one workgroup per replica
+            d0, d1 = w.dims
+            flops_step = 2.0 * w.B * 2 * d0 * d1
+            workgroups = w.m
         per_launch_flops = flops_step * w.m * K2 / launches
         achieved = per_launch_flops / (avg_launch_ms * 1e-3) / 1e12
         peak = MFMA_BF16_PEAK_TFLOPS if w.bf16 else MFMA_FP32_PEAK_TFLOPS
@@ -117,7 +123,7 @@ def bench_mlp(args, pkg, synth):
                 "launches": launches, "avg_launch_us": round(avg_launch_ms * 1e3, 2),
                 "algorithmic_flops_per_launch": per_launch_flops,
                 "mfma_busy_pct": PMC_RESIDENT[name]["mfma_busy_pct"] if name in PMC_RESIDENT else None,
-                "workgroups": w.m * ((d1 + 63) // 64 * 64 // 16), "compute_units": 256}
+                "workgroups": workgroups, "compute_units": 256}
     else:
         bytes_per_iter = 16.0 * w.m * w.P                    # read W,V + write W,V of every replica, fp32
         per_launch_bytes = bytes_per_iter * K2 / launches

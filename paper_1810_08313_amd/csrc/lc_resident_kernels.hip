@@ -369,23 +369,234 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
     }
 }
 
+// Softmax regression (one layer, d0 -> d1 with d1 <= 16 classes): the same idea without any
+// exchange.  One workgroup per replica keeps W^T, V^T and the bias in LDS for all the steps of a
+// launch; a step is logits (reduction split over the wavefronts), softmax cross-entropy, and
+// dW = A_0^T dZ with the momentum update applied in place.
+struct Res1Args {
+    float* X;
+    float* V;
+    int64_t x_stride;
+    const float* Xr;
+    int64_t xr_stride;
+    int64_t w_off, b_off;
+    int d0, d1, dp0;
+    int B, G;
+    const void* a0_bm;      // [slots][G][Bp][dp0] of OT
+    const void* a0_fm;      // [slots][G][dp0][Bp] of OT
+    int64_t a0_slot;
+    const int32_t* labels;  // [slots][G][Bp]
+    int slot0, n_steps;
+    float lr, beta_first, beta, wd;
+    float* loss;            // [G][kLossParts], slot 0 written
+};
+
+template <typename OT, int MT>
+__global__ __launch_bounds__(kResThreads) void resident1_kernel(Res1Args a) {
+    constexpr int Bp = 16 * MT;
+    constexpr int NS = Bp / 32;
+    constexpr int KP = kResWaves / MT;
+    __shared__ __attribute__((aligned(16))) float ws[16][kResK2P];    // W^T (row = class)
+    __shared__ __attribute__((aligned(16))) float vs[16][kResK2P];
+    __shared__ __attribute__((aligned(16))) float part[KP][Bp][17];
+    __shared__ float zs[Bp][17];                                       // dZ
+    __shared__ __attribute__((aligned(16))) OT dzt[16][Bp + 8];        // dZ^T
+    __shared__ float bs[16], vbs[16];
+    __shared__ float lred[Bp];
+    __shared__ float colsum[kResWaves][16];
+
+    const int g = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 15, q = lane >> 4;
+    float* Xg = a.X + g * a.x_stride;
+    float* Vg = a.V + g * a.x_stride;
+    const float* Xrg = a.Xr + g * a.xr_stride;
+
+    for (int e = tid; e < 16 * a.dp0; e += kResThreads) {
+        const int k = e / 16, c = e % 16;
+        const bool in = k < a.d0 && c < a.d1;
+        ws[c][k] = in ? Xrg[a.w_off + static_cast<int64_t>(k) * a.d1 + c] : 0.f;
+        vs[c][k] = in ? Vg[a.w_off + static_cast<int64_t>(k) * a.d1 + c] : 0.f;
+    }
+    if (tid < 16) {
+        bs[tid] = tid < a.d1 ? Xrg[a.b_off + tid] : 0.f;
+        vbs[tid] = tid < a.d1 ? Vg[a.b_off + tid] : 0.f;
+    }
+    __syncthreads();
+
+    const int mt = wave % MT, kpart = wave / MT;
+    for (int s = 0; s < a.n_steps; ++s) {
+        const float beta = s == 0 ? a.beta_first : a.beta;
+        const int slot = a.slot0 + s;
+        const OT* A0 = static_cast<const OT*>(a.a0_bm) + slot * a.a0_slot + static_cast<int64_t>(g) * Bp * a.dp0;
+        const OT* A0T = static_cast<const OT*>(a.a0_fm) + slot * a.a0_slot + static_cast<int64_t>(g) * a.dp0 * Bp;
+        const int32_t* lab = a.labels + (static_cast<int64_t>(slot) * a.G + g) * Bp;
+
+        // ---- logits, partial over this wavefront's share of d0
+        {
+            f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
+            const OT* arow = A0 + static_cast<int64_t>(16 * mt + j) * a.dp0 + 8 * q;
+            for (int st = kpart; st < a.dp0 / 32; st += KP) {
+                const int k0 = 32 * st + 8 * q;
+                const Frag<OT> af = load8(arow + 32 * st);
+                const float4 x0 = *reinterpret_cast<const float4*>(&ws[j][k0]);
+                const float4 x1 = *reinterpret_cast<const float4*>(&ws[j][k0 + 4]);
+                const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+                Frag<OT> bf;
+                pack8(bf, x);
+                z = mma8(af, bf, z);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[kpart][16 * mt + 4 * q + r][j] = z[r];
+        }
+        __syncthreads();
+        // ---- softmax cross-entropy and dZ, one thread per (sample, class); column sums of dZ
+        if (tid < Bp * 16) {
+            const int b = tid >> 4, c = tid & 15;
+            float z = part[0][b][c];
+#pragma unroll
+            for (int p = 1; p < KP; ++p) z += part[p][b][c];
+            z += bs[c];
+            const int y = b < a.B ? lab[b] : -1;
+            const bool valid = c < a.d1;
+            float zmax = valid ? z : -INFINITY;
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o, 16));
+            const float ex = valid ? expf(z - zmax) : 0.f;
+            float sum = ex;
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 16);
+            const float zy = __shfl(z, y >= 0 ? y : 0, 16);
+            float dz = 0.f;
+            if (y >= 0 && valid)
+                dz = round_operand((ex * (1.f / sum) - (c == y ? 1.f : 0.f)) * (1.f / static_cast<float>(a.B)), OT());
+            zs[b][c] = dz;
+            dzt[c][b] = static_cast<OT>(dz);
+            if (c == 0) lred[b] = y >= 0 ? -(zy - zmax - logf(sum)) : 0.f;
+            float cs = dz;
+            cs += __shfl_xor(cs, 16, 64);
+            cs += __shfl_xor(cs, 32, 64);
+            if (lane < 16) colsum[wave][lane] = cs;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            float v = lane < Bp ? lred[lane] : 0.f;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+            if (lane == 0) a.loss[static_cast<int64_t>(g) * kLossParts] = v / static_cast<float>(a.B);
+        } else if (wave == 1 && lane < a.d1) {
+            float db = 0.f;
+            for (int w = 0; w < Bp / 4; ++w) db += colsum[w][lane];
+            const float vb = beta * vbs[lane] + (db + a.wd * bs[lane]);
+            vbs[lane] = vb;
+            bs[lane] -= a.lr * vb;
+        }
+        // ---- dW = A_0^T dZ and the update; tile kt = 16 rows of W
+        for (int kt = wave; kt < a.dp0 / 16; kt += kResWaves) {
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int st = 0; st < NS; ++st) {
+                const int b0 = 32 * st + 8 * q;
+                const Frag<OT> af = load8(A0T + static_cast<int64_t>(16 * kt + j) * Bp + b0);
+                const Frag<OT> bf = *reinterpret_cast<const Frag<OT>*>(&dzt[j][b0]);
+                acc = mma8(af, bf, acc);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int k = 16 * kt + 4 * q + r;
+                if (k < a.d0 && j < a.d1) {
+                    const float w = ws[j][k];
+                    const float v = beta * vs[j][k] + (acc[r] + a.wd * w);
+                    vs[j][k] = v;
+                    ws[j][k] = w - a.lr * v;
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    for (int e = tid; e < a.d0 * a.d1; e += kResThreads) {
+        const int k = e / a.d1, c = e % a.d1;
+        Xg[a.w_off + e] = ws[c][k];
+        Vg[a.w_off + e] = vs[c][k];
+    }
+    if (tid < a.d1) {
+        Xg[a.b_off + tid] = bs[tid];
+        Vg[a.b_off + tid] = vbs[tid];
+    }
+}
+
 }  // namespace
 
 size_t resident_exchange_floats(const lc_handle* h) {
-    // two step parities x (replicas x padded batch x padded hidden width)
+    // two step parities x (replicas x padded batch x padded hidden width); the single-layer form
+    // exchanges nothing (a token amount keeps the buffer pointer non-null)
+    if (h->L == 1) return 64;
     return 2 * static_cast<size_t>(h->m) * h->train.Bp * h->layer[1].dp_out;
 }
 
 // Two layers, at most 16 classes and 64 samples, widths within the LDS budget, and few enough
-// workgroups that all of them are on the chip at the same time (one per compute unit).
+// workgroups that all of them are on the chip at the same time (one per compute unit); or one
+// layer of at most 256 (padded) inputs and 16 classes.
 bool resident_shape_ok(const lc_handle* h) {
-    if (h->md.kind != LC_KIND_MLP || h->L != 2) return false;
-    if (h->layer[2].d_out > 16 || h->md.B > 64) return false;
+    if (h->md.kind != LC_KIND_MLP || h->md.B > 64) return false;
+    if (h->L == 1) return h->layer[1].d_out <= 16 && h->layer[1].dp_in <= kResMaxD1;
+    if (h->L != 2) return false;
+    if (h->layer[2].d_out > 16) return false;
     if (h->layer[1].dp_in > kResMaxD0 || h->layer[1].dp_out > kResMaxD1) return false;
-    return static_cast<int64_t>(h->m) * (h->layer[1].dp_out / 16) <= 256;
+    return h->m <= 64 && static_cast<int64_t>(h->m) * (h->layer[1].dp_out / 16) <= 256;
 }
 
+namespace {
+
+hipError_t launch_resident1(lc_handle* h, int slot0, int n_steps) {
+    const ActSet& S = h->train;
+    const bool bf16 = h->md.gemm == LC_GEMM_BF16;
+    Res1Args a;
+    a.X = h->X;
+    a.V = h->V;
+    a.x_stride = h->Ps;
+    a.Xr = h->lazy_rows ? h->xbar : h->X;
+    a.xr_stride = h->lazy_rows ? 0 : h->Ps;
+    a.w_off = h->layer[1].w_off;
+    a.b_off = h->layer[1].b_off;
+    a.d0 = h->layer[1].d_in;
+    a.d1 = h->layer[1].d_out;
+    a.dp0 = h->layer[1].dp_in;
+    a.B = S.B;
+    a.G = S.G;
+    a.a0_bm = S.a_bm[0];
+    a.a0_fm = S.a_fm[0];
+    a.a0_slot = static_cast<int64_t>(S.G) * S.Bp * a.dp0;
+    a.labels = S.labels;
+    a.slot0 = slot0;
+    a.n_steps = n_steps;
+    a.lr = h->md.lr;
+    a.beta_first = effective_beta(h);
+    a.beta = h->md.beta;
+    a.wd = h->md.wd;
+    a.loss = S.loss;
+    if (slot0 < 0 || n_steps < 1 || slot0 + n_steps > S.slots) return hipErrorInvalidValue;
+    if (S.Bp != 32 && S.Bp != 64) return hipErrorInvalidValue;
+    if (a.dp0 > kResMaxD1 || a.d1 > 16) return hipErrorInvalidValue;
+    timing_start(h, kTimeBwd);
+    const dim3 grid(static_cast<unsigned>(S.G)), block(kResThreads);
+    if (S.Bp == 32) {
+        if (bf16) hipLaunchKernelGGL((resident1_kernel<bf16_t, 2>), grid, block, 0, h->stream, a);
+        else hipLaunchKernelGGL((resident1_kernel<float, 2>), grid, block, 0, h->stream, a);
+    } else {
+        if (bf16) hipLaunchKernelGGL((resident1_kernel<bf16_t, 4>), grid, block, 0, h->stream, a);
+        else hipLaunchKernelGGL((resident1_kernel<float, 4>), grid, block, 0, h->stream, a);
+    }
+    h->loss_parts_train = 1;
+    timing_stop(h, kTimeBwd);
+    return hipGetLastError();
+}
+
+}  // namespace
+
 hipError_t launch_resident(lc_handle* h, int n_steps) {
+    if (h->L == 1) return launch_resident1(h, 0, n_steps);
     const ActSet& S = h->train;
     const bool bf16 = h->md.gemm == LC_GEMM_BF16;
     ResArgs a;

@@ -240,8 +240,10 @@ def test_update_from_grad_and_fused_average(pkg, orc, m, P):
 def _resident_shape(dims, m, B):
     """Shapes lc_set_resident documents as taking the resident step kernel."""
     up64 = lambda d: (d + 63) // 64 * 64
+    if len(dims) == 2:
+        return dims[1] <= 16 and B <= 64 and up64(dims[0]) <= 256
     return (len(dims) == 3 and dims[2] <= 16 and B <= 64 and up64(dims[0]) <= 1024 and up64(dims[1]) <= 256
-            and m * up64(dims[1]) // 16 <= 256)
+            and m <= 64 and m * up64(dims[1]) // 16 <= 256)
 
 
 @pytest.mark.parametrize("resident", [True, False])
@@ -310,7 +312,10 @@ def test_plain_sgd_without_momentum_and_repeatability(pkg, orc):
 
 
 RESIDENT_CASES = [
-    # dims, m, B: unaligned rows and a ragged batch; two column slices and one; the 2-layer configuration
+    # dims, m, B: softmax regression (one workgroup per replica, no exchange), ragged; then two layers:
+    # unaligned rows and a ragged batch; two column slices and one; the 2-layer configuration
+    ([70, 7], 5, 20),
+    ([64, 10], 4, 32),
     ([67, 129, 10], 3, 33),
     ([96, 64, 16], 5, 64),
     ([784, 256, 10], 8, 64),
@@ -522,12 +527,13 @@ def test_refined_schedule_bit_exact(pkg, orc):
     run.close()
 
 
+@pytest.mark.parametrize("dims", [[130, 70, 33, 7], [96, 64, 10]])   # per-layer kernels; resident kernel
 @pytest.mark.parametrize("bf16", [False, True])
-def test_block_momentum_rounds(pkg, orc, bf16):
+def test_block_momentum_rounds(pkg, orc, bf16, dims):
     """Block momentum (global factor 0.3, local 0.9, local buffers restarted at every
     averaging step) over several periods against the oracle."""
-    dims, m, B, tau = [130, 70, 33, 7], 4, 48, 3
-    _say(f"block momentum bf16={bf16}")
+    m, B, tau = 4, 48, 3
+    _say(f"block momentum bf16={bf16} dims={dims}")
     ref, run = _problem(pkg, orc, dims, m, B, lr=0.05, beta=0.9, bf16=bf16)
     tol = TOL16 if bf16 else TOL32
     ref.block_begin(0.3)
