@@ -39,10 +39,10 @@ FLAT = {"cfg5a": (16, 25_600_000), "cfg5b": (8, 138_000_000)}
 # path it is the one kernel.  Summaries with the commands are in profiles/pmc_traffic_mfma_<workload>.txt.
 PMC = {
     "cfg2": {"traffic": (28.105e6 + 2.381e6) / 2, "mfma_busy_pct": (8.34 * 9.2 + 1.16 * 8.8) / 18.0},
-    "cfg3": {"traffic": (822.271e6 + 288.509e6 + 15.963e6) / 3,
-             "mfma_busy_pct": (3.20 * 152.6 + 4.35 * 71.6 + 1.10 * 10.3) / 234.5},
-    "cfg4": {"traffic": (6463.755e6 + 2 * 4335.111e6 + 46.455e6) / 4,
-             "mfma_busy_pct": (0.82 * 1280 + 1.65 * 1160 + 1.19 * 20) / 2460},
+    "cfg3": {"traffic": (822.251e6 + 288.474e6 + 15.963e6) / 3,
+             "mfma_busy_pct": (3.21 * 150.0 + 4.38 * 71.6 + 1.13 * 10.3) / 231.9},
+    "cfg4": {"traffic": (6463.943e6 + 2 * 4335.461e6 + 46.455e6) / 4,
+             "mfma_busy_pct": (0.87 * 1190 + 1.63 * 1620 + 1.19 * 27) / 2837},
 }
 PMC_RESIDENT = {
     "cfg2": {"traffic": 56.525e6, "mfma_busy_pct": 13.55},   # per launch of 5 local steps
