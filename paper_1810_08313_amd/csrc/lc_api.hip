@@ -256,9 +256,10 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     // 256 MB: the size of the memory-side cache; below it weights are worth keeping cached
     h->stream_weights = 8.0 * static_cast<double>(m) * static_cast<double>(h->Ps) > 256.0 * 1024 * 1024;
     h->avg_two_phase = true;
-    // chunk of one row that the broadcast re-reads from cache (measured optimum: 24 MB, just
-    // under the 32 MB of L2; 8 MB when very many rows follow each reduce)
-    h->avg_chunk_floats = (m >= 48 ? 2 : 6) * 1024 * 1024;
+    // chunk of one row that the broadcast re-reads from cache (measured optima: 24 MB for few
+    // rows, 22 MB from a dozen rows on, 8 MB when very many rows follow each reduce; above 24 MB
+    // the rate falls off sharply)
+    h->avg_chunk_floats = (m >= 48 ? 8 : m >= 12 ? 22 : 24) * 256 * 1024;
     if (const char* e = getenv("LC_AVG_CHUNK_MB")) {   // tuning knobs for measurement runs
         const int mb = atoi(e);
         if (mb >= 1 && mb <= 1024) h->avg_chunk_floats = static_cast<int64_t>(mb) * 256 * 1024;
