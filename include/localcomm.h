@@ -138,7 +138,7 @@ int lc_attach_quad(lc_handle* h, const float* a, const float* c);
  * Errors: LC_ERR_ARG (tau < 1), LC_ERR_STATE, LC_ERR_HIP. */
 int lc_local_steps(lc_handle* h, int tau);
 
-/* The averaging step (Sec. 2, the "k mod tau = 0" branch): every row of X is
+/* The averaging step (Sec. 2: the branch of the update rule taken when k is a multiple of tau): every row of X is
  * replaced by the mean of all rows, X <- X J with J = 11^T/m (Appendix).  V is
  * not touched.  Afterwards all rows are bit-identical; calling it twice changes
  * nothing more.  Asynchronous. */
@@ -194,7 +194,7 @@ int adacomm_next_tau(double F0, double Fl, int tau0);
 /* AdaComm with the refinements of Sec. 4.3.  Candidate
  *   c = ceil( sqrt( (lr0 / lrl) * Fl / F0 ) * tau0 )      (Sec. 4.3.2, practical coupling; lr0 = lrl
  *                                                           gives the basic rule)
- * "Faster decay when training saturates" (Sec. 4.3.1): c is taken only if c + slack < tau_prev,
+ * Saturation refinement (Sec. 4.3.1): c is taken only if c + slack < tau_prev,
  * otherwise the period becomes ceil(gamma * tau_prev), 0 < gamma <= 1 (the paper uses 1/2).  At the
  * first decision after a learning-rate change (lr_changed != 0) c is taken as it is: the coupling
  * exists to let the period grow there.  Evaluated in IEEE double in this order: Fl/F0, lr0/lrl,
@@ -221,8 +221,7 @@ int lc_run(lc_handle* h, int64_t K, int tau0, int adaptive, int64_t interval,
  * in force at entry).  The learning-rate schedule is n_lr pairs: from iteration lr_at[j] on
  * (counted from 0 at lc_init, increasing) the rate is lr_val[j].  Changes take effect at
  * averaging steps only; with postpone_lr != 0 a due change waits until the period has reached 1
- * ("first gradually decay the communication period to 1 and then decay the learning rate",
- * Sec. 4.3.2).  sched_lr (host, capacity cap) receives the rate in force after each decision.
+ * (Sec. 4.3.2: the period is brought down to 1 first, the rate is lowered only then).  sched_lr (host, capacity cap) receives the rate in force after each decision.
  * F_0 is always evaluated, so interval >= 1 is required. */
 int lc_run_ex(lc_handle* h, int64_t K, int tau0, int64_t interval, int refine, double gamma, int slack,
               int n_lr, const int64_t* lr_at, const float* lr_val, int postpone_lr,

@@ -58,12 +58,12 @@ typedef struct orc_state orc_state;
 uint64_t orc_mix64(uint64_t z);
 
 /* Mini-batch index stream: sample b of worker i at local iteration k (k counts
- * from 0) is drawn with replacement from the whole dataset (Sec. 2, "randomly
- * sampled mini-batch", one stream per worker as in the tau=1 special case). */
+ * from 0) is drawn with replacement from the whole dataset (Sec. 2: a random
+ * mini-batch per step, one stream per worker as in the tau=1 special case). */
 int64_t orc_index(uint64_t seed, int i, int64_t k, int b, int64_t N);
 
-/* Partition sampler (Sec. 5.1, "Dataset": each worker is assigned a partition which is randomly
- * shuffled after every epoch).  Worker i of m owns samples [floor(i N / m), floor((i+1) N / m));
+/* Partition sampler (Sec. 5.1, dataset paragraph: every worker owns one partition of the data and
+ * reshuffles it after each epoch).  Worker i of m owns samples [floor(i N / m), floor((i+1) N / m));
  * an epoch is S = floor(min_i n_i / B) iterations; in epoch e = k / S the worker walks a pseudo-random
  * permutation of its partition (4-round Feistel network keyed by seed, worker and epoch, with cycle
  * walking), B positions per iteration.  Returns the dataset index, or -1 if a partition is smaller
@@ -97,8 +97,8 @@ void orc_sgd_update(int64_t P, float* x, float* v, const float* g, float lr, flo
 int orc_next_tau(double F0, double Fl, int tau0);
 
 /* AdaComm refinements (Sec. 4.3): candidate c = ceil( sqrt( (lr0/lrl) * Fl/F0 ) * tau0 ), the
- * practical learning-rate coupling of Sec. 4.3.2 (lr0 = lrl gives the basic rule).  "Faster
- * decay when training saturates" (Sec. 4.3.1): c is taken only if c + slack < tau_prev,
+ * practical learning-rate coupling of Sec. 4.3.2 (lr0 = lrl gives the basic rule).  Saturation
+ * refinement (Sec. 4.3.1): c is taken only if c + slack < tau_prev,
  * otherwise the period becomes ceil(gamma * tau_prev).  At the first decision after a
  * learning-rate change (lr_changed != 0) c is taken as it is, since the coupling exists to let
  * the period grow there.  Result at least 1; negative on invalid input. */

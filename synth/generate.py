@@ -3,7 +3,7 @@
 The recipes follow the workloads named for this build (Gaussian-mixture
 classification sets, CIFAR-shaped uniform images with a class offset, flat
 parameter vectors for the averaging stress).  They stand in for the CIFAR-10 /
-CIFAR-100 image sets of the paper's Sec. 5.1 ("Platform" / "Datasets"): same
+CIFAR-100 image sets of the paper's Sec. 5.1 (platform and dataset paragraphs): same
 feature count (32*32*3 = 3072), same sample count (50 000) and class count, but
 no item of those sets is reproduced.
 
