@@ -157,8 +157,8 @@ int lc_materialize(lc_handle* h);
 
 /* Resident local steps (Sec. 2: a worker's tau local updates touch only its own model).  For
  * two-layer LC_KIND_MLP models with at most 16 classes, B <= 64, padded widths d0 <= 1024 and
- * d1 <= 256, m <= 64 and m * ceil64(d1) / 16 <= 256, lc_local_steps() runs up to 8 consecutive
- * steps as ONE kernel: each workgroup keeps a 16-unit slice of the first layer and its momentum
+ * d1 <= 256, m <= 64 and m * ceil64(d1) / 16 <= 256, lc_local_steps() runs up to 32 consecutive
+ * steps (8 when the gathered inputs of a step exceed 4 MB) as ONE kernel: each workgroup keeps a 16-unit slice of the first layer and its momentum
  * on chip (LDS and registers) for all of them, and the workgroups of a replica meet once per step
  * at a barrier in device memory to exchange the hidden activations.  One-layer models (softmax
  * regression) with at most 16 classes, B <= 64 and padded d0 <= 256 take the same route with one

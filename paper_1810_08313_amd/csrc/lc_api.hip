@@ -103,7 +103,14 @@ size_t carve(lc_handle* h, char* base) {
             S.B = h->md.B;
             S.Bp = padded_batch(h->md.B);
         }
-        S.slots = eval ? 1 : kGatherSlots;
+        S.slots = 1;
+        if (!eval) {
+            // 8 steps' inputs per gather launch; up to 32 where they are small (the resident step
+            // kernel then also takes that many steps per launch), within about 128 MB
+            const size_t slot_bytes = 2 * static_cast<size_t>(S.G) * S.Bp * h->layer[1].dp_in * ot;
+            size_t n = (static_cast<size_t>(128) << 20) / slot_bytes;
+            S.slots = n < kGatherSlots ? kGatherSlots : (n > 4 * kGatherSlots ? 4 * kGatherSlots : static_cast<int>(n));
+        }
         S.cur_slot = 0;
         for (int l = 0; l <= L; ++l) {
             const size_t dp = static_cast<size_t>(l == 0 ? h->layer[1].dp_in : h->layer[l].dp_out);
@@ -339,8 +346,9 @@ int lc_local_steps(lc_handle* h, int tau) {
     const int rc = require_objective(h);
     if (rc != LC_OK) return rc;
     if (tau < 1) return LC_ERR_ARG;
-    for (int t0 = 0; t0 < tau; t0 += kGatherSlots) {
-        const int n = tau - t0 < kGatherSlots ? tau - t0 : kGatherSlots;
+    const int slots = h->md.kind == LC_KIND_MLP ? h->train.slots : kGatherSlots;
+    for (int t0 = 0; t0 < tau; t0 += slots) {
+        const int n = tau - t0 < slots ? tau - t0 : slots;
         // mini-batch selection does not depend on the weights: one launch prepares the inputs
         // of the next n steps
         if (h->md.kind == LC_KIND_MLP) LC_HIP(h, launch_gather(h, false, h->k, n));

@@ -21,7 +21,7 @@ constexpr int kWave = 64;
 constexpr int kColChunk = 64;   // columns of W handled per wave and per loop trip
 constexpr int kRowsPerWave = 16;
 constexpr int kXcds = 8;
-constexpr int kGatherSlots = 8;  // local steps whose mini-batches one gather launch prepares
+constexpr int kGatherSlots = 8;  // local steps whose mini-batches one gather launch prepares (at least; see carve())
 constexpr int kLossParts = 8;    // partial loss sums per group (one per block that shares a group's batch)
 
 inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }

@@ -325,9 +325,9 @@ RESIDENT_CASES = [
 @pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("dims,m,B", RESIDENT_CASES)
 def test_resident_rounds_against_oracle_and_layer_kernels(pkg, orc, dims, m, B, bf16):
-    """Runs of local steps inside one launch (5 steps, then 11 = 8 + 3 in two launches) with
-    averaging in between, deferred broadcast on: against the oracle, and against the
-    launch-per-layer kernels (same arithmetic, other summation order)."""
+    """Runs of local steps inside one launch each (5 steps, then 11; the state goes back to
+    memory and is reloaded in between) with averaging in between, deferred broadcast on: against
+    the oracle, and against the launch-per-layer kernels (same arithmetic, other summation order)."""
     assert _resident_shape(dims, m, B)
     _say(f"resident rounds dims={dims} m={m} B={B} bf16={bf16}")
     tol = TOL16 if bf16 else TOL32
