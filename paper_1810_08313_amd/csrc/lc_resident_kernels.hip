@@ -26,7 +26,9 @@
 // poll with relaxed loads, then an agent-scope acquire.  All workgroups of a launch are
 // co-resident (the launcher refuses grids above one workgroup per compute unit), and the
 // poll loop is bounded: a workgroup that runs out of polls raises the error flag, stops
-// waiting for good and finishes its steps, so the grid always drains.
+// waiting for good and finishes its steps, so the grid always drains.  (A cooperative launch
+// would have the runtime vouch for the co-residency, but costs 18 us more per launch here, a
+// tenth of the throughput at five steps per launch; the bounded wait covers the same case.)
 #include "lc_internal.h"
 #include "lc_mma.h"
 
