@@ -1072,7 +1072,7 @@ hipError_t launch_fwd_cfg(const FwdArgs& a, int mt, bool wide, bool afm, unsigne
     hipLaunchKernelGGL((forward_kernel<OT, MT_, NW_, PF_, WM, AFM_>), dim3(grid), dim3(NW_ * 64), 0, s, a)
     switch (mt) {
         case 1: if (wide) LC_FWD(1, 8, 3, false); else LC_FWD(1, 4, 3, false); break;
-        case 2: if (wide) LC_FWD(2, 8, 3, false); else LC_FWD(2, 4, 3, false); break;
+        case 2: if (wide) LC_FWD(2, 8, 3, false); else LC_FWD(2, 4, 1, false); break;   // many blocks: occupancy 3 beats a deeper queue
         case 4: if (wide) LC_FWD(4, 8, 1, false); else LC_FWD(4, 4, 3, false); break;
         case 8: if (afm) LC_FWD(8, 4, 1, true); else LC_FWD(8, 4, 1, false); break;
         default: return hipErrorInvalidValue;
