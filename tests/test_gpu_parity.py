@@ -700,6 +700,37 @@ def test_full_size_local_step_sampled_replicas(pkg, orc, name, replicas):
     run.close()
 
 
+def test_cfg2_full_configuration_periods(pkg, orc):
+    """The 2-layer configuration exactly as the benchmark runs it (m=8, B=64, 60k samples,
+    momentum 0.9, tau=5, deferred broadcast, resident step kernel): two periods against the
+    oracle on all replicas."""
+    _say("cfg2 full configuration")
+    w = synth.make_workload("cfg2")
+    omd = orc.make_model(orc.KIND_MLP, w.dims, B=w.B, N=w.N, E=w.E, lr=w.lr, beta=w.beta, wd=w.wd, bf16=False)
+    gmd = pkg.make_model(pkg.KIND_MLP, w.dims, B=w.B, N=w.N, E=w.E, lr=w.lr, beta=w.beta, wd=w.wd, bf16=False)
+    run = pkg.LocalSGD(w.m, gmd, w.seed, w.x1, w.data, w.labels)
+    run.set_lazy_broadcast(True)
+    assert run.resident_active()
+    orc.set_threads(8)
+    ref = orc.Run(w.m, omd, w.seed, w.x1, w.data, w.labels)
+    for period in range(2):
+        ref.local_steps(w.tau0)
+        run.local_steps(w.tau0)
+        X, V, k = run.get_state()
+        assert k == ref.k == w.tau0 * (period + 1)
+        _assert_close(X, ref.X, w.dims, TOL32 * 4, f"X period {period}")
+        _assert_close(V, ref.V, w.dims, TOL32 * 8, f"V period {period}")
+        ll = run.local_losses()
+        assert np.abs(ll - ref.last_losses).max() < 4 * TOL32 * max(np.abs(ref.last_losses).max(), 1e-3)
+        ref.average()
+        run.average()
+    orc.set_threads(1)
+    X, _, _ = run.get_state()
+    _assert_close(X, ref.X, w.dims, TOL32 * 4, "X after averaging")
+    assert all(np.array_equal(X[i], X[0]) for i in range(1, w.m))
+    run.close()
+
+
 @pytest.mark.parametrize("m,P", [(16, 25_600_000), (8, 138_000_000)])
 def test_full_size_averaging_and_update(pkg, m, P):
     """The averaging stress sizes: sampled columns against the exact mean, all
