@@ -167,7 +167,10 @@ int lc_materialize(lc_handle* h);
  * on = 0 selects the launch-per-layer path for every shape; the default is on.  Shapes outside
  * the limits always take the launch-per-layer path.  The barrier wait is bounded: if it ever
  * times out the kernel still terminates, and the next synchronising call (lc_loss,
- * lc_get_state, lc_get_local_losses) returns LC_ERR_SYNC; the state is then undefined. */
+ * lc_get_state, lc_get_local_losses) returns LC_ERR_SYNC; the state is then undefined.  The
+ * barrier needs all workgroups of the launch on the chip together: that holds when the kernel
+ * has the GPU to itself (at most 256 workgroups, one per compute unit), not necessarily when
+ * other streams keep compute units busy at the same time -- turn the mode off for such use. */
 int lc_set_resident(lc_handle* h, int on);
 /* 1 if lc_local_steps() of this (attached) handle takes the resident step kernel, else 0. */
 int lc_resident_active(const lc_handle* h);
