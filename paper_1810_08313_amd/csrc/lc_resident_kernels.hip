@@ -13,7 +13,7 @@
 //   keeps  a full private copy of W_2, V_2, b_2 (d1 x d2 is tiny), updated identically by
 //          every workgroup of the replica, so the second layer needs no exchange at all.
 // One step:
-//   (1) A_1[:, C] = ReLU(A_0 W_1[:, C] + b_1[C])          MFMA, K split over the 4 wavefronts
+//   (1) A_1[:, C] = ReLU(A_0 W_1[:, C] + b_1[C])          MFMA; the 16 wavefronts split batch tiles and K
 //   (2) publish the slice, replica-wide barrier, every workgroup then sees all of A_1
 //   (3) Z_2 = A_1 W_2 + b_2, softmax cross-entropy, dZ_2   (redundantly in every workgroup)
 //   (4) dZ_1[:, C] = (dZ_2 W_2[C, :]^T) .* [A_1[:, C] > 0]  with the weights of before the update
@@ -23,7 +23,9 @@
 // buffered by step parity so that a fast workgroup never overwrites what a slow one still reads.
 //
 // The barrier is a counter per replica in device memory: arrive with an agent-scope release,
-// poll with relaxed loads, then an agent-scope acquire.  All workgroups of a launch are
+// poll with relaxed loads, then an agent-scope acquire.  The slices are published with
+// agent-scope (write-through) stores, so the release has no dirty cache lines to write back;
+// the counters are never reset, each launch is told their value at its start.  All workgroups of a launch are
 // co-resident (the launcher refuses grids above one workgroup per compute unit), and the
 // poll loop is bounded: a workgroup that runs out of polls raises the error flag, stops
 // waiting for good and finishes its steps, so the grid always drains.  (A cooperative launch
