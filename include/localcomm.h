@@ -144,6 +144,21 @@ int lc_local_steps(lc_handle* h, int tau);
  * nothing more.  Asynchronous. */
 int lc_average(lc_handle* h);
 
+/* n_periods times { tau local iterations; averaging step } (Sec. 2: the PASGD update rule run
+ * over n_periods communication periods of length tau).  The result is that of calling
+ * lc_local_steps(h, tau); lc_average(h) n_periods times, and that is what happens for most
+ * shapes.  Where the resident step kernel applies (see lc_set_resident), tau is at most the
+ * number of steps it takes per launch, and the model is small (one layer; or two layers with
+ * m * ceil64(d0) * 64 bytes <= 200 KB, the amount a workgroup then reads from the other replicas),
+ * several whole periods are ONE launch: at an averaging step every workgroup hands over its part
+ * of the model, all workgroups of all replicas meet at a barrier in device memory (bounded wait,
+ * LC_ERR_SYNC as described at lc_set_resident), and each forms the mean of its own part -- same
+ * arithmetic as lc_average(), so the results are bit-identical to the call-by-call form with the
+ * resident kernel.  lc_set_resident(h, 2) lifts the size condition.  Not used while block
+ * momentum is on.  Afterwards every row of X holds the averaged model.  Asynchronous.
+ * Errors: LC_ERR_ARG (tau < 1 or n_periods < 1), LC_ERR_STATE, LC_ERR_HIP. */
+int lc_local_periods(lc_handle* h, int tau, int n_periods);
+
 /* Deferred broadcast.  With on != 0 (LC_KIND_MLP only) lc_average() only computes the averaged
  * model (reads m rows, writes one vector in scratch): the next local step reads that one model for
  * every replica -- it is served from cache m-1 times out of m -- and writes every row of X, as it
@@ -164,7 +179,9 @@ int lc_materialize(lc_handle* h);
  * regression) with at most 16 classes, B <= 64 and padded d0 <= 256 take the same route with one
  * workgroup per replica and no barrier.  Same arithmetic as the
  * launch-per-layer path up to the summation order (results agree to rounding, not bit for bit).
- * on = 0 selects the launch-per-layer path for every shape; the default is on.  Shapes outside
+ * on = 0 selects the launch-per-layer path for every shape; the default is on (1); on = 2
+ * additionally makes lc_local_periods() take the averaging steps inside the launch at every
+ * shape the kernel handles, also where ending the launch is the faster way.  Shapes outside
  * the limits always take the launch-per-layer path.  The barrier wait is bounded: if it ever
  * times out the kernel still terminates, and the next synchronising call (lc_loss,
  * lc_get_state, lc_get_local_losses) returns LC_ERR_SYNC; the state is then undefined.  The

@@ -79,6 +79,8 @@ def lib() -> C.CDLL:
     L.lc_attach_quad.argtypes = [vp, vp, vp]
     L.lc_local_steps.restype = C.c_int
     L.lc_local_steps.argtypes = [vp, C.c_int]
+    L.lc_local_periods.restype = C.c_int
+    L.lc_local_periods.argtypes = [vp, C.c_int, C.c_int]
     L.lc_average.restype = C.c_int
     L.lc_average.argtypes = [vp]
     L.lc_set_lazy_broadcast.restype = C.c_int
@@ -260,14 +262,19 @@ class LocalSGD:
     def local_steps(self, tau: int) -> None:
         self._check(self._L.lc_local_steps(self._h, int(tau)), "lc_local_steps")
 
+    def local_periods(self, tau: int, n_periods: int) -> None:
+        self._check(self._L.lc_local_periods(self._h, int(tau), int(n_periods)), "lc_local_periods")
+
     def average(self) -> None:
         self._check(self._L.lc_average(self._h), "lc_average")
 
     def set_lazy_broadcast(self, on: bool) -> None:
         self._check(self._L.lc_set_lazy_broadcast(self._h, int(bool(on))), "lc_set_lazy_broadcast")
 
-    def set_resident(self, on: bool) -> None:
-        self._check(self._L.lc_set_resident(self._h, int(bool(on))), "lc_set_resident")
+    def set_resident(self, on) -> None:
+        """False/0: launch-per-layer kernels; True/1: resident step kernel where it applies; 2: and
+        in-kernel averaging steps at every shape it handles (see lc_local_periods)."""
+        self._check(self._L.lc_set_resident(self._h, int(on)), "lc_set_resident")
 
     def resident_active(self) -> bool:
         rc = self._L.lc_resident_active(self._h)

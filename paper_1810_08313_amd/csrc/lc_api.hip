@@ -130,9 +130,11 @@ size_t carve(lc_handle* h, char* base) {
     if (resident_shape_ok(h)) {
         h->res_a1x = static_cast<float*>(c.take(sizeof(float) * 2 * resident_exchange_floats(h)));
         h->res_ctr = static_cast<unsigned*>(c.take(sizeof(unsigned) * 128));
+        h->res_avx = static_cast<float*>(c.take(sizeof(float) * 2 * static_cast<size_t>(h->m) * h->Ps));
     } else {
         h->res_a1x = nullptr;
         h->res_ctr = nullptr;
+        h->res_avx = nullptr;
     }
     h->n_partial = 0;
     h->partial = nullptr;
@@ -196,6 +198,18 @@ int check_resident(lc_handle* h) {
     if (flag == 0) return LC_OK;
     LC_HIP(h, hipMemsetAsync(h->res_ctr + 64, 0, sizeof(unsigned), h->stream));
     return LC_ERR_SYNC;
+}
+
+// Whole periods of tau iterations that can be taken from iteration k on without looking at the
+// schedule in between: it is looked at again at the first averaging step at or after `lim` (the
+// next loss evaluation, learning-rate change, or the end).  0 when less than one period is left.
+int whole_periods(int64_t k, int tau, int64_t lim, int64_t k_end) {
+    const int64_t fit = (k_end - k) / tau;
+    if (fit < 1) return 0;
+    int64_t np = lim > k ? (lim - k + tau - 1) / tau : 1;
+    if (np > fit) np = fit;
+    if (np > 65536) np = 65536;
+    return static_cast<int>(np);
 }
 
 }  // namespace
@@ -283,8 +297,10 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     h->res_a1x = nullptr;
     h->res_ctr = nullptr;
     h->res_on = true;
+    h->res_fuse_always = false;
     h->res_used = false;
     h->res_arrivals = 0;
+    h->res_garrivals = 0;
     h->res_spin_limit = 400000;   // several hundred milliseconds of polling
     h->timing_which = kTimeNone;
     h->ev_used = 0;
@@ -328,6 +344,7 @@ int lc_attach(lc_handle* h, void* X, void* V, void* scratch, size_t scratch_byte
     (void)carve(h, h->scratch);
     LC_HIP(h, hipMemsetAsync(scratch, 0, need, h->stream));
     h->res_arrivals = 0;
+    h->res_garrivals = 0;
     LC_HIP(h, hipStreamSynchronize(h->stream));
     h->attached = true;
     return LC_OK;
@@ -354,7 +371,7 @@ int lc_local_steps(lc_handle* h, int tau) {
         if (h->md.kind == LC_KIND_MLP) LC_HIP(h, launch_gather(h, false, h->k, n));
         if (h->res_on && h->res_a1x) {
             // small two-layer model: the n steps are one launch with the weights held on chip
-            LC_HIP(h, launch_resident(h, n));
+            LC_HIP(h, launch_resident(h, n, 0));
             h->train.cur_slot = n - 1;
             h->k += n;
             h->v_cleared = false;
@@ -367,6 +384,40 @@ int lc_local_steps(lc_handle* h, int tau) {
             const int r = one_local_step(h);
             if (r != LC_OK) return r;
         }
+    }
+    return LC_OK;
+}
+
+int lc_local_periods(lc_handle* h, int tau, int n_periods) {
+    const int rc = require_objective(h);
+    if (rc != LC_OK) return rc;
+    if (tau < 1 || n_periods < 1) return LC_ERR_ARG;
+    // In-kernel averaging pays while the m copies a workgroup has to read from the other replicas
+    // (other XCDs) are small: measured on the 784-256-10 model at m = 8, 400 KB per workgroup take
+    // 15 us, more than ending the launch and running the averaging kernel costs.
+    const bool small = h->L == 1 || static_cast<int64_t>(h->m) * h->layer[1].dp_in * 64 <= 200 * 1024;
+    const bool fused = h->md.kind == LC_KIND_MLP && h->res_on && h->res_a1x && h->res_avx && !h->bm_on &&
+                       tau <= h->train.slots && (small || h->res_fuse_always);
+    if (!fused) {
+        for (int p = 0; p < n_periods; ++p) {
+            int e = lc_local_steps(h, tau);
+            if (e == LC_OK) e = lc_average(h);
+            if (e != LC_OK) return e;
+        }
+        return LC_OK;
+    }
+    // weights resident on chip: as many whole periods per launch as one gather launch has inputs
+    // for, the averaging steps taken inside the kernel
+    const int per_launch = h->train.slots / tau;
+    for (int done = 0; done < n_periods; done += per_launch) {
+        const int p = n_periods - done < per_launch ? n_periods - done : per_launch;
+        LC_HIP(h, launch_gather(h, false, h->k, p * tau));
+        LC_HIP(h, launch_resident(h, p * tau, tau));
+        h->train.cur_slot = p * tau - 1;
+        h->k += static_cast<int64_t>(p) * tau;
+        h->v_cleared = false;
+        h->lazy_rows = false;   // every row of X holds the mean
+        h->res_used = true;
     }
     return LC_OK;
 }
@@ -406,6 +457,7 @@ int lc_set_lazy_broadcast(lc_handle* h, int on) {
 int lc_set_resident(lc_handle* h, int on) {
     if (!h) return LC_ERR_ARG;
     h->res_on = on != 0;
+    h->res_fuse_always = on == 2;
     return LC_OK;
 }
 
@@ -570,11 +622,17 @@ int lc_run_ex(lc_handle* h, int64_t K, int tau0, int64_t interval, int refine, d
     const int64_t k_end = h->k + K;
     while (h->k < k_end) {
         const int64_t left = k_end - h->k;
-        const int t = static_cast<int64_t>(tau) < left ? tau : static_cast<int>(left);
-        e = lc_local_steps(h, t);
-        if (e == LC_OK) e = lc_average(h);
+        int64_t lim = next_eval < k_end ? next_eval : k_end;
+        if (next_lr < n_lr && lr_at[next_lr] < lim) lim = lr_at[next_lr];
+        const int np = whole_periods(h->k, tau, lim, k_end);
+        if (np > 0) {
+            e = lc_local_periods(h, tau, np);
+        } else {
+            e = lc_local_steps(h, static_cast<int>(left));   // the last, shortened period
+            if (e == LC_OK) e = lc_average(h);
+        }
         if (e != LC_OK) return e;
-        ++r;
+        r += np > 0 ? np : 1;
         while (next_lr < n_lr && h->k >= lr_at[next_lr] && (!postpone_lr || tau == 1)) {
             h->md.lr = lr_val[next_lr];
             ++next_lr;
@@ -630,11 +688,16 @@ int lc_run(lc_handle* h, int64_t K, int tau0, int adaptive, int64_t interval, in
     const int64_t k_end = h->k + K;
     while (h->k < k_end) {
         const int64_t left = k_end - h->k;
-        const int t = static_cast<int64_t>(tau) < left ? tau : static_cast<int>(left);
-        int e = lc_local_steps(h, t);
-        if (e == LC_OK) e = lc_average(h);
+        const int np = whole_periods(h->k, tau, adaptive && next_eval < k_end ? next_eval : k_end, k_end);
+        int e;
+        if (np > 0) {
+            e = lc_local_periods(h, tau, np);
+        } else {
+            e = lc_local_steps(h, static_cast<int>(left));   // the last, shortened period
+            if (e == LC_OK) e = lc_average(h);
+        }
         if (e != LC_OK) return e;
-        ++r;
+        r += np > 0 ? np : 1;
         if (adaptive && h->k >= next_eval && h->k < k_end) {
             double Fl = 0.0;
             e = lc_loss(h, &Fl);

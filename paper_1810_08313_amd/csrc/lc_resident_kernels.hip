@@ -69,10 +69,130 @@ struct ResArgs {
     unsigned* err;        // set to 1 when a barrier wait ran out of polls
     int spin_limit;       // polls one barrier wait may take
     float* loss;          // [G][kLossParts], slot 0 written
+    int period;           // averaging step after every `period` steps inside the launch; 0: none
+    float* avx;           // [2][G][x_stride] models handed over at an averaging step, by parity of the period
+    unsigned* gctr;       // arrivals of all workgroups at averaging steps since attach
+    unsigned gctr_base;   // its value when this launch starts
 };
+
+// Barrier among the workgroups that add to *ctr, called by one thread per workgroup after a
+// workgroup barrier: what the workgroup wrote before is visible to every workgroup that leaves
+// the wait.  The wait is bounded; a workgroup that runs out of polls raises the error flag and
+// never waits again (it still arrives, so the counts stay right), so the grid always drains.
+__device__ __forceinline__ void arrive_and_wait(unsigned* ctr, unsigned target, int spin_limit, unsigned* err,
+                                                bool& gave_up) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int polls = 0;
+    while (!gave_up) {
+        const unsigned seen = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (static_cast<int>(seen - target) >= 0) break;
+        if (++polls > spin_limit) {
+            gave_up = true;
+            atomicExch(err, 1u);
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+}
+
+// x_bar = (1/m) sum_i x^(i) of one entry (Sec. 2, the averaging step), summed in double in
+// replica order and rounded once: the same arithmetic, bit for bit, as the averaging kernels.
+__device__ __forceinline__ float mean_of_replicas(const float* p, int64_t stride, int G) {
+    double s = 0.0;
+    for (int i0 = 0; i0 < G; i0 += 8) {   // eight loads in flight, added in replica order
+        float r[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (i0 + u < G) r[u] = p[(i0 + u) * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (i0 + u < G) s += static_cast<double>(r[u]);
+    }
+    return static_cast<float>(s / static_cast<double>(G));
+}
 
 __device__ __forceinline__ float round_operand(float x, bf16_t) { return static_cast<float>(static_cast<bf16_t>(x)); }
 __device__ __forceinline__ float round_operand(float x, float) { return x; }
+
+// The averaging step inside a resident launch (Sec. 2: after tau local updates the models are
+// replaced by their mean; the momentum buffers stay local).  Every workgroup hands over its part
+// of the model, waits for all workgroups of all replicas, and forms the mean of its own part from
+// the m copies.  Two buffers, by parity of the period: a workgroup overwrites a buffer only after
+// the barrier of the period in between, which every reader of the older contents has reached by
+// then.
+__device__ __forceinline__ void average_resident(const ResArgs& a, int tid, int pi, int g, int cb,
+                                                 float (*w1s)[kResK1P], float (*w2s)[kResK2P], float* b1s,
+                                                 float* b2s, bool& gave_up) {
+    const int wave = tid >> 6, j = tid & 15, q = (tid >> 4) & 3;
+    const int c_base = 16 * cb, n_kt = a.dp0 / 16;
+    const bool vec = a.vec != 0;
+    float* all = a.avx + static_cast<int64_t>(pi & 1) * a.G * a.x_stride;
+    float* mine = all + g * a.x_stride;
+    for (int kt = wave; kt < n_kt; kt += kResWaves) {
+        const int k = 16 * kt + j, c = c_base + 4 * q;
+        if (k < a.d0) {
+            const float4 w = make_float4(w1s[4 * q + 0][k], w1s[4 * q + 1][k], w1s[4 * q + 2][k], w1s[4 * q + 3][k]);
+            store_w4(mine + a.w1_off + static_cast<int64_t>(k) * a.d1, c, a.d1, vec, false, w);
+        }
+    }
+    if (tid < 16 && c_base + tid < a.d1) mine[a.b1_off + c_base + tid] = b1s[tid];
+    if (cb == 0) {
+        for (int e = tid; e < a.d1 * a.d2; e += kResThreads) mine[a.w2_off + e] = w2s[e % a.d2][e / a.d2];
+        if (tid < a.d2) mine[a.b2_off + tid] = b2s[tid];
+    }
+    __builtin_amdgcn_s_waitcnt(0);   // this wavefront's stores have left before the workgroup arrives
+    __syncthreads();
+    if (tid == 0)
+        arrive_and_wait(a.gctr, a.gctr_base + static_cast<unsigned>(pi + 1) * static_cast<unsigned>(a.G * a.NB),
+                        a.spin_limit, a.err, gave_up);
+    __syncthreads();
+    for (int kt = wave; kt < n_kt; kt += kResWaves) {
+        const int k = 16 * kt + j, c = c_base + 4 * q;
+        if (k < a.d0) {
+            const float* src = all + a.w1_off + static_cast<int64_t>(k) * a.d1;
+            double s0 = 0, s1 = 0, s2 = 0, s3 = 0;
+            for (int g0 = 0; g0 < a.G; g0 += 8) {
+                float4 r[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (g0 + u < a.G) r[u] = load_w4(src + (g0 + u) * a.x_stride, c, a.d1, vec, false);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (g0 + u < a.G) {
+                        s0 += static_cast<double>(r[u].x);
+                        s1 += static_cast<double>(r[u].y);
+                        s2 += static_cast<double>(r[u].z);
+                        s3 += static_cast<double>(r[u].w);
+                    }
+            }
+            const double dm = static_cast<double>(a.G);
+            w1s[4 * q + 0][k] = static_cast<float>(s0 / dm);
+            w1s[4 * q + 1][k] = static_cast<float>(s1 / dm);
+            w1s[4 * q + 2][k] = static_cast<float>(s2 / dm);
+            w1s[4 * q + 3][k] = static_cast<float>(s3 / dm);
+        }
+    }
+    // the second layer and the biases: every thread's loads first, then its stores
+    constexpr int kPer = kResMaxD1 * 16 / kResThreads;
+    float mw2[kPer];
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+        const int e = tid + u * kResThreads;
+        mw2[u] = e < a.d1 * a.d2 ? mean_of_replicas(all + a.w2_off + e, a.x_stride, a.G) : 0.f;
+    }
+    float mb = 0.f;
+    const bool has_b1 = tid < 16 && c_base + tid < a.d1, has_b2 = tid >= 64 && tid < 64 + a.d2;
+    if (has_b1) mb = mean_of_replicas(all + a.b1_off + c_base + tid, a.x_stride, a.G);
+    if (has_b2) mb = mean_of_replicas(all + a.b2_off + tid - 64, a.x_stride, a.G);
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+        const int e = tid + u * kResThreads;
+        if (e < a.d1 * a.d2) w2s[e % a.d2][e / a.d2] = mw2[u];
+    }
+    if (has_b1) b1s[tid] = mb;
+    if (has_b2) b2s[tid - 64] = mb;
+    __syncthreads();
+}
 
 template <typename OT, int MT>
 __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
@@ -135,7 +255,15 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
     }
     __syncthreads();
     bool gave_up = false;   // thread 0: a barrier wait ran out of polls
-    for (int s = 0; s < a.n_steps; ++s) {
+    for (int s = 0; s < a.n_steps;) {
+    // One period (the whole launch when it has no averaging steps).  What the steps derive from
+    // the thread's id is derived afresh from an opaque copy per period, so that none of it is
+    // held in registers across the averaging step, which needs them for its own loads.
+    int tid_p = threadIdx.x;
+    asm volatile("" : "+v"(tid_p));
+    const int tid = tid_p, lane = tid & 63, wave = tid >> 6, j = lane & 15, q = lane >> 4;
+    const int s_end = a.period > 0 ? s + a.period : a.n_steps;
+    for (; s < s_end; ++s) {
         const float beta = s == 0 ? a.beta_first : a.beta;
         const int slot = a.slot0 + s;
         const OT* A0 = static_cast<const OT*>(a.a0_bm) + slot * a.a0_slot + static_cast<int64_t>(g) * Bp * a.dp0;
@@ -184,21 +312,9 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
 
         // ---- (2) replica-wide barrier
         __syncthreads();
-        if (tid == 0 && a.NB > 1) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-            __hip_atomic_fetch_add(&a.ctr[g], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const unsigned target = a.ctr_base + static_cast<unsigned>(s + 1) * static_cast<unsigned>(a.NB);
-            int polls = 0;
-            while (!gave_up) {
-                const unsigned seen = __hip_atomic_load(&a.ctr[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (static_cast<int>(seen - target) >= 0) break;
-                if (++polls > a.spin_limit) {
-                    gave_up = true;
-                    atomicExch(a.err, 1u);
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        }
+        if (tid == 0 && a.NB > 1)
+            arrive_and_wait(&a.ctr[g], a.ctr_base + static_cast<unsigned>(s + 1) * static_cast<unsigned>(a.NB),
+                            a.spin_limit, a.err, gave_up);
         __syncthreads();
         // ---- (3) logits: wavefront (mt, kpart) again, partial sums over its share of d1; then
         //      softmax cross-entropy and dZ_2, one thread per sample
@@ -341,6 +457,8 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
         }
         __syncthreads();
     }
+    if (a.period > 0) average_resident(a, tid, s / a.period - 1, g, cb, w1s, w2s, b1s, b2s, gave_up);
+    }
 
     // ---- write the state back
 #pragma unroll
@@ -393,6 +511,12 @@ struct Res1Args {
     int slot0, n_steps;
     float lr, beta_first, beta, wd;
     float* loss;            // [G][kLossParts], slot 0 written
+    int period;             // averaging step after every `period` steps inside the launch; 0: none
+    float* avx;             // [2][G][x_stride] models handed over at an averaging step
+    unsigned* gctr;         // arrivals at averaging steps since attach
+    unsigned gctr_base;
+    unsigned* err;
+    int spin_limit;
 };
 
 template <typename OT, int MT>
@@ -429,6 +553,7 @@ __global__ __launch_bounds__(kResThreads) void resident1_kernel(Res1Args a) {
     __syncthreads();
 
     const int mt = wave % MT, kpart = wave / MT;
+    bool gave_up = false;   // thread 0: a barrier wait ran out of polls
     for (int s = 0; s < a.n_steps; ++s) {
         const float beta = s == 0 ? a.beta_first : a.beta;
         const int slot = a.slot0 + s;
@@ -517,6 +642,24 @@ __global__ __launch_bounds__(kResThreads) void resident1_kernel(Res1Args a) {
             }
         }
         __syncthreads();
+        if (a.period == 0 || (s + 1) % a.period != 0) continue;
+        // ---- averaging step, as in the two-layer kernel: hand over the model, wait for all
+        //      replicas, take the mean of the m copies
+        const int pi = (s + 1) / a.period - 1;
+        float* all = a.avx + static_cast<int64_t>(pi & 1) * a.G * a.x_stride;
+        float* mine = all + g * a.x_stride;
+        for (int e = tid; e < a.d0 * a.d1; e += kResThreads) mine[a.w_off + e] = ws[e % a.d1][e / a.d1];
+        if (tid < a.d1) mine[a.b_off + tid] = bs[tid];
+        __builtin_amdgcn_s_waitcnt(0);   // this wavefront's stores have left before the workgroup arrives
+        __syncthreads();
+        if (tid == 0)
+            arrive_and_wait(a.gctr, a.gctr_base + static_cast<unsigned>(pi + 1) * static_cast<unsigned>(a.G),
+                            a.spin_limit, a.err, gave_up);
+        __syncthreads();
+        for (int e = tid; e < a.d0 * a.d1; e += kResThreads)
+            ws[e % a.d1][e / a.d1] = mean_of_replicas(all + a.w_off + e, a.x_stride, a.G);
+        if (tid < a.d1) bs[tid] = mean_of_replicas(all + a.b_off + tid, a.x_stride, a.G);
+        __syncthreads();
     }
 
     for (int e = tid; e < a.d0 * a.d1; e += kResThreads) {
@@ -553,7 +696,7 @@ bool resident_shape_ok(const lc_handle* h) {
 
 namespace {
 
-hipError_t launch_resident1(lc_handle* h, int slot0, int n_steps) {
+hipError_t launch_resident1(lc_handle* h, int slot0, int n_steps, int period) {
     const ActSet& S = h->train;
     const bool bf16 = h->md.gemm == LC_GEMM_BF16;
     Res1Args a;
@@ -580,7 +723,14 @@ hipError_t launch_resident1(lc_handle* h, int slot0, int n_steps) {
     a.beta = h->md.beta;
     a.wd = h->md.wd;
     a.loss = S.loss;
+    a.period = period;
+    a.avx = h->res_avx;
+    a.gctr = h->res_ctr + 65;
+    a.gctr_base = h->res_garrivals;
+    a.err = h->res_ctr + 64;
+    a.spin_limit = h->res_spin_limit;
     if (slot0 < 0 || n_steps < 1 || slot0 + n_steps > S.slots) return hipErrorInvalidValue;
+    if (period < 0 || (period > 0 && (n_steps % period != 0 || !h->res_avx || S.G > 256))) return hipErrorInvalidValue;
     if (S.Bp != 32 && S.Bp != 64) return hipErrorInvalidValue;
     if (a.dp0 > kResMaxD1 || a.d1 > 16) return hipErrorInvalidValue;
     timing_start(h, kTimeBwd);
@@ -593,14 +743,15 @@ hipError_t launch_resident1(lc_handle* h, int slot0, int n_steps) {
         else hipLaunchKernelGGL((resident1_kernel<float, 4>), grid, block, 0, h->stream, a);
     }
     h->loss_parts_train = 1;
+    if (period > 0) h->res_garrivals += static_cast<unsigned>(n_steps / period) * static_cast<unsigned>(S.G);
     timing_stop(h, kTimeBwd);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_resident(lc_handle* h, int n_steps) {
-    if (h->L == 1) return launch_resident1(h, 0, n_steps);
+hipError_t launch_resident(lc_handle* h, int n_steps, int period) {
+    if (h->L == 1) return launch_resident1(h, 0, n_steps, period);
     const ActSet& S = h->train;
     const bool bf16 = h->md.gemm == LC_GEMM_BF16;
     ResArgs a;
@@ -639,7 +790,12 @@ hipError_t launch_resident(lc_handle* h, int n_steps) {
     a.err = h->res_ctr + 64;
     a.spin_limit = h->res_spin_limit;
     a.loss = S.loss;
+    a.period = period;
+    a.avx = h->res_avx;
+    a.gctr = h->res_ctr + 65;
+    a.gctr_base = h->res_garrivals;
     if (n_steps < 1 || n_steps > S.slots) return hipErrorInvalidValue;
+    if (period < 0 || (period > 0 && (n_steps % period != 0 || !h->res_avx))) return hipErrorInvalidValue;
     const int64_t total = static_cast<int64_t>(a.G) * a.NB;
     if (total > 256 || a.G > 64 || !h->res_a1x) return hipErrorInvalidValue;
     const unsigned grid = static_cast<unsigned>((total + kXcds - 1) / kXcds * kXcds);
@@ -654,6 +810,7 @@ hipError_t launch_resident(lc_handle* h, int n_steps) {
     }
     h->loss_parts_train = 1;
     h->res_arrivals += static_cast<unsigned>(n_steps) * static_cast<unsigned>(a.NB);   // wraps like the counters do
+    if (period > 0) h->res_garrivals += static_cast<unsigned>(n_steps / period) * static_cast<unsigned>(total);
     timing_stop(h, kTimeBwd);
     return hipGetLastError();
 }

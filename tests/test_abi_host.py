@@ -66,6 +66,7 @@ def test_init_rejects_bad_arguments(pkg):
     assert L.lc_init(2, P, C.byref(good), 1, C.byref(h)) == 0 and h.value
     # not attached yet: every device entry point refuses
     assert L.lc_local_steps(h, 1) == -3
+    assert L.lc_local_periods(h, 1, 1) == -3 and L.lc_local_periods(None, 1, 1) == -1
     assert L.lc_average(h) == -3
     out = C.c_double()
     assert L.lc_loss(h, C.byref(out)) == -3

@@ -390,6 +390,88 @@ def test_resident_repeatable_and_barrier_timeout_reported(pkg, orc):
     run.close()
 
 
+PERIOD_CASES = [
+    # dims, m, B, tau, periods: one launch holds several periods (32 steps at most); 7 periods of 5
+    # need two launches; one period per launch at tau=20; tau=1 (an averaging step after every step);
+    # a shape outside the resident kernel's limits (call-by-call fallback)
+    ([70, 7], 5, 20, 4, 5),
+    ([67, 129, 10], 3, 33, 5, 7),
+    ([96, 64, 16], 5, 64, 1, 9),
+    ([784, 256, 10], 8, 64, 20, 2),
+    ([130, 70, 33, 7], 3, 16, 3, 2),
+]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("dims,m,B,tau,periods", PERIOD_CASES)
+def test_periods_in_one_launch(pkg, orc, dims, m, B, tau, periods, bf16):
+    """lc_local_periods(tau, n): whole communication periods inside one resident launch, the
+    averaging steps taken in the kernel.  Bit-identical to local_steps(tau) + average() call by
+    call (same kernels, same averaging arithmetic), and within tolerance of the oracle."""
+    _say(f"periods in one launch dims={dims} m={m} B={B} tau={tau} n={periods} bf16={bf16}")
+    tol = TOL16 if bf16 else TOL32
+    ref, run = _problem(pkg, orc, dims, m, B, wd=5e-4, bf16=bf16, lr=0.05)
+    _, sep = _problem(pkg, orc, dims, m, B, wd=5e-4, bf16=bf16, lr=0.05)
+    run.set_resident(2)   # in-kernel averaging also at the size where ending the launch is faster
+    for lazy in (False, True):   # the second batch starts from a deferred broadcast
+        run.set_lazy_broadcast(lazy)
+        sep.set_lazy_broadcast(lazy)
+        if lazy:
+            run.local_steps(2)
+            run.average()
+            sep.local_steps(2)
+            sep.average()
+            ref.local_steps(2)
+            ref.average()
+        run.local_periods(tau, periods)
+        for _ in range(periods):
+            sep.local_steps(tau)
+            sep.average()
+            ref.local_steps(tau)
+            ref.average()
+        X, V, k = run.get_state()
+        Xs, Vs, ks = sep.get_state()
+        assert k == ks == ref.k
+        assert np.array_equal(X.view(np.uint32), Xs.view(np.uint32))
+        assert np.array_equal(V.view(np.uint32), Vs.view(np.uint32))
+        for i in range(1, m):
+            assert np.array_equal(X[i].view(np.uint32), X[0].view(np.uint32))
+        assert np.array_equal(run.local_losses().view(np.uint32), sep.local_losses().view(np.uint32))
+        scale = 4 * max(1, (tau * periods) // 8)
+        _assert_close(X, ref.X, dims, tol * scale, "X against the oracle")
+        _assert_close(V, ref.V, dims, tol * 2 * scale, "V against the oracle")
+        assert abs(run.loss() - ref.loss()) < tol * scale * max(ref.loss(), 1e-3)
+    run.close()
+    sep.close()
+
+
+def test_periods_in_one_launch_timeout_reported(pkg, orc):
+    """The all-replica barrier of the in-kernel averaging step gives up like the per-step one."""
+    dims, m, B = [64, 10], 4, 32   # one workgroup per replica: only the averaging barrier waits
+    _say("periods in one launch, forced barrier time-out")
+    ref, run = _problem(pkg, orc, dims, m, B)
+    x1 = ref.X.copy()
+    run.set_barrier_polls(0)
+    run.local_periods(2, 3)
+    with pytest.raises(pkg.LcError) as ei:
+        run.get_state()
+    assert ei.value.status == -9
+    run.set_barrier_polls(400000)
+    run.set_state(x1, np.zeros_like(x1), 0)
+    for _ in range(3):
+        ref.local_steps(2)
+        ref.average()
+    run.local_periods(2, 3)
+    X, V, k = run.get_state()
+    assert k == 6
+    _assert_close(X, ref.X, dims, TOL32 * 4, "X after recovery")
+    with pytest.raises(pkg.LcError):
+        run.local_periods(0, 1)
+    with pytest.raises(pkg.LcError):
+        run.local_periods(1, 0)
+    run.close()
+
+
 # --------------------------------------------------------------- loss + driver
 
 @pytest.mark.parametrize("bf16", [False, True])
