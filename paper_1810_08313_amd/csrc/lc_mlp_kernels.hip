@@ -222,6 +222,7 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
     const float* W = a.X + g * a.x_stride + a.w_off;
     const OT* A = static_cast<const OT*>(a.a_in) + (static_cast<int64_t>(g) * a.Bp + row0) * a.dp_in;
     const bool vec = a.vec != 0;
+    const bool narrow = WM == kWGeneric && a.d_out <= 16;   // see load_w_step
 
     // everything the epilogue needs from memory is requested now, so that it does not add
     // dependent round trips after the reduction (these kernels are latency-bound when small)
@@ -247,13 +248,25 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
     const int n_steps = a.dp_in / 32;
     auto load_w_step = [&](int s, float4 (&w)[8]) {
         if constexpr (WM == kWGeneric) {
-            const int k0 = s * 32 + 8 * q;
+            // (steps past the end are never used: any valid step is read for them)
+            const int k0 = (s < n_steps ? s : n_steps - 1) * 32 + 8 * q;
+            if (narrow) {
+                // at most 16 columns (a classifier's last layer): lane column j stands for column
+                // j itself and only the first of the four tiles is used, so a step costs a lane
+                // 8 loads instead of 32 of which most lanes would sit out
+                float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                if (j < a.d_out) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int row = k0 + e;
-                w[e] = (s < n_steps && row < a.d_in)
-                           ? load_wm<WM>(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec)
-                           : make_float4(0.f, 0.f, 0.f, 0.f);
+                    for (int e = 0; e < 8; ++e) {
+                        const int rr = k0 + e < a.d_in ? k0 + e : a.d_in - 1;
+                        x[e] = W[static_cast<int64_t>(rr) * a.d_out + j];
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) w[e] = make_float4(k0 + e < a.d_in ? x[e] : 0.f, 0.f, 0.f, 0.f);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) w[e] = load_w4_rows(W, k0 + e, a.d_in, c0 + 4 * j, a.d_out, vec, false);
             }
         } else {
             // Rows past d_in meet activation columns that are zero, and steps past the end are
@@ -370,9 +383,14 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-            *reinterpret_cast<float4*>(&part[wave][16 * mt + 4 * q + r][4 * j]) =
-                make_float4(acc[mt][0][r], acc[mt][1][r], acc[mt][2][r], acc[mt][3][r]);
+        for (int r = 0; r < 4; ++r) {
+            if (narrow) {   // column j in place j; places 16.. of the tile are not used in this mode
+                part[wave][16 * mt + 4 * q + r][j] = acc[mt][0][r];
+            } else {
+                *reinterpret_cast<float4*>(&part[wave][16 * mt + 4 * q + r][4 * j]) =
+                    make_float4(acc[mt][0][r], acc[mt][1][r], acc[mt][2][r], acc[mt][3][r]);
+            }
+        }
     __syncthreads();
     for (int f = threadIdx.x; f < MT * 16 * (kColChunk / 4); f += NW * 64) {
         const int row = f / (kColChunk / 4), c4 = (f % (kColChunk / 4)) * 4;
@@ -651,12 +669,8 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         for (int r = 0; r < 4; ++r) {
             const int row = k0 + 4 * q + r;
             if constexpr (WM == kWGeneric) {
-                if (row < a.d_in) {
-                    ww[r] = load_wm<WM>(Wr + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec);
-                    vv[r] = load_wm<WM>(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec);
-                } else {
-                    ww[r] = vv[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-                }
+                ww[r] = load_w4_rows(Wr, row, a.d_in, c0 + 4 * j, a.d_out, vec, false);
+                vv[r] = load_w4_rows(Vw, row, a.d_in, c0 + 4 * j, a.d_out, vec, false);
             } else {
                 // rows past d_in read the last row instead (no branch between the loads); their
                 // weights are zeroed when used and they are never stored
@@ -863,9 +877,7 @@ __global__ __launch_bounds__(512) void head_kernel(HeadArgs a) {
             float4 w[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int row = k0 + e;
-                w[e] = row < a.d_in ? load_w4(Wr + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream)
-                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+                w[e] = load_w4_rows(Wr, k0 + e, a.d_in, 4 * j, a.d_out, vec, stream);
             }
             Frag<OT> af[NT];
 #pragma unroll
@@ -983,12 +995,8 @@ __global__ __launch_bounds__(512) void head_kernel(HeadArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int row = k0 + 4 * q + r;
-            if (row < a.d_in) {
-                w[r] = load_w4(Wr + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream);
-                v[r] = load_w4(Vw + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream);
-            } else {
-                w[r] = v[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-            }
+            w[r] = load_w4_rows(Wr, row, a.d_in, 4 * j, a.d_out, vec, stream);
+            v[r] = load_w4_rows(Vw, row, a.d_in, 4 * j, a.d_out, vec, stream);
         }
         f32x4 acc[4];
 #pragma unroll

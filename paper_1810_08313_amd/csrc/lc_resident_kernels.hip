@@ -85,12 +85,13 @@ __device__ __forceinline__ void arrive_and_wait(unsigned* ctr, unsigned target, 
     __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     int polls = 0;
     while (!gave_up) {
-        const unsigned seen = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (static_cast<int>(seen - target) >= 0) break;
-        if (++polls > spin_limit) {
+        if (polls++ >= spin_limit) {   // a limit of 0 gives up without looking: the host's way to force this path
             gave_up = true;
             atomicExch(err, 1u);
+            break;
         }
+        const unsigned seen = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (static_cast<int>(seen - target) >= 0) break;
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 }
