@@ -39,10 +39,21 @@ FLAT = {"cfg5a": (16, 25_600_000), "cfg5b": (8, 138_000_000)}
 # path it is the one kernel.  Summaries with the commands are in profiles/pmc_traffic_mfma_<workload>.txt.
 PMC = {
     "cfg2": {"traffic": (28.105e6 + 2.381e6) / 2, "mfma_busy_pct": (8.34 * 9.2 + 1.16 * 8.8) / 18.0},
-    "cfg3": {"traffic": (822.251e6 + 288.474e6 + 15.963e6) / 3,
-             "mfma_busy_pct": (3.21 * 150.0 + 4.38 * 71.6 + 1.13 * 10.3) / 231.9},
-    "cfg4": {"traffic": (6463.943e6 + 2 * 4335.461e6 + 46.455e6) / 4,
-             "mfma_busy_pct": (0.87 * 1190 + 1.63 * 1620 + 1.19 * 27) / 2837},
+    # layer 1: first_layer_kernel where the next step's input is at hand (17 of 20 steps at tau=20,
+    # 8 of 10 at tau=10; 8 steps are gathered per launch), backward_kernel otherwise
+    "cfg3": {"traffic": ((0.85 * 844.894e6 + 0.15 * 822.520e6) + 288.498e6 + 15.972e6) / 3,
+             "mfma_busy_pct": (0.85 * 7.60 * 202.0 + 0.15 * 3.27 * 162.0 + 4.36 * 70.2 + 1.13 * 10.8) /
+                              (0.85 * 202.0 + 0.15 * 162.0 + 70.2 + 10.8)},
+    "cfg4": {"traffic": ((0.8 * 6539.535e6 + 0.2 * 6465.981e6) + 2 * 4335.516e6 + 46.458e6) / 4,
+             "mfma_busy_pct": (0.8 * 2.44 * 1262 + 0.2 * 0.88 * 1184 + 1.61 * 1694 + 1.21 * 27) /
+                              (0.8 * 1262 + 0.2 * 1184 + 1694 + 27)},
+}
+# the same two workloads with --no-first-layer-fusion (backward_kernel for every layer)
+PMC_UNFUSED = {
+    "cfg3": {"traffic": (822.520e6 + 288.498e6 + 15.972e6) / 3,
+             "mfma_busy_pct": (3.27 * 162.0 + 4.36 * 70.2 + 1.13 * 10.8) / 243.0},
+    "cfg4": {"traffic": (6465.981e6 + 2 * 4335.516e6 + 46.458e6) / 4,
+             "mfma_busy_pct": (0.88 * 1184 + 1.61 * 1694 + 1.21 * 27) / 2905},
 }
 PMC_RESIDENT = {
     "cfg2": {"traffic": 56.525e6, "mfma_busy_pct": 13.55},   # per launch of 5 local steps
@@ -61,6 +72,8 @@ def parse():
     ap.add_argument("--eager", action="store_true", help="write the average to every row at once (no deferred broadcast)")
     ap.add_argument("--layer-kernels", action="store_true",
                     help="launch-per-layer kernels also where the resident step kernel applies")
+    ap.add_argument("--no-first-layer-fusion", action="store_true",
+                    help="separate first-layer forward launch in every step (see lc_set_first_layer_fusion)")
     return ap.parse_args()
 
 
@@ -81,6 +94,7 @@ def bench_mlp(args, pkg, synth):
     run = pkg.LocalSGD(w.m, md, w.seed, w.x1, w.data, w.labels)
     run.set_lazy_broadcast(not args.eager)   # bit-identical results; see lc_set_lazy_broadcast
     run.set_resident(not args.layer_kernels)
+    run.set_first_layer_fusion(not args.no_first_layer_fusion)
     resident = run.resident_active()
     interval = w.interval if adaptive else 0
 
@@ -128,8 +142,11 @@ def bench_mlp(args, pkg, synth):
         bytes_per_iter = 16.0 * w.m * w.P                    # read W,V + write W,V of every replica, fp32
         per_launch_bytes = bytes_per_iter * K2 / launches
         achieved = per_launch_bytes / (avg_launch_ms * 1e-3) / 1e9
-        pmc = PMC.get(name) if args.tau is None else None
-        roof = {"bound": "hbm", "kernel": "backward_kernel (dA + dW + momentum update, all layers)",
+        pmc = (PMC_UNFUSED if args.no_first_layer_fusion and name in PMC_UNFUSED else PMC).get(name) \
+            if args.tau is None else None
+        roof = {"bound": "hbm", "kernel": "backward_kernel (dA + dW + momentum update, all layers; where "
+                                          "first_layer_kernel serves layer 1 its launch also holds the next "
+                                          "step's first-layer forward)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": pmc["traffic"] if pmc else None,
@@ -143,7 +160,8 @@ def bench_mlp(args, pkg, synth):
                        f"{', interval=%d' % interval if adaptive else ''}, lr={w.lr}, momentum={w.beta}",
            "m": w.m, "P": w.P, "batch_per_replica": w.B, "tau0": tau0, "adaptive": adaptive,
            "averaging_rounds": rounds, "tau_schedule": sched[:16], "final_loss": round(final_loss, 6),
-           "deferred_broadcast": not args.eager, "resident_step_kernel": resident}
+           "deferred_broadcast": not args.eager, "resident_step_kernel": resident,
+           "first_layer_fusion": not args.no_first_layer_fusion}
     return dict(value=w.m * K / sec, sec=sec, K=K, W=W, roofline=roof, config=cfg,
                 dtype="bf16" if w.bf16 else "f32", workload=w, tau0=tau0)
 

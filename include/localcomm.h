@@ -189,6 +189,18 @@ int lc_materialize(lc_handle* h);
  * has the GPU to itself (at most 256 workgroups, one per compute unit), not necessarily when
  * other streams keep compute units busy at the same time -- turn the mode off for such use. */
 int lc_set_resident(lc_handle* h, int on);
+/* First-layer fusion across steps (Sec. 2: between two averaging steps a worker's updates touch
+ * only its own model, so the first layer's weights after step k are what step k+1 multiplies its
+ * mini-batch with).  Inside one lc_local_steps() call, for LC_KIND_MLP models with at least two
+ * layers, first-layer rows that are a multiple of 64 columns long and m * d1 / 64 >= 192, the
+ * first layer's backward kernel of a step also computes the first hidden activations of the
+ * next step from the weight tile it has just updated, and that step's first-layer forward launch
+ * is dropped: W_1 then moves 16 instead of 20 bytes per parameter and step.  The first step of a
+ * call and steps whose inputs are gathered by a later launch run the forward pass on its own.
+ * Same arithmetic up to the summation order of the first-layer products.  Default on;
+ * on = 0 keeps the separate forward launch and the row-owner backward kernel everywhere. */
+int lc_set_first_layer_fusion(lc_handle* h, int on);
+
 /* 1 if lc_local_steps() of this (attached) handle takes the resident step kernel, else 0. */
 int lc_resident_active(const lc_handle* h);
 

@@ -271,6 +271,9 @@ class LocalSGD:
     def set_lazy_broadcast(self, on: bool) -> None:
         self._check(self._L.lc_set_lazy_broadcast(self._h, int(bool(on))), "lc_set_lazy_broadcast")
 
+    def set_first_layer_fusion(self, on: bool) -> None:
+        self._check(self._L.lc_set_first_layer_fusion(self._h, int(bool(on))), "lc_set_first_layer_fusion")
+
     def set_resident(self, on) -> None:
         """False/0: launch-per-layer kernels; True/1: resident step kernel where it applies; 2: and
         in-kernel averaging steps at every shape it handles (see lc_local_periods)."""

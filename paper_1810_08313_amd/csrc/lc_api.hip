@@ -163,7 +163,10 @@ int materialise(lc_handle* h) {
     return LC_OK;
 }
 
-int one_local_step(lc_handle* h) {
+// next_gathered: the step after this one belongs to the same call and its mini-batch is already
+// in the next input slot, so the first layer's backward kernel may run that step's first-layer
+// forward pass on the weights it has just updated.
+int one_local_step(lc_handle* h, bool next_gathered) {
     if (h->md.kind == LC_KIND_QUAD) {
         const int rc = materialise(h);
         if (rc != LC_OK) return rc;
@@ -172,15 +175,22 @@ int one_local_step(lc_handle* h) {
         // (the mini-batch of this step was gathered into slot train.cur_slot by lc_local_steps)
         // layer L first in the backward sweep: dZ_{l-1} is produced from W_l before W_l
         // is overwritten inside the same kernel, and kernels run in stream order
+        // (as a plain backward pass the column-owner kernel is a few per cent slower than the
+        // row-owner one: it is taken only when it also saves the next forward launch)
+        const bool first_fused = h->fl_on && next_gathered && first_layer_kernel_ok(h);
+        const int l_lo = h->a1_ready ? 2 : 1;   // A_1 of this step came out of the previous step's backward pass
         if (head_is_fused(h)) {
-            for (int l = 1; l < h->L; ++l) LC_HIP(h, launch_forward(h, false, l, 0));
+            for (int l = l_lo; l < h->L; ++l) LC_HIP(h, launch_forward(h, false, l, 0));
             LC_HIP(h, launch_head(h));
-            for (int l = h->L - 1; l >= 1; --l) LC_HIP(h, launch_backward(h, l));
         } else {
-            for (int l = 1; l <= h->L; ++l) LC_HIP(h, launch_forward(h, false, l, 0));
+            for (int l = l_lo; l <= h->L; ++l) LC_HIP(h, launch_forward(h, false, l, 0));
             if (!forward_fuses_softmax(h)) LC_HIP(h, launch_softmax(h, false, 0));
-            for (int l = h->L; l >= 1; --l) LC_HIP(h, launch_backward(h, l));
         }
+        for (int l = head_is_fused(h) ? h->L - 1 : h->L; l >= 1; --l) {
+            if (l == 1 && first_fused) LC_HIP(h, launch_first_layer(h));
+            else LC_HIP(h, launch_backward(h, l));
+        }
+        h->a1_ready = first_fused;
     }
     h->k += 1;
     h->v_cleared = false;   // the step just queued wrote V = g
@@ -298,6 +308,8 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     h->res_ctr = nullptr;
     h->res_on = true;
     h->res_fuse_always = false;
+    h->fl_on = true;
+    h->a1_ready = false;
     h->res_used = false;
     h->res_arrivals = 0;
     h->res_garrivals = 0;
@@ -379,9 +391,10 @@ int lc_local_steps(lc_handle* h, int tau) {
             h->res_used = true;
             continue;
         }
+        h->a1_ready = false;
         for (int t = 0; t < n; ++t) {
             h->train.cur_slot = t;
-            const int r = one_local_step(h);
+            const int r = one_local_step(h, t + 1 < n);
             if (r != LC_OK) return r;
         }
     }
@@ -458,6 +471,12 @@ int lc_set_resident(lc_handle* h, int on) {
     if (!h) return LC_ERR_ARG;
     h->res_on = on != 0;
     h->res_fuse_always = on == 2;
+    return LC_OK;
+}
+
+int lc_set_first_layer_fusion(lc_handle* h, int on) {
+    if (!h) return LC_ERR_ARG;
+    h->fl_on = on != 0;
     return LC_OK;
 }
 

@@ -92,6 +92,8 @@ struct lc_handle {
     float* res_avx;         // [2 parities][m][Ps] models handed over at averaging steps inside a launch
     unsigned res_garrivals; // the same for the all-replica counter of those averaging steps (res_ctr[65])
     bool res_on;            // lc_set_resident
+    bool fl_on;             // lc_set_first_layer_fusion
+    bool a1_ready;          // A_1 of the step about to run was produced by the previous step's backward pass
     bool res_fuse_always;   // lc_set_resident(2): averaging steps inside the launch at every eligible shape
     bool res_used;          // a resident launch has run since the error flag was last read
     int res_spin_limit;     // polls a barrier wait may take
@@ -120,6 +122,8 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset);
 bool forward_fuses_softmax(const lc_handle* h);  // last layer's kernel also does a3
 hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset);
 hipError_t launch_backward(lc_handle* h, int l);
+bool first_layer_kernel_ok(const lc_handle* h);   // layer 1: backward kernel that also runs the next step's forward
+hipError_t launch_first_layer(lc_handle* h);
 bool head_is_fused(const lc_handle* h);   // last layer: forward + softmax + backward in one kernel
 hipError_t launch_head(lc_handle* h);
 

@@ -390,6 +390,52 @@ def test_resident_repeatable_and_barrier_timeout_reported(pkg, orc):
     run.close()
 
 
+FIRST_LAYER_CASES = [
+    # dims, m, B: shapes the column-owner first-layer kernel takes (m * d1 / 64 >= 192, d0 a
+    # multiple of 16): 2, 4 and 8 batch tiles; 6, 5 and 7 sixteen-row steps over 4 wavefronts
+    ([96, 256, 24, 10], 48, 30),
+    ([80, 192, 10], 64, 64),
+    ([112, 512, 24, 10], 32, 120),
+]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("dims,m,B", FIRST_LAYER_CASES)
+def test_first_layer_fusion_across_steps(pkg, orc, dims, m, B, bf16):
+    """Runs of local steps in which the first layer's backward kernel also produces the next
+    step's first hidden activations: against the oracle, and against the same steps with the
+    separate forward launch (same arithmetic, other summation order); a second call and an
+    averaging step with deferred broadcast in between."""
+    assert not _resident_shape(dims, m, B)
+    _say(f"first-layer fusion dims={dims} m={m} B={B} bf16={bf16}")
+    tol = TOL16 if bf16 else TOL32
+    ref, run = _problem(pkg, orc, dims, m, B, wd=5e-4, bf16=bf16, lr=0.05)
+    _, sep = _problem(pkg, orc, dims, m, B, wd=5e-4, bf16=bf16, lr=0.05)
+    sep.set_first_layer_fusion(False)
+    run.set_lazy_broadcast(True)
+    sep.set_lazy_broadcast(True)
+    done = 0
+    for tau in (3, 1, 4):
+        ref.local_steps(tau)
+        run.local_steps(tau)
+        sep.local_steps(tau)
+        done += tau
+        X, V, k = run.get_state()
+        Xs, Vs, _ = sep.get_state()
+        assert k == ref.k == done
+        _assert_close(X, ref.X, dims, tol * 4, f"X after {done}")
+        _assert_close(V, ref.V, dims, tol * 8, f"V after {done}")
+        _assert_close(X, Xs, dims, tol * 4, f"X vs separate forward after {done}")
+        ll = run.local_losses()
+        assert np.abs(ll - ref.last_losses).max() < 4 * tol * max(np.abs(ref.last_losses).max(), 1e-3)
+        ref.average()
+        run.average()
+        sep.average()
+        assert abs(run.loss() - ref.loss()) < 4 * tol * max(ref.loss(), 1e-3)
+    run.close()
+    sep.close()
+
+
 PERIOD_CASES = [
     # dims, m, B, tau, periods: one launch holds several periods (32 steps at most); 7 periods of 5
     # need two launches; one period per launch at tau=20; tau=1 (an averaging step after every step);
