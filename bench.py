@@ -39,14 +39,14 @@ FLAT = {"cfg5a": (16, 25_600_000), "cfg5b": (8, 138_000_000)}
 # path it is the one kernel.  Summaries with the commands are in profiles/pmc_traffic_mfma_<workload>.txt.
 PMC = {
     "cfg2": {"traffic": (28.105e6 + 2.381e6) / 2, "mfma_busy_pct": (8.34 * 9.2 + 1.16 * 8.8) / 18.0},
-    # layer 1: first_layer_kernel where the next step's input is at hand (17 of 20 steps at tau=20,
-    # 8 of 10 at tau=10; 8 steps are gathered per launch), backward_kernel otherwise
-    "cfg3": {"traffic": ((0.85 * 844.894e6 + 0.15 * 822.520e6) + 288.498e6 + 15.972e6) / 3,
-             "mfma_busy_pct": (0.85 * 7.60 * 202.0 + 0.15 * 3.27 * 162.0 + 4.36 * 70.2 + 1.13 * 10.8) /
-                              (0.85 * 202.0 + 0.15 * 162.0 + 70.2 + 10.8)},
-    "cfg4": {"traffic": ((0.8 * 6539.535e6 + 0.2 * 6465.981e6) + 2 * 4335.516e6 + 46.458e6) / 4,
-             "mfma_busy_pct": (0.8 * 2.44 * 1262 + 0.2 * 0.88 * 1184 + 1.61 * 1694 + 1.21 * 27) /
-                              (0.8 * 1262 + 0.2 * 1184 + 1694 + 27)},
+    # layer 1: first_layer_kernel where the next step's input is at hand (18 of 20 steps at tau=20,
+    # 9 of 10 at tau=10; 16 steps are gathered per launch), backward_kernel otherwise
+    "cfg3": {"traffic": ((0.9 * 844.894e6 + 0.1 * 822.520e6) + 288.498e6 + 15.972e6) / 3,
+             "mfma_busy_pct": (0.9 * 7.60 * 202.0 + 0.1 * 3.27 * 162.0 + 4.36 * 70.2 + 1.13 * 10.8) /
+                              (0.9 * 202.0 + 0.1 * 162.0 + 70.2 + 10.8)},
+    "cfg4": {"traffic": ((0.9 * 6539.535e6 + 0.1 * 6465.981e6) + 2 * 4335.516e6 + 46.458e6) / 4,
+             "mfma_busy_pct": (0.9 * 2.44 * 1262 + 0.1 * 0.88 * 1184 + 1.61 * 1694 + 1.21 * 27) /
+                              (0.9 * 1262 + 0.1 * 1184 + 1694 + 27)},
 }
 # the same two workloads with --no-first-layer-fusion (backward_kernel for every layer)
 PMC_UNFUSED = {

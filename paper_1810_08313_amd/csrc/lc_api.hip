@@ -110,6 +110,10 @@ size_t carve(lc_handle* h, char* base) {
             const size_t slot_bytes = 2 * static_cast<size_t>(S.G) * S.Bp * h->layer[1].dp_in * ot;
             size_t n = (static_cast<size_t>(128) << 20) / slot_bytes;
             S.slots = n < kGatherSlots ? kGatherSlots : (n > 4 * kGatherSlots ? 4 * kGatherSlots : static_cast<int>(n));
+            // the first-layer kernel folds a step's first forward pass into the step before it, which
+            // needs that step's inputs gathered by the same launch: fewer, longer runs (400 MB at the
+            // two large configurations)
+            if (first_layer_kernel_ok(h) && S.slots < 2 * kGatherSlots) S.slots = 2 * kGatherSlots;
         }
         S.cur_slot = 0;
         for (int l = 0; l <= L; ++l) {

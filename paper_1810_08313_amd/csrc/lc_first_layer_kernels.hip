@@ -268,15 +268,22 @@ __global__ __launch_bounds__(256) void first_layer_kernel(FirstArgs a) {
             *reinterpret_cast<float4*>(&part[wave][16 * mt + 4 * q + r][4 * j]) =
                 make_float4(facc[mt][0][r], facc[mt][1][r], facc[mt][2][r], facc[mt][3][r]);
     __syncthreads();
+    for (int f = tid; f < Bp * (kColChunk / 4); f += 256) {
+        const int b = f / (kColChunk / 4), c4 = (f % (kColChunk / 4)) * 4;
+        float4 z = *reinterpret_cast<const float4*>(&part[0][b][c4]);
+#pragma unroll
+        for (int wv = 1; wv < kFlWaves; ++wv) {
+            const float4 o = *reinterpret_cast<const float4*>(&part[wv][b][c4]);
+            z.x += o.x; z.y += o.y; z.z += o.z; z.w += o.w;
+        }
+        z.x += bias_s[c4]; z.y += bias_s[c4 + 1]; z.z += bias_s[c4 + 2]; z.w += bias_s[c4 + 3];
+        *reinterpret_cast<float4*>(&part[0][b][c4]) =
+            make_float4(z.x > 0.f ? z.x : 0.f, z.y > 0.f ? z.y : 0.f, z.z > 0.f ? z.z : 0.f, z.w > 0.f ? z.w : 0.f);
+    }
+    __syncthreads();
     OT* obm = static_cast<OT*>(a.out_bm) + static_cast<int64_t>(g) * Bp * a.dp_out;
     OT* ofm = static_cast<OT*>(a.out_fm) + static_cast<int64_t>(g) * a.dp_out * Bp;
-    auto value = [&](int b, int c) {
-        float z = part[0][b][c];
-#pragma unroll
-        for (int wv = 1; wv < kFlWaves; ++wv) z += part[wv][b][c];
-        z += bias_s[c];
-        return z > 0.f ? z : 0.f;
-    };
+    auto value = [&](int b, int c) { return part[0][b][c]; };
     // 8 outputs per thread and pass, one vector store each: along the columns for the
     // batch-major copy, along the batch for the feature-major one; only batch rows below B
     // are written, so the zero padding of the buffers is preserved
