@@ -102,19 +102,10 @@ __device__ __forceinline__ void store8(bf16_t* p, const float (&y)[8]) {
 // once per kernel and the loads and stores carry the non-temporal hint; small
 // models, whose weights stay cache-resident between kernels, use plain accesses.
 __device__ __forceinline__ float4 load_w4(const float* row, int c, int d_out, bool vec, bool stream) {
-    if (vec) {
-        // rows are 16-byte aligned and a multiple of 4 long, c is a multiple of 4: the four
-        // columns are inside the row together or not at all.  Lanes past the end read the row's
-        // last vector and drop it (no branch around the load).
-        const int cc = c < d_out ? c : d_out - 4;
-        float4 x;
-        if (!stream) {
-            x = *reinterpret_cast<const float4*>(row + cc);
-        } else {
-            const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(row + cc));
-            x = make_float4(t[0], t[1], t[2], t[3]);
-        }
-        return c < d_out ? x : make_float4(0.f, 0.f, 0.f, 0.f);
+    if (vec && c + 3 < d_out) {
+        if (!stream) return *reinterpret_cast<const float4*>(row + c);
+        const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(row + c));
+        return make_float4(t[0], t[1], t[2], t[3]);
     }
     // unaligned or ragged rows, element by element.  (Loading unconditionally from clamped
     // positions instead was measured and is slower: the cost of these loads grows with the

@@ -100,13 +100,13 @@ __device__ __forceinline__ void arrive_and_wait(unsigned* ctr, unsigned target, 
 // replica order and rounded once: the same arithmetic, bit for bit, as the averaging kernels.
 __device__ __forceinline__ float mean_of_replicas(const float* p, int64_t stride, int G) {
     double s = 0.0;
-    for (int i0 = 0; i0 < G; i0 += 8) {   // eight loads in flight, added in replica order
-        float r[8];
+    for (int i0 = 0; i0 < G; i0 += 4) {   // four loads in flight, added in replica order
+        float r[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < 4; ++u)
             if (i0 + u < G) r[u] = p[(i0 + u) * stride];
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < 4; ++u)
             if (i0 + u < G) s += static_cast<double>(r[u]);
     }
     return static_cast<float>(s / static_cast<double>(G));
@@ -173,25 +173,13 @@ __device__ __forceinline__ void average_resident(const ResArgs& a, int tid, int 
             w1s[4 * q + 3][k] = static_cast<float>(s3 / dm);
         }
     }
-    // the second layer and the biases: every thread's loads first, then its stores
-    constexpr int kPer = kResMaxD1 * 16 / kResThreads;
-    float mw2[kPer];
-#pragma unroll
-    for (int u = 0; u < kPer; ++u) {
-        const int e = tid + u * kResThreads;
-        mw2[u] = e < a.d1 * a.d2 ? mean_of_replicas(all + a.w2_off + e, a.x_stride, a.G) : 0.f;
-    }
-    float mb = 0.f;
-    const bool has_b1 = tid < 16 && c_base + tid < a.d1, has_b2 = tid >= 64 && tid < 64 + a.d2;
-    if (has_b1) mb = mean_of_replicas(all + a.b1_off + c_base + tid, a.x_stride, a.G);
-    if (has_b2) mb = mean_of_replicas(all + a.b2_off + tid - 64, a.x_stride, a.G);
-#pragma unroll
-    for (int u = 0; u < kPer; ++u) {
-        const int e = tid + u * kResThreads;
-        if (e < a.d1 * a.d2) w2s[e % a.d2][e / a.d2] = mw2[u];
-    }
-    if (has_b1) b1s[tid] = mb;
-    if (has_b2) b2s[tid - 64] = mb;
+    // the second layer and the biases, an entry at a time (its m loads together): this phase must
+    // stay light in registers, the step loop around it has none to spare
+#pragma unroll 1
+    for (int e = tid; e < a.d1 * a.d2; e += kResThreads)
+        w2s[e % a.d2][e / a.d2] = mean_of_replicas(all + a.w2_off + e, a.x_stride, a.G);
+    if (tid < 16 && c_base + tid < a.d1) b1s[tid] = mean_of_replicas(all + a.b1_off + c_base + tid, a.x_stride, a.G);
+    if (tid >= 64 && tid < 64 + a.d2) b2s[tid - 64] = mean_of_replicas(all + a.b2_off + tid - 64, a.x_stride, a.G);
     __syncthreads();
 }
 
