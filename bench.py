@@ -56,7 +56,8 @@ PMC_UNFUSED = {
              "mfma_busy_pct": (0.88 * 1184 + 1.61 * 1694 + 1.21 * 27) / 2905},
 }
 PMC_RESIDENT = {
-    "cfg2": {"traffic": 56.525e6, "mfma_busy_pct": 13.55},   # per launch of 5 local steps
+    "cfg1": {"traffic": 0.982e6, "mfma_busy_pct": 0.08},     # per launch of 32 local steps and 8 averaging steps
+    "cfg2": {"traffic": 56.548e6, "mfma_busy_pct": 13.36},   # per launch of 5 local steps
 }
 
 
@@ -130,8 +131,9 @@ def bench_mlp(args, pkg, synth):
         per_launch_flops = flops_step * w.m * K2 / launches
         achieved = per_launch_flops / (avg_launch_ms * 1e-3) / 1e12
         peak = MFMA_BF16_PEAK_TFLOPS if w.bf16 else MFMA_FP32_PEAK_TFLOPS
-        roof = {"bound": "mfma", "kernel": "resident_kernel (all layers of %d local steps per launch, weights in LDS)"
-                % round(K2 / launches),
+        roof = {"bound": "mfma", "kernel": "%s (all layers of %d local steps per launch, weights in LDS%s)"
+                % ("resident_kernel" if len(w.dims) == 3 else "resident1_kernel", round(K2 / launches),
+                   ", averaging steps inside" if K2 / launches > tau0 else ""),
                 "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "traffic": PMC_RESIDENT[name]["traffic"] if name in PMC_RESIDENT and args.tau is None else None,
                 "launches": launches, "avg_launch_us": round(avg_launch_ms * 1e3, 2),
