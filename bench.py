@@ -73,6 +73,8 @@ def parse():
     ap.add_argument("--eager", action="store_true", help="write the average to every row at once (no deferred broadcast)")
     ap.add_argument("--layer-kernels", action="store_true",
                     help="launch-per-layer kernels also where the resident step kernel applies")
+    ap.add_argument("--agent-scope-exchange", action="store_true",
+                    help="resident kernel: exchange through device scope (see lc_set_xcd_local_exchange)")
     ap.add_argument("--no-first-layer-fusion", action="store_true",
                     help="separate first-layer forward launch in every step (see lc_set_first_layer_fusion)")
     return ap.parse_args()
@@ -96,6 +98,7 @@ def bench_mlp(args, pkg, synth):
     run.set_lazy_broadcast(not args.eager)   # bit-identical results; see lc_set_lazy_broadcast
     run.set_resident(not args.layer_kernels)
     run.set_first_layer_fusion(not args.no_first_layer_fusion)
+    run.set_xcd_local_exchange(not args.agent_scope_exchange)
     resident = run.resident_active()
     interval = w.interval if adaptive else 0
 

@@ -45,7 +45,8 @@ typedef enum {
     LC_ERR_HIP = -6,        /* a HIP call failed; lc_last_hip_error() has the code */
     LC_ERR_NONFINITE = -7,  /* the evaluated loss is not finite */
     LC_ERR_UNSUPPORTED = -8, /* shape outside what the kernels handle */
-    LC_ERR_SYNC = -9         /* a replica-wide barrier of the resident step kernel timed out */
+    LC_ERR_SYNC = -9,        /* a replica-wide barrier of the resident step kernel timed out */
+    LC_ERR_PLACEMENT = -10   /* a workgroup of the resident step kernel ran on another XCD than the probe predicted */
 } lc_status;
 
 typedef enum { LC_KIND_QUAD = 0, LC_KIND_MLP = 1 } lc_kind;
@@ -189,6 +190,18 @@ int lc_materialize(lc_handle* h);
  * has the GPU to itself (at most 256 workgroups, one per compute unit), not necessarily when
  * other streams keep compute units busy at the same time -- turn the mode off for such use. */
 int lc_set_resident(lc_handle* h, int on);
+/* Exchange inside one XCD.  The resident step kernel's workgroups of one replica exchange their
+ * activations once per step.  Blocks are numbered so that a replica's workgroups run on one XCD
+ * (one L2 cache) whenever m * ceil64(d1) / 16 / 8 is a multiple of ceil64(d1) / 16; counter and
+ * activations then stay in that L2 (workgroup-scope atomics, which the hardware performs in the
+ * L2, and an invalidate of the compute unit's L1 only) instead of travelling to the memory side
+ * and back.  The placement rule (hardware block id mod 8 selects the XCD) is observed by a probe
+ * kernel at lc_attach(), and every workgroup compares its own XCD id with it when it starts: a
+ * mismatch is reported as LC_ERR_PLACEMENT by the next synchronising call (the state is then
+ * undefined).  Where the rule does not hold, or with on = 0, the agent-scope exchange is used.
+ * Identical results either way.  Default on. */
+int lc_set_xcd_local_exchange(lc_handle* h, int on);
+
 /* First-layer fusion across steps (Sec. 2: between two averaging steps a worker's updates touch
  * only its own model, so the first layer's weights after step k are what step k+1 multiplies its
  * mini-batch with).  Inside one lc_local_steps() call, for LC_KIND_MLP models with at least two

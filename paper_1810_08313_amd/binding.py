@@ -271,6 +271,9 @@ class LocalSGD:
     def set_lazy_broadcast(self, on: bool) -> None:
         self._check(self._L.lc_set_lazy_broadcast(self._h, int(bool(on))), "lc_set_lazy_broadcast")
 
+    def set_xcd_local_exchange(self, on: bool) -> None:
+        self._check(self._L.lc_set_xcd_local_exchange(self._h, int(bool(on))), "lc_set_xcd_local_exchange")
+
     def set_first_layer_fusion(self, on: bool) -> None:
         self._check(self._L.lc_set_first_layer_fusion(self._h, int(bool(on))), "lc_set_first_layer_fusion")
 

@@ -133,7 +133,7 @@ size_t carve(lc_handle* h, char* base) {
     }
     if (resident_shape_ok(h)) {
         h->res_a1x = static_cast<float*>(c.take(sizeof(float) * 2 * resident_exchange_floats(h)));
-        h->res_ctr = static_cast<unsigned*>(c.take(sizeof(unsigned) * 128));
+        h->res_ctr = static_cast<unsigned*>(c.take(sizeof(unsigned) * 384));
         h->res_avx = static_cast<float*>(c.take(sizeof(float) * 2 * static_cast<size_t>(h->m) * h->Ps));
     } else {
         h->res_a1x = nullptr;
@@ -211,7 +211,7 @@ int check_resident(lc_handle* h) {
     h->res_used = false;
     if (flag == 0) return LC_OK;
     LC_HIP(h, hipMemsetAsync(h->res_ctr + 64, 0, sizeof(unsigned), h->stream));
-    return LC_ERR_SYNC;
+    return (flag & 2u) ? LC_ERR_PLACEMENT : LC_ERR_SYNC;
 }
 
 // Whole periods of tau iterations that can be taken from iteration k on without looking at the
@@ -242,6 +242,7 @@ const char* lc_strerror(int status) {
         case LC_ERR_NONFINITE: return "loss is not finite";
         case LC_ERR_UNSUPPORTED: return "shape not supported";
         case LC_ERR_SYNC: return "replica barrier timed out in the resident step kernel";
+        case LC_ERR_PLACEMENT: return "resident step kernel: a workgroup ran on another XCD than the placement probe predicted";
         default: return "unknown status";
     }
 }
@@ -314,6 +315,9 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     h->res_fuse_always = false;
     h->fl_on = true;
     h->a1_ready = false;
+    h->res_local_on = true;
+    h->res_xcc_known = false;
+    h->res_xcc_of = 0;
     h->res_used = false;
     h->res_arrivals = 0;
     h->res_garrivals = 0;
@@ -362,6 +366,7 @@ int lc_attach(lc_handle* h, void* X, void* V, void* scratch, size_t scratch_byte
     h->res_arrivals = 0;
     h->res_garrivals = 0;
     LC_HIP(h, hipStreamSynchronize(h->stream));
+    LC_HIP(h, probe_block_placement(h));   // (only where the resident kernel applies)
     h->attached = true;
     return LC_OK;
 }
@@ -475,6 +480,12 @@ int lc_set_resident(lc_handle* h, int on) {
     if (!h) return LC_ERR_ARG;
     h->res_on = on != 0;
     h->res_fuse_always = on == 2;
+    return LC_OK;
+}
+
+int lc_set_xcd_local_exchange(lc_handle* h, int on) {
+    if (!h) return LC_ERR_ARG;
+    h->res_local_on = on != 0;
     return LC_OK;
 }
 

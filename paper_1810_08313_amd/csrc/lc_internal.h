@@ -87,11 +87,14 @@ struct lc_handle {
     bool lazy_enabled_step;   // set only while lc_average runs its reduce-only form
     // resident local steps (small two-layer models): exchange buffer, barrier counters, switches
     float* res_a1x;         // [2 layouts][2 parities][m][Bp][dp1], null when the shape does not qualify
-    unsigned* res_ctr;      // [0..63] arrival counters per replica, [64] error flag, [65] all-replica counter
+    unsigned* res_ctr;      // [0..63] arrival counters per replica, [64] error flag, [65] all-replica counter, [128..383] placement probe
     unsigned res_arrivals;  // value of every counter once the queued launches have run (zeroed with the scratch at attach)
     float* res_avx;         // [2 parities][m][Ps] models handed over at averaging steps inside a launch
     unsigned res_garrivals; // the same for the all-replica counter of those averaging steps (res_ctr[65])
     bool res_on;            // lc_set_resident
+    bool res_local_on;      // lc_set_xcd_local_exchange
+    bool res_xcc_known;     // the probe found blocks dealt to the XCDs by id mod 8
+    unsigned res_xcc_of;    // 4 bits per residue: the XCD it runs on
     bool fl_on;             // lc_set_first_layer_fusion
     bool a1_ready;          // A_1 of the step about to run was produced by the previous step's backward pass
     bool res_fuse_always;   // lc_set_resident(2): averaging steps inside the launch at every eligible shape
@@ -130,6 +133,7 @@ hipError_t launch_head(lc_handle* h);
 // resident path (weights stay in LDS over a run of local steps)
 bool resident_shape_ok(const lc_handle* h);
 size_t resident_exchange_floats(const lc_handle* h);   // per layout
+hipError_t probe_block_placement(lc_handle* h);   // synchronises the stream once
 hipError_t launch_resident(lc_handle* h, int n_steps, int period);  // the steps gathered into slots 0 .. n_steps-1
 
 // timing helpers used by the launchers

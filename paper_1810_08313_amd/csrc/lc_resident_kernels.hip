@@ -69,6 +69,8 @@ struct ResArgs {
     unsigned* err;        // set to 1 when a barrier wait ran out of polls
     int spin_limit;       // polls one barrier wait may take
     float* loss;          // [G][kLossParts], slot 0 written
+    int local_xcd;        // every replica's workgroups share one XCD (one L2): exchange through that L2
+    unsigned xcc_of;      // 4 bits per residue of the hardware block id mod 8: the XCD such blocks run on
     int period;           // averaging step after every `period` steps inside the launch; 0: none
     float* avx;           // [2][G][x_stride] models handed over at an averaging step, by parity of the period
     unsigned* gctr;       // arrivals of all workgroups at averaging steps since attach
@@ -87,13 +89,49 @@ __device__ __forceinline__ void arrive_and_wait(unsigned* ctr, unsigned target, 
     while (!gave_up) {
         if (polls++ >= spin_limit) {   // a limit of 0 gives up without looking: the host's way to force this path
             gave_up = true;
-            atomicExch(err, 1u);
+            atomicOr(err, 1u);
             break;
         }
         const unsigned seen = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (static_cast<int>(seen - target) >= 0) break;
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+}
+
+// The same barrier for workgroups that all run on one XCD, i.e. behind one L2: counter and data
+// need not leave that L2.  Read-modify-write atomics without the device-scope bit are performed
+// in the L2, so the counter is added to and polled there (the poll is a compare-and-swap that
+// never matches: a workgroup-scope LOAD may be served by the compute unit's L1 and then never sees
+// the count move -- measured).  The slices were written through to the L2 and stay there as
+// dirty lines; after the L1 has been invalidated (the agent-scope acquire does that) loads find
+// them in the L2, where the agent-scope form sends data and counter to the memory side and
+// back.  Valid only while the participants really share an L2: the launcher checks the placement
+// rule once with a probe kernel, and every workgroup checks its own XCD id against it.
+__device__ __forceinline__ void arrive_and_wait_same_xcd(unsigned* ctr, unsigned target, int spin_limit, unsigned* err,
+                                                         bool& gave_up) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    int polls = 0;
+    while (!gave_up) {
+        if (polls++ >= spin_limit) {
+            gave_up = true;
+            atomicOr(err, 1u);
+            break;
+        }
+        unsigned seen = 0xFFFFFFFFu;   // (were the count ever this, the swap would write the same value back)
+        __hip_atomic_compare_exchange_strong(ctr, &seen, 0xFFFFFFFFu, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (static_cast<int>(seen - target) >= 0) break;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+}
+
+// The XCD this wavefront runs on: hardware register XCC_ID (number 20), bits 3:0.  The operand
+// of s_getreg is (size - 1) << 11 | offset << 6 | register.
+__device__ __forceinline__ unsigned this_xcd() { return __builtin_amdgcn_s_getreg(((4 - 1) << 11) | (0 << 6) | 20); }
+
+__global__ void xcd_probe_kernel(unsigned* out) {
+    if (threadIdx.x == 0) out[blockIdx.x] = this_xcd();
 }
 
 // x_bar = (1/m) sum_i x^(i) of one entry (Sec. 2, the averaging step), summed in double in
@@ -244,6 +282,8 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
     }
     __syncthreads();
     bool gave_up = false;   // thread 0: a barrier wait ran out of polls
+    if (a.local_xcd && threadIdx.x == 0 && this_xcd() != ((a.xcc_of >> (4 * (blockIdx.x % kXcds))) & 15u))
+        atomicOr(a.err, 2u);   // not where the probe saw such blocks run: the exchange cannot be trusted
     for (int s = 0; s < a.n_steps;) {
     // One period (the whole launch when it has no averaging steps).  What the steps derive from
     // the thread's id is derived afresh from an opaque copy per period, so that none of it is
@@ -294,16 +334,26 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
             float act = 0.f;
             if (b < a.B && c_base + c < a.d1) act = round_operand(z > 0.f ? z : 0.f, OT());
             a1s[b][c] = act;
-            // written through to device scope right away, so the release below finds nothing to write back
-            __hip_atomic_store(&xbm[static_cast<int64_t>(b) * a.dp1 + c_base + c], act, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&xfm[static_cast<int64_t>(c_base + c) * Bp + b], act, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            float* pbm = &xbm[static_cast<int64_t>(b) * a.dp1 + c_base + c];
+            float* pfm = &xfm[static_cast<int64_t>(c_base + c) * Bp + b];
+            if (a.local_xcd) {   // as far as the XCD's L2
+                __hip_atomic_store(pbm, act, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_store(pfm, act, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            } else {   // written through to device scope right away, so the release below finds nothing to write back
+                __hip_atomic_store(pbm, act, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(pfm, act, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
+        // every wavefront's stores have arrived before the workgroup does
+        __builtin_amdgcn_s_waitcnt(0);
 
         // ---- (2) replica-wide barrier
         __syncthreads();
-        if (tid == 0 && a.NB > 1)
-            arrive_and_wait(&a.ctr[g], a.ctr_base + static_cast<unsigned>(s + 1) * static_cast<unsigned>(a.NB),
-                            a.spin_limit, a.err, gave_up);
+        if (tid == 0 && a.NB > 1) {
+            const unsigned target = a.ctr_base + static_cast<unsigned>(s + 1) * static_cast<unsigned>(a.NB);
+            if (a.local_xcd) arrive_and_wait_same_xcd(&a.ctr[g], target, a.spin_limit, a.err, gave_up);
+            else arrive_and_wait(&a.ctr[g], target, a.spin_limit, a.err, gave_up);
+        }
         __syncthreads();
         // ---- (3) logits: wavefront (mt, kpart) again, partial sums over its share of d1; then
         //      softmax cross-entropy and dZ_2, one thread per sample
@@ -783,6 +833,13 @@ hipError_t launch_resident(lc_handle* h, int n_steps, int period) {
     a.avx = h->res_avx;
     a.gctr = h->res_ctr + 65;
     a.gctr_base = h->res_garrivals;
+    {
+        // blocks are numbered so that each XCD works on a contiguous range of logical blocks: a
+        // replica's NB workgroups share an XCD when the ranges are whole multiples of NB
+        const int64_t per = (static_cast<int64_t>(a.G) * a.NB + kXcds - 1) / kXcds;
+        a.local_xcd = (h->res_local_on && h->res_xcc_known && per % a.NB == 0) ? 1 : 0;
+        a.xcc_of = h->res_xcc_of;
+    }
     if (n_steps < 1 || n_steps > S.slots) return hipErrorInvalidValue;
     if (period < 0 || (period > 0 && (n_steps % period != 0 || !h->res_avx))) return hipErrorInvalidValue;
     const int64_t total = static_cast<int64_t>(a.G) * a.NB;
@@ -802,6 +859,34 @@ hipError_t launch_resident(lc_handle* h, int n_steps, int period) {
     if (period > 0) h->res_garrivals += static_cast<unsigned>(n_steps / period) * static_cast<unsigned>(total);
     timing_stop(h, kTimeBwd);
     return hipGetLastError();
+}
+
+// Where do blocks run?  Hardware block ids are dealt to the XCDs round-robin; the resident kernel's
+// XCD-local exchange needs exactly that, so it is observed once per handle instead of assumed:
+// 256 one-thread blocks report their XCD, and the rule holds if blocks with the same id mod 8
+// agree and the 8 residues name 8 different XCDs.
+hipError_t probe_block_placement(lc_handle* h) {
+    h->res_xcc_known = false;
+    h->res_xcc_of = 0;
+    if (!h->res_ctr) return hipSuccess;
+    unsigned* dev = h->res_ctr + 128;
+    unsigned host[256];
+    hipLaunchKernelGGL(xcd_probe_kernel, dim3(256), dim3(64), 0, h->stream, dev);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(host, dev, sizeof(host), hipMemcpyDeviceToHost, h->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) return e;
+    unsigned seen = 0, packed = 0;
+    for (int r = 0; r < kXcds; ++r) {
+        for (int b = r; b < 256; b += kXcds)
+            if (host[b] != host[r] || host[b] > 15u) return hipSuccess;   // no such rule here: agent-scope exchange
+        if (seen & (1u << host[r])) return hipSuccess;
+        seen |= 1u << host[r];
+        packed |= host[r] << (4 * r);
+    }
+    h->res_xcc_known = true;
+    h->res_xcc_of = packed;
+    return hipSuccess;
 }
 
 }  // namespace lc

@@ -73,6 +73,7 @@ def test_init_rejects_bad_arguments(pkg):
     assert L.lc_update_from_grad(h) == -3
     assert L.lc_workspace_bytes(h) > 0
     # switches of the resident step kernel: argument checks need no device
+    assert L.lc_set_xcd_local_exchange(h, 0) == 0 and L.lc_set_xcd_local_exchange(None, 1) == -1
     assert L.lc_set_first_layer_fusion(h, 0) == 0 and L.lc_set_first_layer_fusion(None, 1) == -1
     assert L.lc_set_resident(h, 0) == 0 and L.lc_set_resident(h, 1) == 0 and L.lc_set_resident(None, 1) == -1
     assert L.lc_set_barrier_polls(h, -1) == -1 and L.lc_set_barrier_polls(h, 0) == 0

@@ -436,6 +436,34 @@ def test_first_layer_fusion_across_steps(pkg, orc, dims, m, B, bf16):
     sep.close()
 
 
+@pytest.mark.parametrize("dims,m,B", [([784, 256, 10], 8, 64), ([96, 64, 16], 16, 32), ([96, 64, 16], 5, 64)])
+def test_resident_exchange_inside_one_xcd_is_bit_identical(pkg, orc, dims, m, B):
+    """The resident kernel's per-step exchange through the XCD's L2 (first two shapes: one replica
+    per XCD, two replicas per XCD) against the agent-scope exchange: same arithmetic, so the same
+    bits; the third shape does not place a replica inside one XCD and uses the agent scope in
+    both runs.  Also against the oracle."""
+    _say(f"xcd-local exchange dims={dims} m={m} B={B}")
+    ref, run = _problem(pkg, orc, dims, m, B, wd=5e-4, lr=0.05)
+    _, far = _problem(pkg, orc, dims, m, B, wd=5e-4, lr=0.05)
+    far.set_xcd_local_exchange(False)
+    for tau in (7, 2):
+        run.local_steps(tau)
+        far.local_steps(tau)
+        ref.local_steps(tau)
+        run.average()
+        far.average()
+        ref.average()
+    X, V, k = run.get_state()
+    Xf, Vf, _ = far.get_state()
+    assert k == 9
+    assert np.array_equal(X.view(np.uint32), Xf.view(np.uint32))
+    assert np.array_equal(V.view(np.uint32), Vf.view(np.uint32))
+    _assert_close(X, ref.X, dims, TOL32 * 4, "X against the oracle")
+    _assert_close(V, ref.V, dims, TOL32 * 8, "V against the oracle")
+    run.close()
+    far.close()
+
+
 PERIOD_CASES = [
     # dims, m, B, tau, periods: one launch holds several periods (32 steps at most); 7 periods of 5
     # need two launches; one period per launch at tau=20; tau=1 (an averaging step after every step);
