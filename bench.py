@@ -57,7 +57,7 @@ PMC_UNFUSED = {
 }
 PMC_RESIDENT = {
     "cfg1": {"traffic": 0.982e6, "mfma_busy_pct": 0.08},     # per launch of 32 local steps and 8 averaging steps
-    "cfg2": {"traffic": 56.548e6, "mfma_busy_pct": 13.36},   # per launch of 5 local steps
+    "cfg2": {"traffic": 47.867e6, "mfma_busy_pct": 14.25},   # per launch of 5 local steps
 }
 
 
@@ -138,7 +138,8 @@ def bench_mlp(args, pkg, synth):
                 % ("resident_kernel" if len(w.dims) == 3 else "resident1_kernel", round(K2 / launches),
                    ", averaging steps inside" if K2 / launches > tau0 else ""),
                 "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                "traffic": PMC_RESIDENT[name]["traffic"] if name in PMC_RESIDENT and args.tau is None else None,
+                "traffic": PMC_RESIDENT[name]["traffic"]
+                if name in PMC_RESIDENT and args.tau is None and not args.agent_scope_exchange else None,
                 "launches": launches, "avg_launch_us": round(avg_launch_ms * 1e3, 2),
                 "algorithmic_flops_per_launch": per_launch_flops,
                 "mfma_busy_pct": PMC_RESIDENT[name]["mfma_busy_pct"] if name in PMC_RESIDENT else None,
