@@ -31,6 +31,12 @@
 // waiting for good and finishes its steps, so the grid always drains.  (A cooperative launch
 // would have the runtime vouch for the co-residency, but costs 18 us more per launch here, a
 // tenth of the throughput at five steps per launch; the bounded wait covers the same case.)
+// Where the block numbering puts all workgroups of a replica on one XCD, slices and counter stay
+// in that XCD's L2 (arrive_and_wait_same_xcd).
+//
+// A launch may also hold several whole communication periods: after every `period` steps the
+// averaging step of Sec. 2 is taken inside the kernel (average_resident), with one barrier over
+// all workgroups of all replicas, always at agent scope.
 #include "lc_internal.h"
 #include "lc_mma.h"
 
