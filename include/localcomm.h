@@ -262,6 +262,20 @@ int adacomm_next_tau_ex(double F0, double Fl, int tau0, int tau_prev, double gam
 int lc_run(lc_handle* h, int64_t K, int tau0, int adaptive, int64_t interval,
            int64_t* sched_k, int32_t* sched_tau, int cap, int32_t* n_sched, int64_t* rounds);
 
+/* Choosing tau_0 (Sec. 4.2, last sentences: a heuristic estimate from a grid search over several
+ * communication periods, each run for a short while).  For every candidate taus[i], from the
+ * model as it is now: K iterations with that fixed period (lc_run without adaptation), then the
+ * training loss of the averaged model into loss_out[i] and the wall-clock seconds of the run into
+ * seconds_out[i]; the state (X, V, k) is put back after each candidate and at the end.  *best is
+ * the index with the largest loss decrease per second, (F_now - loss_out[i]) / seconds_out[i] --
+ * the error-runtime trade-off of the paper read on this machine, where a long period saves
+ * averaging steps and kernel launches instead of network time.  The paper does not state its
+ * criterion; callers who want another one have the two arrays.  The state travels through host
+ * memory (2 m P floats).  Not for use while block momentum is on (LC_ERR_STATE).
+ * Errors: LC_ERR_ARG, LC_ERR_STATE, LC_ERR_HIP, LC_ERR_NONFINITE, LC_ERR_SYNC. */
+int lc_grid_search_tau0(lc_handle* h, const int32_t* taus, int n, int64_t K, double* loss_out,
+                        double* seconds_out, int32_t* best);
+
 /* lc_run() with the refinements.  refine != 0 decides with adacomm_next_tau_ex (lr0 = the rate
  * in force at entry).  The learning-rate schedule is n_lr pairs: from iteration lr_at[j] on
  * (counted from 0 at lc_init, increasing) the rate is lr_val[j].  Changes take effect at

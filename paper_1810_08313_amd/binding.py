@@ -271,6 +271,17 @@ class LocalSGD:
     def set_lazy_broadcast(self, on: bool) -> None:
         self._check(self._L.lc_set_lazy_broadcast(self._h, int(bool(on))), "lc_set_lazy_broadcast")
 
+    def grid_search_tau0(self, taus, K: int):
+        """lc_grid_search_tau0: (index of the best candidate, losses, seconds)."""
+        arr = np.ascontiguousarray(taus, dtype=np.int32)
+        loss = np.zeros(len(arr), np.float64)
+        sec = np.zeros(len(arr), np.float64)
+        best = C.c_int32(-1)
+        self._check(self._L.lc_grid_search_tau0(self._h, arr.ctypes.data_as(C.c_void_p), len(arr), C.c_int64(int(K)),
+                                                loss.ctypes.data_as(C.c_void_p), sec.ctypes.data_as(C.c_void_p),
+                                                C.byref(best)), "lc_grid_search_tau0")
+        return int(best.value), loss, sec
+
     def set_xcd_local_exchange(self, on: bool) -> None:
         self._check(self._L.lc_set_xcd_local_exchange(self._h, int(bool(on))), "lc_set_xcd_local_exchange")
 

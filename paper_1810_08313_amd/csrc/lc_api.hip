@@ -5,6 +5,7 @@
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
+#include <time.h>
 
 #include <new>
 
@@ -753,6 +754,48 @@ int lc_run(lc_handle* h, int64_t K, int tau0, int adaptive, int64_t interval, in
     *rounds = r;
     LC_HIP(h, hipStreamSynchronize(h->stream));
     return LC_OK;
+}
+
+int lc_grid_search_tau0(lc_handle* h, const int32_t* taus, int n, int64_t K, double* loss_out, double* seconds_out,
+                        int32_t* best) {
+    const int rc = require_objective(h);
+    if (rc != LC_OK) return rc;
+    if (!taus || n < 1 || K < 1 || !loss_out || !seconds_out || !best) return LC_ERR_ARG;
+    for (int i = 0; i < n; ++i)
+        if (taus[i] < 1) return LC_ERR_ARG;
+    if (h->bm_on) return LC_ERR_STATE;   // a block-momentum run has state this helper does not save
+    // every candidate starts from the model as it is now: kept on the host meanwhile
+    const size_t count = static_cast<size_t>(h->m) * static_cast<size_t>(h->P);
+    float* X0 = static_cast<float*>(malloc(sizeof(float) * count));
+    float* V0 = static_cast<float*>(malloc(sizeof(float) * count));
+    int64_t k0 = 0;
+    int e = (X0 && V0) ? lc_get_state(h, X0, V0, &k0) : LC_ERR_ARG;
+    double F0 = 0.0;
+    if (e == LC_OK) e = lc_loss(h, &F0);
+    double best_rate = 0.0;
+    *best = -1;
+    for (int i = 0; i < n && e == LC_OK; ++i) {
+        int64_t sk = 0, rounds = 0;
+        int32_t st = 0, ns = 0;
+        timespec t0, t1;
+        clock_gettime(CLOCK_MONOTONIC, &t0);
+        e = lc_run(h, K, taus[i], 0, 0, &sk, &st, 1, &ns, &rounds);   // synchronises the stream at its end
+        clock_gettime(CLOCK_MONOTONIC, &t1);
+        if (e == LC_OK) e = lc_loss(h, &loss_out[i]);
+        if (e != LC_OK) break;
+        seconds_out[i] = static_cast<double>(t1.tv_sec - t0.tv_sec) + 1e-9 * static_cast<double>(t1.tv_nsec - t0.tv_nsec);
+        // the error-runtime trade-off: loss gained per second of this machine's time
+        const double rate = (F0 - loss_out[i]) / (seconds_out[i] > 0.0 ? seconds_out[i] : 1e-9);
+        if (*best < 0 || rate > best_rate) {
+            *best = i;
+            best_rate = rate;
+        }
+        e = lc_set_state(h, X0, V0, k0);
+    }
+    if (e != LC_OK && X0 && V0) (void)lc_set_state(h, X0, V0, k0);
+    free(X0);
+    free(V0);
+    return e;
 }
 
 int lc_set_grad(lc_handle* h, const void* G) {

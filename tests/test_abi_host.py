@@ -67,6 +67,7 @@ def test_init_rejects_bad_arguments(pkg):
     # not attached yet: every device entry point refuses
     assert L.lc_local_steps(h, 1) == -3
     assert L.lc_local_periods(h, 1, 1) == -3 and L.lc_local_periods(None, 1, 1) == -1
+    assert L.lc_grid_search_tau0(h, None, 1, 1, None, None, None) == -3
     assert L.lc_average(h) == -3
     out = C.c_double()
     assert L.lc_loss(h, C.byref(out)) == -3

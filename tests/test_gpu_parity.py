@@ -627,6 +627,40 @@ def test_adaptive_schedule_bit_exact(pkg, orc):
     run.close()
 
 
+@pytest.mark.parametrize("dims,m,B", [([64, 10], 4, 32), ([64, 32, 10], 4, 32), ([130, 70, 33, 7], 3, 16)])
+def test_grid_search_for_tau0(pkg, orc, dims, m, B):
+    """The tau_0 helper: every candidate's loss is the loss of K iterations with that fixed
+    period from the same start (against the oracle's own runs), the state is back where it
+    was afterwards, bit for bit, and the index returned is the largest loss decrease per second
+    of the two arrays it hands back."""
+    _say(f"grid search dims={dims} m={m}")
+    ref, run = _problem(pkg, orc, dims, m, B, N=2000, lr=0.05, beta=0.9, E=512, mean_sd=2.0)
+    run.local_steps(3)
+    run.average()
+    ref.local_steps(3)
+    ref.average()
+    X0, V0, k0 = run.get_state()
+    F0 = run.loss()
+    taus, K = [1, 4, 16, 5], 32
+    best, loss, sec = run.grid_search_tau0(taus, K)
+    X1, V1, k1 = run.get_state()
+    assert k1 == k0 == 3
+    assert np.array_equal(X1.view(np.uint32), X0.view(np.uint32))
+    assert np.array_equal(V1.view(np.uint32), V0.view(np.uint32))
+    assert (sec > 0).all() and np.isfinite(loss).all()
+    assert best == int(np.argmax((F0 - loss) / sec))
+    for i, tau in enumerate(taus):   # the oracle from the same start: a fresh run brought to iteration 3
+        r, g = _problem(pkg, orc, dims, m, B, N=2000, lr=0.05, beta=0.9, E=512, mean_sd=2.0)
+        g.close()
+        r.local_steps(3)
+        r.average()
+        r.run(K, tau)
+        assert abs(loss[i] - r.loss()) < 1e-3 * max(r.loss(), 1e-3), (tau, loss[i], r.loss())
+    with pytest.raises(pkg.LcError):
+        run.grid_search_tau0([4, 0], K)
+    run.close()
+
+
 # ------------------------------------------------------------------ quadratic
 
 def test_quadratic_closed_form_and_schedule(pkg, orc):
