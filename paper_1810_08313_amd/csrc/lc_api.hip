@@ -227,6 +227,54 @@ int whole_periods(int64_t k, int tau, int64_t lim, int64_t k_end) {
     return static_cast<int>(np);
 }
 
+// tau local iterations, n_periods times, with the averaging step after each period where asked.
+// Mini-batch selection does not depend on the weights, so one gather launch prepares the inputs
+// of a whole chunk of steps: as many whole periods as it has slots for, or a piece of a period
+// that is longer than that.  Inside a chunk a period's steps are one resident launch (small
+// models), or one launch sequence per step in which the first layer's backward kernel may run
+// the next step's first forward pass as long as that step belongs to the same period and chunk.
+int run_periods(lc_handle* h, int tau, int n_periods, bool average) {
+    const bool mlp = h->md.kind == LC_KIND_MLP;
+    const int slots = mlp ? h->train.slots : kGatherSlots;
+    const bool resident = mlp && h->res_on && h->res_a1x;
+    int64_t left = static_cast<int64_t>(tau) * n_periods;
+    int pos = 0;   // steps of the current period already taken
+    while (left > 0) {
+        int64_t n = (pos == 0 && tau <= slots) ? static_cast<int64_t>(slots / tau) * tau : (tau - pos < slots ? tau - pos : slots);
+        if (n > left) n = left;
+        if (mlp) LC_HIP(h, launch_gather(h, false, h->k, static_cast<int>(n)));
+        h->a1_ready = false;
+        for (int t = 0; t < n;) {
+            const int in_period = tau - pos < n - t ? tau - pos : static_cast<int>(n - t);
+            if (resident) {
+                LC_HIP(h, launch_resident(h, t, in_period, 0));
+                t += in_period;
+                h->train.cur_slot = t - 1;
+                h->k += in_period;
+                h->v_cleared = false;
+                h->lazy_rows = false;
+                h->res_used = true;
+            } else {
+                for (int u = 0; u < in_period; ++u, ++t) {
+                    h->train.cur_slot = t;
+                    const int r = one_local_step(h, u + 1 < in_period);
+                    if (r != LC_OK) return r;
+                }
+            }
+            pos += in_period;
+            if (pos == tau) {
+                pos = 0;
+                if (average) {
+                    const int r = lc_average(h);
+                    if (r != LC_OK) return r;
+                }
+            }
+        }
+        left -= n;
+    }
+    return LC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -385,30 +433,7 @@ int lc_local_steps(lc_handle* h, int tau) {
     const int rc = require_objective(h);
     if (rc != LC_OK) return rc;
     if (tau < 1) return LC_ERR_ARG;
-    const int slots = h->md.kind == LC_KIND_MLP ? h->train.slots : kGatherSlots;
-    for (int t0 = 0; t0 < tau; t0 += slots) {
-        const int n = tau - t0 < slots ? tau - t0 : slots;
-        // mini-batch selection does not depend on the weights: one launch prepares the inputs
-        // of the next n steps
-        if (h->md.kind == LC_KIND_MLP) LC_HIP(h, launch_gather(h, false, h->k, n));
-        if (h->res_on && h->res_a1x) {
-            // small two-layer model: the n steps are one launch with the weights held on chip
-            LC_HIP(h, launch_resident(h, n, 0));
-            h->train.cur_slot = n - 1;
-            h->k += n;
-            h->v_cleared = false;
-            h->lazy_rows = false;
-            h->res_used = true;
-            continue;
-        }
-        h->a1_ready = false;
-        for (int t = 0; t < n; ++t) {
-            h->train.cur_slot = t;
-            const int r = one_local_step(h, t + 1 < n);
-            if (r != LC_OK) return r;
-        }
-    }
-    return LC_OK;
+    return run_periods(h, tau, 1, false);
 }
 
 int lc_local_periods(lc_handle* h, int tau, int n_periods) {
@@ -421,21 +446,14 @@ int lc_local_periods(lc_handle* h, int tau, int n_periods) {
     const bool small = h->L == 1 || static_cast<int64_t>(h->m) * h->layer[1].dp_in * 64 <= 200 * 1024;
     const bool fused = h->md.kind == LC_KIND_MLP && h->res_on && h->res_a1x && h->res_avx && !h->bm_on &&
                        tau <= h->train.slots && (small || h->res_fuse_always);
-    if (!fused) {
-        for (int p = 0; p < n_periods; ++p) {
-            int e = lc_local_steps(h, tau);
-            if (e == LC_OK) e = lc_average(h);
-            if (e != LC_OK) return e;
-        }
-        return LC_OK;
-    }
+    if (!fused) return run_periods(h, tau, n_periods, true);
     // weights resident on chip: as many whole periods per launch as one gather launch has inputs
     // for, the averaging steps taken inside the kernel
     const int per_launch = h->train.slots / tau;
     for (int done = 0; done < n_periods; done += per_launch) {
         const int p = n_periods - done < per_launch ? n_periods - done : per_launch;
         LC_HIP(h, launch_gather(h, false, h->k, p * tau));
-        LC_HIP(h, launch_resident(h, p * tau, tau));
+        LC_HIP(h, launch_resident(h, 0, p * tau, tau));
         h->train.cur_slot = p * tau - 1;
         h->k += static_cast<int64_t>(p) * tau;
         h->v_cleared = false;

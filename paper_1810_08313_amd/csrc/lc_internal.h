@@ -134,7 +134,7 @@ hipError_t launch_head(lc_handle* h);
 bool resident_shape_ok(const lc_handle* h);
 size_t resident_exchange_floats(const lc_handle* h);   // per layout
 hipError_t probe_block_placement(lc_handle* h);   // synchronises the stream once
-hipError_t launch_resident(lc_handle* h, int n_steps, int period);  // the steps gathered into slots 0 .. n_steps-1
+hipError_t launch_resident(lc_handle* h, int slot0, int n_steps, int period);  // the steps gathered into slots slot0 .. slot0+n_steps-1
 
 // timing helpers used by the launchers
 void timing_start(lc_handle* h, int which);

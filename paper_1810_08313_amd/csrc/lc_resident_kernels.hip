@@ -795,8 +795,8 @@ hipError_t launch_resident1(lc_handle* h, int slot0, int n_steps, int period) {
 
 }  // namespace
 
-hipError_t launch_resident(lc_handle* h, int n_steps, int period) {
-    if (h->L == 1) return launch_resident1(h, 0, n_steps, period);
+hipError_t launch_resident(lc_handle* h, int slot0, int n_steps, int period) {
+    if (h->L == 1) return launch_resident1(h, slot0, n_steps, period);
     const ActSet& S = h->train;
     const bool bf16 = h->md.gemm == LC_GEMM_BF16;
     ResArgs a;
@@ -821,7 +821,7 @@ hipError_t launch_resident(lc_handle* h, int n_steps, int period) {
     a.a0_fm = S.a_fm[0];
     a.a0_slot = static_cast<int64_t>(S.G) * S.Bp * a.dp0;
     a.labels = S.labels;
-    a.slot0 = 0;
+    a.slot0 = slot0;
     a.n_steps = n_steps;
     a.lr = h->md.lr;
     a.beta_first = effective_beta(h);
@@ -846,7 +846,7 @@ hipError_t launch_resident(lc_handle* h, int n_steps, int period) {
         a.local_xcd = (h->res_local_on && h->res_xcc_known && per % a.NB == 0) ? 1 : 0;
         a.xcc_of = h->res_xcc_of;
     }
-    if (n_steps < 1 || n_steps > S.slots) return hipErrorInvalidValue;
+    if (slot0 < 0 || n_steps < 1 || slot0 + n_steps > S.slots) return hipErrorInvalidValue;
     if (period < 0 || (period > 0 && (n_steps % period != 0 || !h->res_avx))) return hipErrorInvalidValue;
     const int64_t total = static_cast<int64_t>(a.G) * a.NB;
     if (total > 256 || a.G > 64 || !h->res_a1x) return hipErrorInvalidValue;
