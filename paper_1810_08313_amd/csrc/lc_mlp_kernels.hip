@@ -132,27 +132,38 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
     }
     __syncthreads();
     const DT* data = static_cast<const DT*>(a.data);
+    // every thread moves 8 consecutive values: one vector load where the row piece is whole and
+    // aligned (d0 a multiple of 8), one vector store per layout (the padded widths are multiples
+    // of 64 and 32; padding positions receive the zeros they must hold anyway)
     {
         const int r = t >> 3, seg = (t & 7) * 8;
         const int64_t idx = rows[r];
+        const int kk0 = k0 + seg;
+        float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (idx >= 0) {
+            if (a.d0 % 8 == 0 && kk0 + 8 <= a.d0) {
+                const Frag<DT> f = load8(data + idx * a.d0 + kk0);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int kk = k0 + seg + e;
-            tile[r][seg + e] = (idx >= 0 && kk < a.d0) ? to_f32(data[idx * a.d0 + kk]) : 0.f;
+                for (int e = 0; e < 8; ++e) x[e] = to_f32(f.v[e]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (kk0 + e < a.d0) x[e] = to_f32(data[idx * a.d0 + kk0 + e]);
+            }
         }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tile[r][seg + e] = x[e];
+        OT* bm = static_cast<OT*>(a.a_bm) + step * a.a_slot + static_cast<int64_t>(g) * a.Bp * a.dp0;
+        store8(bm + static_cast<int64_t>(b0 + r) * a.dp0 + kk0, x);
     }
     __syncthreads();
-    OT* bm = static_cast<OT*>(a.a_bm) + step * a.a_slot + static_cast<int64_t>(g) * a.Bp * a.dp0;
-    {
-        const int r = t >> 3, seg = (t & 7) * 8;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) bm[static_cast<int64_t>(b0 + r) * a.dp0 + k0 + seg + e] = static_cast<OT>(tile[r][seg + e]);
-    }
     if (a.a_fm) {
         OT* fm = static_cast<OT*>(a.a_fm) + step * a.a_slot + static_cast<int64_t>(g) * a.dp0 * a.Bp;
         const int kk = t >> 2, seg = (t & 3) * 8;
+        float y[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) fm[static_cast<int64_t>(k0 + kk) * a.Bp + b0 + seg + e] = static_cast<OT>(tile[seg + e][kk]);
+        for (int e = 0; e < 8; ++e) y[e] = tile[seg + e][kk];
+        store8(fm + static_cast<int64_t>(k0 + kk) * a.Bp + b0 + seg, y);
     }
 }
 
