@@ -273,11 +273,28 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
             v1[i] = f32x4{v.x, v.y, v.z, v.w};
         }
     }
-    for (int e = tid; e < 16 * a.dp1; e += kResThreads) {
-        const int k = e / 16, c2 = e % 16;
-        const bool in = k < a.d1 && c2 < a.d2;
-        w2s[c2][k] = in ? Xrg[a.w2_off + static_cast<int64_t>(k) * a.d2 + c2] : 0.f;
-        v2s[c2][k] = in ? Vg[a.w2_off + static_cast<int64_t>(k) * a.d2 + c2] : 0.f;
+    {
+        // the private copy of the second layer: all of a thread's loads first (no branch around them:
+        // positions outside the matrix read its first entry and are zeroed), then its LDS writes
+        constexpr int kPer = 16 * kResMaxD1 / kResThreads;
+        float w2r[kPer], v2r[kPer];
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int e = tid + u * kResThreads, k = e / 16, c2 = e % 16;
+            const bool in = k < a.d1 && c2 < a.d2;
+            const int64_t at = a.w2_off + (in ? static_cast<int64_t>(k) * a.d2 + c2 : 0);
+            w2r[u] = Xrg[at];
+            v2r[u] = Vg[at];
+        }
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int e = tid + u * kResThreads, k = e / 16, c2 = e % 16;
+            const bool in = k < a.d1 && c2 < a.d2;
+            if (e < 16 * a.dp1) {
+                w2s[c2][k] = in ? w2r[u] : 0.f;
+                v2s[c2][k] = in ? v2r[u] : 0.f;
+            }
+        }
     }
     if (tid < 16) {
         const bool in1 = c_base + tid < a.d1, in2 = tid < a.d2;
