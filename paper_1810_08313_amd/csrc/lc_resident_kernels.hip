@@ -258,19 +258,37 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
     const float* Xrg = a.Xr + g * a.xr_stride;
     // ---- load the resident state
     f32x4 v1[kResTiles];   // V_1 at rows 16 kt + j, columns c_base + 4 q .. + 3, kt = wave + 16 i
+    {
+        // all tiles' loads first, with no branch around them (rows that do not exist read the last
+        // row and are zeroed): one memory round trip instead of one per tile
+        float4 wl[kResTiles], vl[kResTiles];
+        if (vec && c_base + 16 <= a.d1) {   // the whole slice exists and is aligned (uniform over the workgroup)
 #pragma unroll
-    for (int i = 0; i < kResTiles; ++i) {
-        const int kt = wave + kResWaves * i;
-        v1[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (kt < n_kt) {
-            const int k = 16 * kt + j, c = c_base + 4 * q;
-            float4 w = make_float4(0.f, 0.f, 0.f, 0.f), v = w;
-            if (k < a.d0) {
-                w = load_w4(Xrg + a.w1_off + static_cast<int64_t>(k) * a.d1, c, a.d1, vec, false);
-                v = load_w4(Vg + a.w1_off + static_cast<int64_t>(k) * a.d1, c, a.d1, vec, false);
+            for (int i = 0; i < kResTiles; ++i) {
+                const int k = 16 * (wave + kResWaves * i) + j, kc = k < a.d0 ? k : a.d0 - 1;
+                const int64_t at = a.w1_off + static_cast<int64_t>(kc) * a.d1 + c_base + 4 * q;
+                wl[i] = *reinterpret_cast<const float4*>(Xrg + at);
+                vl[i] = *reinterpret_cast<const float4*>(Vg + at);
             }
-            w1s[4 * q + 0][k] = w.x; w1s[4 * q + 1][k] = w.y; w1s[4 * q + 2][k] = w.z; w1s[4 * q + 3][k] = w.w;
-            v1[i] = f32x4{v.x, v.y, v.z, v.w};
+        } else {
+#pragma unroll
+            for (int i = 0; i < kResTiles; ++i) {
+                const int k = 16 * (wave + kResWaves * i) + j, kc = k < a.d0 ? k : a.d0 - 1;
+                wl[i] = load_w4(Xrg + a.w1_off + static_cast<int64_t>(kc) * a.d1, c_base + 4 * q, a.d1, vec, false);
+                vl[i] = load_w4(Vg + a.w1_off + static_cast<int64_t>(kc) * a.d1, c_base + 4 * q, a.d1, vec, false);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kResTiles; ++i) {
+            const int kt = wave + kResWaves * i, k = 16 * kt + j;
+            const bool in = k < a.d0;
+            v1[i] = in ? f32x4{vl[i].x, vl[i].y, vl[i].z, vl[i].w} : f32x4{0.f, 0.f, 0.f, 0.f};
+            if (kt < n_kt) {
+                w1s[4 * q + 0][k] = in ? wl[i].x : 0.f;
+                w1s[4 * q + 1][k] = in ? wl[i].y : 0.f;
+                w1s[4 * q + 2][k] = in ? wl[i].z : 0.f;
+                w1s[4 * q + 3][k] = in ? wl[i].w : 0.f;
+            }
         }
     }
     {
