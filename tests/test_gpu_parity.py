@@ -461,6 +461,13 @@ def test_resident_exchange_inside_one_xcd_is_bit_identical(pkg, orc, dims, m, B)
     assert np.array_equal(V.view(np.uint32), Vf.view(np.uint32))
     _assert_close(X, ref.X, dims, TOL32 * 4, "X against the oracle")
     _assert_close(V, ref.V, dims, TOL32 * 8, "V against the oracle")
+    # a longer run through the schedule driver (400 steps, 80 averaging steps): still the same bits
+    run.run(400, 5)
+    far.run(400, 5)
+    X, V, _ = run.get_state()
+    Xf, Vf, _ = far.get_state()
+    assert np.array_equal(X.view(np.uint32), Xf.view(np.uint32))
+    assert np.array_equal(V.view(np.uint32), Vf.view(np.uint32))
     # the bounded wait of this form of the barrier gives up the same way
     run.set_barrier_polls(0)
     run.local_steps(2)
@@ -468,7 +475,7 @@ def test_resident_exchange_inside_one_xcd_is_bit_identical(pkg, orc, dims, m, B)
         run.get_state()
     assert ei.value.status == -9
     run.set_barrier_polls(400000)
-    run.set_state(Xf, Vf, 9)
+    run.set_state(Xf, Vf, 409)
     run.local_steps(3)
     far.local_steps(3)
     X, V, _ = run.get_state()
