@@ -142,3 +142,17 @@ def test_product_path_does_not_touch_the_oracle():
             if fn.endswith((".py", ".hip", ".h", ".cpp")):
                 src = open(os.path.join(dp, fn)).read()
                 assert "oracle" not in src.lower().replace("no cpu path", ""), os.path.join(dp, fn)
+
+
+def test_public_header_is_plain_c(tmp_path):
+    """include/localcomm.h is the boundary: it must compile as C99 and as C++ on its own."""
+    import shutil
+    import subprocess
+    inc = os.path.join(ROOT, "include")
+    for cc, std, ext in (("gcc", "-std=c99", "c"), ("g++", "-std=c++17", "cpp")):
+        if not shutil.which(cc):
+            pytest.skip(f"{cc} not available")
+        src = tmp_path / f"use_header.{ext}"
+        src.write_text('#include "localcomm.h"\nint main(void) { return LC_OK; }\n')
+        subprocess.run([cc, std, "-pedantic", "-Wall", "-Werror", "-I", inc, "-c", str(src), "-o", str(tmp_path / f"o_{ext}.o")],
+                       check=True, capture_output=True)
