@@ -174,9 +174,10 @@ int lc_materialize(lc_handle* h);
 /* Resident local steps (Sec. 2: a worker's tau local updates touch only its own model).  For
  * two-layer LC_KIND_MLP models with at most 16 classes, B <= 64, padded widths d0 <= 1024 and
  * d1 <= 256, m <= 64 and m * ceil64(d1) / 16 <= 256, lc_local_steps() runs up to 32 consecutive
- * steps (8 when the gathered inputs of a step exceed 4 MB) as ONE kernel: each workgroup keeps a 16-unit slice of the first layer and its momentum
- * on chip (LDS and registers) for all of them, and the workgroups of a replica meet once per step
- * at a barrier in device memory to exchange the hidden activations.  One-layer models (softmax
+ * steps (8 when the gathered inputs of a step exceed 4 MB) as ONE kernel: each workgroup keeps a 16-unit slice of the first layer, the matching
+ * rows of the second layer and their momentum on chip (LDS and registers) for all of them, and the
+ * workgroups of a replica meet once per step at a barrier in device memory to exchange their shares
+ * of the logits.  One-layer models (softmax
  * regression) with at most 16 classes, B <= 64 and padded d0 <= 256 take the same route with one
  * workgroup per replica and no barrier.  Same arithmetic as the
  * launch-per-layer path up to the summation order (results agree to rounding, not bit for bit).
@@ -191,9 +192,9 @@ int lc_materialize(lc_handle* h);
  * other streams keep compute units busy at the same time -- turn the mode off for such use. */
 int lc_set_resident(lc_handle* h, int on);
 /* Exchange inside one XCD.  The resident step kernel's workgroups of one replica exchange their
- * activations once per step.  Blocks are numbered so that a replica's workgroups run on one XCD
+ * shares of the logits once per step.  Blocks are numbered so that a replica's workgroups run on one XCD
  * (one L2 cache) whenever m * ceil64(d1) / 16 / 8 is a multiple of ceil64(d1) / 16; counter and
- * activations then stay in that L2 (workgroup-scope atomics, which the hardware performs in the
+ * exchanged values then stay in that L2 (workgroup-scope atomics, which the hardware performs in the
  * L2, and an invalidate of the compute unit's L1 only) instead of travelling to the memory side
  * and back.  The placement rule (hardware block id mod 8 selects the XCD) is observed by a probe
  * kernel at lc_attach(), and every workgroup compares its own XCD id with it when it starts: a

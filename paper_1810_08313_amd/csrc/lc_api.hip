@@ -133,7 +133,7 @@ size_t carve(lc_handle* h, char* base) {
         S.loss = static_cast<float*>(c.take(sizeof(float) * static_cast<size_t>(S.G) * passes * kLossParts));
     }
     if (resident_shape_ok(h)) {
-        h->res_a1x = static_cast<float*>(c.take(sizeof(float) * 2 * resident_exchange_floats(h)));
+        h->res_a1x = static_cast<float*>(c.take(sizeof(float) * resident_exchange_floats(h)));
         h->res_ctr = static_cast<unsigned*>(c.take(sizeof(unsigned) * 384));
         h->res_avx = static_cast<float*>(c.take(sizeof(float) * 2 * static_cast<size_t>(h->m) * h->Ps));
     } else {

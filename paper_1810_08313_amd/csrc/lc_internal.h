@@ -86,7 +86,7 @@ struct lc_handle {
     int loss_parts_train, loss_parts_eval;   // how many of the kLossParts slots the last launch wrote
     bool lazy_enabled_step;   // set only while lc_average runs its reduce-only form
     // resident local steps (small two-layer models): exchange buffer, barrier counters, switches
-    float* res_a1x;         // [2 layouts][2 parities][m][Bp][dp1], null when the shape does not qualify
+    float* res_a1x;         // [2 parities][m][dp1/16][Bp][16] exchange buffer of the resident kernel, null when the shape does not qualify
     unsigned* res_ctr;      // [0..63] arrival counters per replica, [64] error flag, [65] all-replica counter, [128..383] placement probe
     unsigned res_arrivals;  // value of every counter once the queued launches have run (zeroed with the scratch at attach)
     float* res_avx;         // [2 parities][m][Ps] models handed over at averaging steps inside a launch
@@ -132,7 +132,7 @@ hipError_t launch_head(lc_handle* h);
 
 // resident path (weights stay in LDS over a run of local steps)
 bool resident_shape_ok(const lc_handle* h);
-size_t resident_exchange_floats(const lc_handle* h);   // per layout
+size_t resident_exchange_floats(const lc_handle* h);
 hipError_t probe_block_placement(lc_handle* h);   // synchronises the stream once
 hipError_t launch_resident(lc_handle* h, int slot0, int n_steps, int period);  // the steps gathered into slots slot0 .. slot0+n_steps-1
 

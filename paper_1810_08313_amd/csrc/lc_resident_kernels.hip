@@ -9,21 +9,26 @@
 // system in every one of them; at this size those launches, not the arithmetic, are the cost.
 //
 // Work split for a model d0 -> d1 -> d2 (d2 <= 16), replica g, workgroup cb of NB = dp1 / 16:
-//   owns   hidden units C = [16 cb, 16 cb + 16): columns C of W_1, V_1 and entries C of b_1;
-//   keeps  a full private copy of W_2, V_2, b_2 (d1 x d2 is tiny), updated identically by
-//          every workgroup of the replica, so the second layer needs no exchange at all.
+//   owns   hidden units C = [16 cb, 16 cb + 16): columns C of W_1, V_1, entries C of b_1, and the
+//          matching ROWS C of W_2, V_2 -- every weight of the model has exactly one owner;
+//   keeps  a private copy of b_2 (d2 values), updated identically by every workgroup.
 // One step:
 //   (1) A_1[:, C] = ReLU(A_0 W_1[:, C] + b_1[C])          MFMA; the 16 wavefronts split batch tiles and K
-//   (2) publish the slice, replica-wide barrier, every workgroup then sees all of A_1
-//   (3) Z_2 = A_1 W_2 + b_2, softmax cross-entropy, dZ_2   (redundantly in every workgroup)
+//   (2) this slice's share of the logits, A_1[:, C] W_2[C, :] (Bp x 16 values), handed to the
+//       replica; replica-wide barrier
+//   (3) Z_2 = sum of the NB shares in slice order + b_2, softmax cross-entropy, dZ_2
+//       (redundantly in every workgroup: a few hundred values)
 //   (4) dZ_1[:, C] = (dZ_2 W_2[C, :]^T) .* [A_1[:, C] > 0]  with the weights of before the update
-//   (5) dW_2 = A_1^T dZ_2, db_2 and the momentum update of the private copy
+//   (5) dW_2[C, :] = A_1[:, C]^T dZ_2, db_2 and their momentum updates
 //   (6) dW_1[:, C] = A_0^T dZ_1[:, C], db_1[C] and the momentum update of the slice
-// The only communication is the A_1 slice (Bp x 16 values per workgroup and step), double
-// buffered by step parity so that a fast workgroup never overwrites what a slow one still reads.
+// The only communication is the share of the logits (Bp x 16 values per workgroup and step),
+// double buffered by step parity so that a fast workgroup never overwrites what a slow one still
+// reads.  (Exchanging the logit shares instead of the activations is what lets W_2 be
+// partitioned: with the activations exchanged every workgroup had to keep and update a full
+// copy of W_2, and the second layer's products, done 16 times over, were a quarter of the step.)
 //
 // The barrier is a counter per replica in device memory: arrive with an agent-scope release,
-// poll with relaxed loads, then an agent-scope acquire.  The slices are published with
+// poll with relaxed loads, then an agent-scope acquire.  The shares are published with
 // agent-scope (write-through) stores, so the release has no dirty cache lines to write back;
 // the counters are never reset, each launch is told their value at its start.  All workgroups of a launch are
 // co-resident (the launcher refuses grids above one workgroup per compute unit), and the
@@ -68,8 +73,7 @@ struct ResArgs {
     int slot0, n_steps;
     float lr, beta_first, beta, wd;
     int vec;              // rows of W_1 may be accessed 16 bytes at a time
-    float* a1x_bm;        // [2][G][Bp][dp1]  exchange buffer, batch-major
-    float* a1x_fm;        // [2][G][dp1][Bp]  the same, feature-major
+    float* zx;            // [2][G][NB][Bp][16] exchange buffer: the slices' shares of the logits, by step parity
     unsigned* ctr;        // [G] arrivals since attach (every workgroup arrives once per step, whatever happens)
     unsigned ctr_base;    // their value when this launch starts
     unsigned* err;        // set to 1 when a barrier wait ran out of polls
@@ -166,7 +170,7 @@ __device__ __forceinline__ float round_operand(float x, float) { return x; }
 // the barrier of the period in between, which every reader of the older contents has reached by
 // then.
 __device__ __forceinline__ void average_resident(const ResArgs& a, int tid, int pi, int g, int cb,
-                                                 float (*w1s)[kResK1P], float (*w2s)[kResK2P], float* b1s,
+                                                 float (*w1s)[kResK1P], float (*w2s)[17], float* b1s,
                                                  float* b2s, bool& gave_up) {
     const int wave = tid >> 6, j = tid & 15, q = (tid >> 4) & 3;
     const int c_base = 16 * cb, n_kt = a.dp0 / 16;
@@ -181,10 +185,11 @@ __device__ __forceinline__ void average_resident(const ResArgs& a, int tid, int 
         }
     }
     if (tid < 16 && c_base + tid < a.d1) mine[a.b1_off + c_base + tid] = b1s[tid];
-    if (cb == 0) {
-        for (int e = tid; e < a.d1 * a.d2; e += kResThreads) mine[a.w2_off + e] = w2s[e % a.d2][e / a.d2];
-        if (tid < a.d2) mine[a.b2_off + tid] = b2s[tid];
+    if (tid >= 64 && tid < 320) {   // own rows of the second layer
+        const int kk = (tid - 64) >> 4, c2 = tid & 15;
+        if (c_base + kk < a.d1 && c2 < a.d2) mine[a.w2_off + static_cast<int64_t>(c_base + kk) * a.d2 + c2] = w2s[c2][kk];
     }
+    if (cb == 0 && tid < a.d2) mine[a.b2_off + tid] = b2s[tid];
     __builtin_amdgcn_s_waitcnt(0);   // this wavefront's stores have left before the workgroup arrives
     __syncthreads();
     if (tid == 0)
@@ -219,9 +224,11 @@ __device__ __forceinline__ void average_resident(const ResArgs& a, int tid, int 
     }
     // the second layer and the biases, an entry at a time (its m loads together): this phase must
     // stay light in registers, the step loop around it has none to spare
-#pragma unroll 1
-    for (int e = tid; e < a.d1 * a.d2; e += kResThreads)
-        w2s[e % a.d2][e / a.d2] = mean_of_replicas(all + a.w2_off + e, a.x_stride, a.G);
+    if (tid >= 128 && tid < 384) {
+        const int kk = (tid - 128) >> 4, c2 = tid & 15;
+        if (c_base + kk < a.d1 && c2 < a.d2)
+            w2s[c2][kk] = mean_of_replicas(all + a.w2_off + static_cast<int64_t>(c_base + kk) * a.d2 + c2, a.x_stride, a.G);
+    }
     if (tid < 16 && c_base + tid < a.d1) b1s[tid] = mean_of_replicas(all + a.b1_off + c_base + tid, a.x_stride, a.G);
     if (tid >= 64 && tid < 64 + a.d2) b2s[tid - 64] = mean_of_replicas(all + a.b2_off + tid - 64, a.x_stride, a.G);
     __syncthreads();
@@ -233,12 +240,10 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
     constexpr int NS = Bp / 32;   // 32-wide steps over the batch
     constexpr int KP = kResWaves / MT;   // wavefronts that share one batch tile and split the reduction
     __shared__ __attribute__((aligned(16))) float w1s[16][kResK1P];    // W_1[:, C]^T
-    __shared__ __attribute__((aligned(16))) float w2s[16][kResK2P];    // W_2^T (row = class)
-    __shared__ __attribute__((aligned(16))) float v2s[16][kResK2P];
+    __shared__ float w2s[16][17], v2s[16][17];                          // W_2[C, :]^T, V_2[C, :]^T: [class][own hidden unit]
     __shared__ __attribute__((aligned(16))) float part[KP][Bp][17];
     __shared__ float a1s[Bp][17];                                       // own slice of A_1
     __shared__ float z2s[Bp][17];                                       // logits, then dZ_2
-    __shared__ __attribute__((aligned(16))) OT dz2t[16][Bp + 8];        // dZ_2^T
     __shared__ __attribute__((aligned(16))) OT dz1t[16][Bp + 8];        // dZ_1[:, C]^T
     __shared__ float b1s[16], vb1s[16], b2s[16], vb2s[16];
     __shared__ float lred[Bp];
@@ -291,28 +296,13 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
             }
         }
     }
-    {
-        // the private copy of the second layer: all of a thread's loads first (no branch around them:
-        // positions outside the matrix read its first entry and are zeroed), then its LDS writes
-        constexpr int kPer = 16 * kResMaxD1 / kResThreads;
-        float w2r[kPer], v2r[kPer];
-#pragma unroll
-        for (int u = 0; u < kPer; ++u) {
-            const int e = tid + u * kResThreads, k = e / 16, c2 = e % 16;
-            const bool in = k < a.d1 && c2 < a.d2;
-            const int64_t at = a.w2_off + (in ? static_cast<int64_t>(k) * a.d2 + c2 : 0);
-            w2r[u] = Xrg[at];
-            v2r[u] = Vg[at];
-        }
-#pragma unroll
-        for (int u = 0; u < kPer; ++u) {
-            const int e = tid + u * kResThreads, k = e / 16, c2 = e % 16;
-            const bool in = k < a.d1 && c2 < a.d2;
-            if (e < 16 * a.dp1) {
-                w2s[c2][k] = in ? w2r[u] : 0.f;
-                v2s[c2][k] = in ? v2r[u] : 0.f;
-            }
-        }
+    if (tid < 256) {   // own rows of the second layer
+        const int kk = tid >> 4, c2 = tid & 15;
+        const bool in = c_base + kk < a.d1 && c2 < a.d2;
+        const int64_t at = a.w2_off + (in ? static_cast<int64_t>(c_base + kk) * a.d2 + c2 : 0);
+        const float w = Xrg[at], v = Vg[at];
+        w2s[c2][kk] = in ? w : 0.f;
+        v2s[c2][kk] = in ? v : 0.f;
     }
     if (tid < 16) {
         const bool in1 = c_base + tid < a.d1, in2 = tid < a.d2;
@@ -340,8 +330,7 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
         const OT* A0T = static_cast<const OT*>(a.a0_fm) + slot * a.a0_slot + static_cast<int64_t>(g) * a.dp0 * Bp;
         const int32_t* lab = a.labels + (static_cast<int64_t>(slot) * a.G + g) * Bp;
         const int par = s & 1;
-        float* xbm = a.a1x_bm + (static_cast<int64_t>(par) * a.G + g) * Bp * a.dp1;
-        float* xfm = a.a1x_fm + (static_cast<int64_t>(par) * a.G + g) * a.dp1 * Bp;
+        float* xp = a.zx + (static_cast<int64_t>(par) * a.G + g) * Bp * a.dp1;   // [NB][Bp][16]
         // ---- (1) Z_1[:, C]: wavefront (mt, kpart) takes batch tile mt and the 32-wide k steps
         //      kpart, kpart + KP, ...
         const int mt = wave % MT, kpart = wave / MT;
@@ -375,15 +364,17 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
             float act = 0.f;
             if (b < a.B && c_base + c < a.d1) act = round_operand(z > 0.f ? z : 0.f, OT());
             a1s[b][c] = act;
-            float* pbm = &xbm[static_cast<int64_t>(b) * a.dp1 + c_base + c];
-            float* pfm = &xfm[static_cast<int64_t>(c_base + c) * Bp + b];
-            if (a.local_xcd) {   // as far as the XCD's L2
-                __hip_atomic_store(pbm, act, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                __hip_atomic_store(pfm, act, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            } else {   // written through to device scope right away, so the release below finds nothing to write back
-                __hip_atomic_store(pbm, act, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(pfm, act, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+        }
+        __syncthreads();
+        // ---- (2) this slice's share of the logits, A_1[:, C] W_2[C, :], handed to the replica
+        if (tid < Bp * 16) {
+            const int b = tid >> 4, c2 = tid & 15;
+            float zp = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < 16; ++kk) zp += a1s[b][kk] * round_operand(w2s[c2][kk], OT());
+            float* px = xp + static_cast<int64_t>(cb) * (Bp * 16) + tid;
+            if (a.local_xcd) __hip_atomic_store(px, zp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);   // as far as the XCD's L2
+            else __hip_atomic_store(px, zp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // written through to device scope
         }
         // every wavefront's stores have arrived before the workgroup does
         __builtin_amdgcn_s_waitcnt(0);
@@ -396,34 +387,21 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
             else arrive_and_wait(&a.ctr[g], target, a.spin_limit, a.err, gave_up);
         }
         __syncthreads();
-        // ---- (3) logits: wavefront (mt, kpart) again, partial sums over its share of d1; then
-        //      softmax cross-entropy and dZ_2, one thread per sample
-        {
-            f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
-            const float* arow = xbm + static_cast<int64_t>(16 * mt + j) * a.dp1 + 8 * q;
-            for (int st = kpart; st < a.dp1 / 32; st += KP) {
-                const int k0 = 32 * st + 8 * q;
-                const float4 y0 = *reinterpret_cast<const float4*>(arow + 32 * st);
-                const float4 y1 = *reinterpret_cast<const float4*>(arow + 32 * st + 4);
-                const float y[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
-                const float4 x0 = *reinterpret_cast<const float4*>(&w2s[j][k0]);
-                const float4 x1 = *reinterpret_cast<const float4*>(&w2s[j][k0 + 4]);
-                const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-                Frag<OT> bf, af;
-                pack8(bf, x);
-                pack8(af, y);
-                z = mma8(af, bf, z);
-            }
-#pragma unroll
-            for (int r = 0; r < 4; ++r) part[kpart][16 * mt + 4 * q + r][j] = z[r];
-        }
-        __syncthreads();
+        // ---- (3) logits = sum of the slices' shares in slice order + b_2; softmax cross-entropy and
+        //      dZ_2 (redundantly in every workgroup: a few hundred values)
         // one thread per (sample, class): 16-lane groups hold a sample's logits
         if (tid < Bp * 16) {
             const int b = tid >> 4, c = tid & 15;
-            float z = part[0][b][c];
+            float z = 0.f;
+            for (int o0 = 0; o0 < a.NB; o0 += 8) {   // eight loads in flight, added in slice order
+                float r[8];
 #pragma unroll
-            for (int p = 1; p < KP; ++p) z += part[p][b][c];
+                for (int u = 0; u < 8; ++u)
+                    if (o0 + u < a.NB) r[u] = xp[static_cast<int64_t>(o0 + u) * (Bp * 16) + tid];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (o0 + u < a.NB) z += r[u];
+            }
             z += b2s[c];
             const int y = b < a.B ? lab[b] : -1;
             const bool valid = c < a.d2;
@@ -439,7 +417,6 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
             if (y >= 0 && valid)
                 dz = round_operand((ex * (1.f / sum) - (c == y ? 1.f : 0.f)) * (1.f / static_cast<float>(a.B)), OT());
             z2s[b][c] = dz;
-            dz2t[c][b] = static_cast<OT>(dz);
             if (c == 0) lred[b] = y >= 0 ? -(zy - zmax - logf(sum)) : 0.f;
         }
         __syncthreads();
@@ -455,7 +432,7 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
         if (tid < Bp * 16) {
             const int b = tid >> 4, c = tid & 15;
             float sum = 0.f;
-            for (int c2 = 0; c2 < a.d2; ++c2) sum += z2s[b][c2] * round_operand(w2s[c2][c_base + c], OT());
+            for (int c2 = 0; c2 < a.d2; ++c2) sum += z2s[b][c2] * round_operand(w2s[c2][c], OT());
             const OT d = static_cast<OT>(a1s[b][c] > 0.f ? sum : 0.f);   // rounds in bf16 mode
             dz1t[c][b] = d;
             float s1 = to_f32(d), s2 = z2s[b][c];
@@ -484,30 +461,16 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
                 b2s[c] -= a.lr * vb;
             }
         }
-        // ---- (5) dW_2 = A_1^T dZ_2 and the update of the private copy; tile kt = 16 rows of W_2
-        for (int kt = wave; kt < a.dp1 / 16; kt += kResWaves) {
-            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int st = 0; st < NS; ++st) {
-                const int b0 = 32 * st + 8 * q;
-                const float* ar = xfm + static_cast<int64_t>(16 * kt + j) * Bp + b0;
-                const float4 y0 = *reinterpret_cast<const float4*>(ar);
-                const float4 y1 = *reinterpret_cast<const float4*>(ar + 4);
-                const float y[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
-                Frag<OT> af;
-                pack8(af, y);
-                const Frag<OT> bf = *reinterpret_cast<const Frag<OT>*>(&dz2t[j][b0]);
-                acc = mma8(af, bf, acc);
-            }
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int k = 16 * kt + 4 * q + r;
-                if (k < a.d1 && j < a.d2) {
-                    const float w = w2s[j][k];
-                    const float v = beta * v2s[j][k] + (acc[r] + a.wd * w);
-                    v2s[j][k] = v;
-                    w2s[j][k] = w - a.lr * v;
-                }
+        // ---- (5) dW_2[C, :] = A_1[:, C]^T dZ_2 and the update of the own rows (16 x 16 values: plain FMAs)
+        if (tid >= 256 && tid < 512) {   // (threads 0..31 are busy with the biases)
+            const int kk = (tid - 256) >> 4, c2 = tid & 15;
+            if (c_base + kk < a.d1 && c2 < a.d2) {
+                float gw = 0.f;
+                for (int b = 0; b < Bp; ++b) gw += a1s[b][kk] * z2s[b][c2];
+                const float w = w2s[c2][kk];
+                const float v = beta * v2s[c2][kk] + (gw + a.wd * w);
+                v2s[c2][kk] = v;
+                w2s[c2][kk] = w - a.lr * v;
             }
         }
         // ---- (6) dW_1[:, C] = A_0^T dZ_1[:, C] and the update of the slice
@@ -558,16 +521,17 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
         Xg[a.b1_off + c_base + tid] = b1s[tid];
         Vg[a.b1_off + c_base + tid] = vb1s[tid];
     }
-    if (cb == 0) {
-        for (int e = tid; e < a.d1 * a.d2; e += kResThreads) {
-            const int k = e / a.d2, c2 = e % a.d2;
-            Xg[a.w2_off + e] = w2s[c2][k];
-            Vg[a.w2_off + e] = v2s[c2][k];
+    if (tid >= 64 && tid < 320) {   // own rows of the second layer
+        const int kk = (tid - 64) >> 4, c2 = tid & 15;
+        if (c_base + kk < a.d1 && c2 < a.d2) {
+            const int64_t at = a.w2_off + static_cast<int64_t>(c_base + kk) * a.d2 + c2;
+            Xg[at] = w2s[c2][kk];
+            Vg[at] = v2s[c2][kk];
         }
-        if (tid < a.d2) {
-            Xg[a.b2_off + tid] = b2s[tid];
-            Vg[a.b2_off + tid] = vb2s[tid];
-        }
+    }
+    if (cb == 0 && tid < a.d2) {
+        Xg[a.b2_off + tid] = b2s[tid];
+        Vg[a.b2_off + tid] = vb2s[tid];
     }
 }
 
@@ -863,8 +827,7 @@ hipError_t launch_resident(lc_handle* h, int slot0, int n_steps, int period) {
     a.beta = h->md.beta;
     a.wd = h->md.wd;
     a.vec = (a.d1 % 4 == 0 && a.w1_off % 4 == 0) ? 1 : 0;
-    a.a1x_bm = h->res_a1x;
-    a.a1x_fm = h->res_a1x + resident_exchange_floats(h);
+    a.zx = h->res_a1x;
     a.ctr = h->res_ctr;
     a.ctr_base = h->res_arrivals;
     a.err = h->res_ctr + 64;
