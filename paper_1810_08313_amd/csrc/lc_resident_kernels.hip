@@ -444,12 +444,14 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
             }
         }
         __syncthreads();
-        // ---- bias updates (one thread per entry)
-        if (tid < 32) {
+        // ---- bias updates (one thread per entry).  These small jobs go to the last wavefronts:
+        //      when the tiles of step (6) do not divide evenly, those have one tile less to do
+        if (tid >= kResThreads - 64 && tid < kResThreads - 32) {
             const int c = tid & 15;
+            const bool first = tid < kResThreads - 48;
             float db = 0.f;
-            for (int w = 0; w < Bp / 4; ++w) db += tid < 16 ? colsum1[w][c] : colsum2[w][c];
-            if (tid < 16) {
+            for (int w = 0; w < Bp / 4; ++w) db += first ? colsum1[w][c] : colsum2[w][c];
+            if (first) {
                 if (c_base + c < a.d1) {
                     const float vb = beta * vb1s[c] + (db + a.wd * b1s[c]);
                     vb1s[c] = vb;
@@ -462,8 +464,8 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
             }
         }
         // ---- (5) dW_2[C, :] = A_1[:, C]^T dZ_2 and the update of the own rows (16 x 16 values: plain FMAs)
-        if (tid >= 256 && tid < 512) {   // (threads 0..31 are busy with the biases)
-            const int kk = (tid - 256) >> 4, c2 = tid & 15;
+        if (tid >= kResThreads - 320 && tid < kResThreads - 64) {
+            const int kk = (tid - (kResThreads - 320)) >> 4, c2 = tid & 15;
             if (c_base + kk < a.d1 && c2 < a.d2) {
                 float gw = 0.f;
                 for (int b = 0; b < Bp; ++b) gw += a1s[b][kk] * z2s[b][c2];
