@@ -57,7 +57,7 @@ PMC_UNFUSED = {
 }
 PMC_RESIDENT = {
     "cfg1": {"traffic": 0.982e6, "mfma_busy_pct": 0.08},     # per launch of 32 local steps and 8 averaging steps
-    "cfg2": {"traffic": 45.572e6, "mfma_busy_pct": 12.65},   # per launch of 5 local steps
+    "cfg2": {"traffic": 45.571e6, "mfma_busy_pct": 12.55},   # per launch of 5 local steps
 }
 
 
