@@ -727,16 +727,22 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         const bool has_next = i + 1 < cc_n;
         if (has_next) issue_loads(chunk_at(i + 1), wn, vn);
 
-        // bias of these 64 columns: db_l = sum_b dZ_l from the staged slice, then the
-        // same update (first row block of the replica; one thread per column)
-        if (rb == 0 && tid < kColChunk && c0 + tid < a.d_out) {
+        // bias of these 64 columns: db_l = sum_b dZ_l from the staged slice, then the same update
+        // (one thread per column).  Every row block of the replica walks this chunk; the job goes
+        // to them in turn, so that no workgroup carries it on all of its trips and finishes late.
+        if (rb == chunk_at(i) % a.n_row_blocks && tid < kColChunk && c0 + tid < a.d_out) {
             float* bx = a.X + g * a.x_stride + a.b_off + c0 + tid;
             float* bv = a.V + g * a.x_stride + a.b_off + c0 + tid;
             const float x = a.Xr[g * a.xr_stride + a.b_off + c0 + tid];   // requested before the sum below
             const float v0 = *bv;
             const OT* zr = dzt_lds[(tid & 3) * 16 + (tid >> 2)];
-            float sb = 0.f;
-            for (int b = 0; b < a.B; ++b) sb += to_f32(zr[b]);
+            float sb = 0.f;   // (batch entries beyond B are zeros; the order of the sum is the batch order)
+#pragma unroll
+            for (int b8 = 0; b8 < Bp; b8 += 8) {
+                const Frag<OT> f = *reinterpret_cast<const Frag<OT>*>(zr + b8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sb += to_f32(f.v[e]);
+            }
             const float vb = a.beta * v0 + (sb + a.wd * x);
             *bv = vb;
             *bx = x - a.lr * vb;
