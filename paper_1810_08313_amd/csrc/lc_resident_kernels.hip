@@ -337,7 +337,7 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
         {
             f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
             const OT* arow = A0 + static_cast<int64_t>(16 * mt + j) * a.dp0 + 8 * q;
-            const int n_st = a.dp0 / 32;
+            const int n_st = (a.d0 + 31) / 32;   // (steps that hold only padding rows are skipped)
             Frag<OT> af = load8(arow + 32 * (kpart < n_st ? kpart : 0));
             for (int st = kpart; st < n_st; st += KP) {
                 const int k0 = 32 * st + 8 * q;
@@ -479,7 +479,7 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
 #pragma unroll
         for (int i = 0; i < kResTiles; ++i) {
             const int kt = wave + kResWaves * i;
-            if (kt < n_kt) {
+            if (16 * kt < a.d0) {   // (tiles that hold only padding rows have nothing to update)
                 f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int st = 0; st < NS; ++st) {
