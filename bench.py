@@ -41,23 +41,23 @@ PMC = {
     "cfg2": {"traffic": (28.105e6 + 2.381e6) / 2, "mfma_busy_pct": (8.34 * 9.2 + 1.16 * 8.8) / 18.0},
     # layer 1: first_layer_kernel where the next step's input is at hand (18 of 20 steps at tau=20,
     # 9 of 10 at tau=10; 16 steps are gathered per launch), backward_kernel otherwise
-    "cfg3": {"traffic": ((0.9 * 844.997e6 + 0.1 * 822.521e6) + 288.489e6 + 15.958e6) / 3,
-             "mfma_busy_pct": (0.9 * 7.59 * 202.0 + 0.1 * 3.16 * 162.0 + 4.35 * 70.2 + 1.16 * 10.8) /
-                              (0.9 * 202.0 + 0.1 * 162.0 + 70.2 + 10.8)},
-    "cfg4": {"traffic": ((0.9 * 6527.112e6 + 0.1 * 6466.016e6) + 2 * 4335.244e6 + 46.474e6) / 4,
-             "mfma_busy_pct": (0.9 * 2.35 * 1262 + 0.1 * 0.87 * 1184 + 1.64 * 1694 + 1.21 * 27) /
+    "cfg3": {"traffic": ((0.9 * 845.005e6 + 0.1 * 822.542e6) + 288.518e6 + 15.975e6) / 3,
+             "mfma_busy_pct": (0.9 * 7.59 * 202.0 + 0.1 * 3.18 * 162.0 + 4.75 * 64.3 + 1.18 * 10.8) /
+                              (0.9 * 202.0 + 0.1 * 162.0 + 64.3 + 10.8)},
+    "cfg4": {"traffic": ((0.9 * 6527.158e6 + 0.1 * 6465.989e6) + 2 * 4336.169e6 + 46.453e6) / 4,
+             "mfma_busy_pct": (0.9 * 2.36 * 1262 + 0.1 * 0.87 * 1184 + 1.65 * 1694 + 1.21 * 27) /
                               (0.9 * 1262 + 0.1 * 1184 + 1694 + 27)},
 }
 # the same two workloads with --no-first-layer-fusion (backward_kernel for every layer)
 PMC_UNFUSED = {
-    "cfg3": {"traffic": (822.521e6 + 288.489e6 + 15.958e6) / 3,
-             "mfma_busy_pct": (3.16 * 162.0 + 4.35 * 70.2 + 1.16 * 10.8) / 243.0},
-    "cfg4": {"traffic": (6466.016e6 + 2 * 4335.244e6 + 46.474e6) / 4,
-             "mfma_busy_pct": (0.87 * 1184 + 1.64 * 1694 + 1.21 * 27) / 2905},
+    "cfg3": {"traffic": (822.542e6 + 288.518e6 + 15.975e6) / 3,
+             "mfma_busy_pct": (3.18 * 162.0 + 4.75 * 64.3 + 1.18 * 10.8) / 237.1},
+    "cfg4": {"traffic": (6465.989e6 + 2 * 4336.169e6 + 46.453e6) / 4,
+             "mfma_busy_pct": (0.87 * 1184 + 1.65 * 1694 + 1.21 * 27) / 2905},
 }
 PMC_RESIDENT = {
     "cfg1": {"traffic": 0.982e6, "mfma_busy_pct": 0.08},     # per launch of 32 local steps and 8 averaging steps
-    "cfg2": {"traffic": 45.571e6, "mfma_busy_pct": 12.55},   # per launch of 5 local steps
+    "cfg2": {"traffic": 44.761e6, "mfma_busy_pct": 12.01},   # per launch of 5 local steps
 }
 
 
