@@ -75,6 +75,8 @@ def parse():
                     help="launch-per-layer kernels also where the resident step kernel applies")
     ap.add_argument("--agent-scope-exchange", action="store_true",
                     help="resident kernel: exchange through device scope (see lc_set_xcd_local_exchange)")
+    ap.add_argument("--no-deferred-update", action="store_true",
+                    help="at tau = 1 write every replica's weights in the step (lc_set_deferred_update(0))")
     ap.add_argument("--no-first-layer-fusion", action="store_true",
                     help="separate first-layer forward launch in every step (see lc_set_first_layer_fusion)")
     return ap.parse_args()
@@ -98,6 +100,7 @@ def bench_mlp(args, pkg, synth):
     run.set_lazy_broadcast(not args.eager)   # bit-identical results; see lc_set_lazy_broadcast
     run.set_resident(not args.layer_kernels)
     run.set_first_layer_fusion(not args.no_first_layer_fusion)
+    run.set_deferred_update(not args.no_deferred_update)
     run.set_xcd_local_exchange(not args.agent_scope_exchange)
     resident = run.resident_active()
     interval = w.interval if adaptive else 0
@@ -146,6 +149,10 @@ def bench_mlp(args, pkg, synth):
                 "workgroups": workgroups, "compute_units": 256}
     else:
         bytes_per_iter = 16.0 * w.m * w.P                    # read W,V + write W,V of every replica, fp32
+        if tau0 == 1 and not adaptive and not args.eager:
+            # every iteration starts from the one averaged model (read once), and with the deferred
+            # update the weights of the replicas are never written
+            bytes_per_iter = (8.0 if not args.no_deferred_update else 12.0) * w.m * w.P + 4.0 * w.P
         per_launch_bytes = bytes_per_iter * K2 / launches
         achieved = per_launch_bytes / (avg_launch_ms * 1e-3) / 1e9
         pmc = (PMC_UNFUSED if args.no_first_layer_fusion and name in PMC_UNFUSED else PMC).get(name) \
@@ -167,7 +174,8 @@ def bench_mlp(args, pkg, synth):
            "m": w.m, "P": w.P, "batch_per_replica": w.B, "tau0": tau0, "adaptive": adaptive,
            "averaging_rounds": rounds, "tau_schedule": sched[:16], "final_loss": round(final_loss, 6),
            "deferred_broadcast": not args.eager, "resident_step_kernel": resident,
-           "first_layer_fusion": not args.no_first_layer_fusion}
+           "first_layer_fusion": not args.no_first_layer_fusion,
+           "deferred_update_at_tau_1": not args.no_deferred_update and not args.eager}
     return dict(value=w.m * K / sec, sec=sec, K=K, W=W, roofline=roof, config=cfg,
                 dtype="bf16" if w.bf16 else "f32", workload=w, tau0=tau0)
 

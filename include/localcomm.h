@@ -215,6 +215,18 @@ int lc_set_xcd_local_exchange(lc_handle* h, int on);
  * on = 0 keeps the separate forward launch and the row-owner backward kernel everywhere. */
 int lc_set_first_layer_fusion(lc_handle* h, int on);
 
+/* Deferred update at tau = 1 (Sec. 2, the k mod tau = 0 branch taken at every iteration: all
+ * workers start each iteration from the same averaged model).  Under the deferred broadcast, in
+ * lc_local_periods(h, 1, n) and the schedule drivers while tau is 1, replica i's model after its
+ * step is x_bar - lr * v_i with v_i the momentum row the step has just written.  The backward
+ * kernels then leave the rows of X unwritten, and the averaging step reads the rows of V and
+ * forms each replica's weights on the fly (same expression, same rounding) before it adds them
+ * up in double: 12 instead of 16 bytes per parameter, replica and iteration, bit-identical
+ * results.  Applies to LC_KIND_MLP models on the launch-per-layer path whose last layer has more
+ * than 128 inputs, not while block momentum is on, and not to lc_local_steps() + lc_average()
+ * called one by one (the library cannot know that an averaging step follows).  Default on. */
+int lc_set_deferred_update(lc_handle* h, int on);
+
 /* 1 if lc_local_steps() of this (attached) handle takes the resident step kernel, else 0. */
 int lc_resident_active(const lc_handle* h);
 

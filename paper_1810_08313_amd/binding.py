@@ -285,6 +285,9 @@ class LocalSGD:
     def set_xcd_local_exchange(self, on: bool) -> None:
         self._check(self._L.lc_set_xcd_local_exchange(self._h, int(bool(on))), "lc_set_xcd_local_exchange")
 
+    def set_deferred_update(self, on: bool) -> None:
+        self._check(self._L.lc_set_deferred_update(self._h, int(bool(on))), "lc_set_deferred_update")
+
     def set_first_layer_fusion(self, on: bool) -> None:
         self._check(self._L.lc_set_first_layer_fusion(self._h, int(bool(on))), "lc_set_first_layer_fusion")
 

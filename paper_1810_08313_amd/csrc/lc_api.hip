@@ -237,6 +237,8 @@ int run_periods(lc_handle* h, int tau, int n_periods, bool average) {
     const bool mlp = h->md.kind == LC_KIND_MLP;
     const int slots = mlp ? h->train.slots : kGatherSlots;
     const bool resident = mlp && h->res_on && h->res_a1x;
+    const bool defer_ok = mlp && !resident && average && tau == 1 && h->defer_x_on && h->lazy_enabled &&
+                          !h->bm_on && !head_is_fused(h);
     int64_t left = static_cast<int64_t>(tau) * n_periods;
     int pos = 0;   // steps of the current period already taken
     while (left > 0) {
@@ -255,17 +257,25 @@ int run_periods(lc_handle* h, int tau, int n_periods, bool average) {
                 h->lazy_rows = false;
                 h->res_used = true;
             } else {
+                // tau = 1 while a broadcast is pending: every replica starts from xbar, so the
+                // iteration writes V only and the averaging step forms xbar - lr V_i itself
+                const bool defer = defer_ok && h->lazy_rows;
+                h->defer_x = defer;
                 for (int u = 0; u < in_period; ++u, ++t) {
                     h->train.cur_slot = t;
                     const int r = one_local_step(h, u + 1 < in_period);
-                    if (r != LC_OK) return r;
+                    if (r != LC_OK) {
+                        h->defer_x = false;
+                        return r;
+                    }
                 }
             }
             pos += in_period;
             if (pos == tau) {
                 pos = 0;
                 if (average) {
-                    const int r = lc_average(h);
+                    const int r = lc_average(h);   // (reads V instead of X while defer_x is set)
+                    h->defer_x = false;
                     if (r != LC_OK) return r;
                 }
             }
@@ -350,6 +360,8 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
         if (mb >= 1 && mb <= 1024) h->avg_chunk_floats = static_cast<int64_t>(mb) * 256 * 1024;
     }
     if (const char* e = getenv("LC_AVG_TWO_PHASE")) h->avg_two_phase = atoi(e) != 0;
+    h->share_w_on = true;
+    if (const char* e = getenv("LC_SHARED_W_ORDER")) h->share_w_on = atoi(e) != 0;
     h->X = h->V = nullptr;
     h->G = h->qa = h->qc = nullptr;
     h->data = nullptr;
@@ -377,6 +389,8 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     h->bm_beta = 0.f;
     h->v_cleared = false;
     h->lazy_enabled = h->lazy_rows = h->lazy_enabled_step = false;
+    h->defer_x_on = true;
+    h->defer_x = false;
     h->loss_parts_train = h->loss_parts_eval = 1;
     (void)carve(h, nullptr);
     *out = h;
@@ -511,6 +525,12 @@ int lc_set_xcd_local_exchange(lc_handle* h, int on) {
 int lc_set_first_layer_fusion(lc_handle* h, int on) {
     if (!h) return LC_ERR_ARG;
     h->fl_on = on != 0;
+    return LC_OK;
+}
+
+int lc_set_deferred_update(lc_handle* h, int on) {
+    if (!h) return LC_ERR_ARG;
+    h->defer_x_on = on != 0;
     return LC_OK;
 }
 

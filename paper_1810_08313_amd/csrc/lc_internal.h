@@ -85,6 +85,12 @@ struct lc_handle {
     bool lazy_enabled, lazy_rows;
     int loss_parts_train, loss_parts_eval;   // how many of the kLossParts slots the last launch wrote
     bool lazy_enabled_step;   // set only while lc_average runs its reduce-only form
+    // deferred update (tau = 1 under the deferred broadcast): every replica starts the iteration
+    // from xbar, so its new weights are xbar - lr V_i; the backward kernels write V only and the
+    // averaging step forms the weights from V on the fly.  defer_x is set only while run_periods
+    // queues such an iteration and its averaging step.
+    bool defer_x_on, defer_x;
+    bool share_w_on;          // block order of the steps that read one model for all replicas (see FwdArgs)
     // resident local steps (small two-layer models): exchange buffer, barrier counters, switches
     float* res_a1x;         // [2 parities][m][dp1/16][Bp][16] exchange buffer of the resident kernel, null when the shape does not qualify
     unsigned* res_ctr;      // [0..63] arrival counters per replica, [64] error flag, [65] all-replica counter, [128..383] placement probe

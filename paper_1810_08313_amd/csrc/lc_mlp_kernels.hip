@@ -192,6 +192,10 @@ struct FwdArgs {
     float* loss;            // [G]
     int eval;               // 1: loss[g] = sum over valid samples; 0: mean over B
     const void* a_in_fm;    // [G][dp_in][Bp] of OT: the same activations feature-major (AFM instances)
+    int n_groups;           // G
+    int shared_w;           // every group reads the same weights from memory (x_stride 0, training step
+                            // right after an averaging step): neighbouring blocks take the same tile of W
+                            // for different replicas, so that it crosses HBM once per XCD, not once per replica
 };
 
 // One block = one replica x 64 output columns x MT batch tiles of 16 rows; its
@@ -223,8 +227,8 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
     const int64_t logical = xcd_logical_block(a.total_blocks);
     if (logical < 0) return;
     const int per_group = a.n_chunks * a.m_split;
-    const int g = static_cast<int>(logical / per_group);
-    const int rem = static_cast<int>(logical % per_group);
+    const int g = a.shared_w ? static_cast<int>(logical % a.n_groups) : static_cast<int>(logical / per_group);
+    const int rem = a.shared_w ? static_cast<int>(logical / a.n_groups) : static_cast<int>(logical % per_group);
     const int c0 = (rem / a.m_split) * kColChunk;
     const int row0 = (rem % a.m_split) * MT * 16;   // first batch row of this block
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -586,6 +590,11 @@ struct BwdArgs {
     int stream;          // non-temporal weight loads and stores
     int n_row_blocks;    // row blocks per group (64 rows each)
     int col_split;       // workgroups sharing one row block's columns (1 when dA is needed)
+    int n_groups;        // G
+    int shared_w;        // all replicas read the same weights (xr_stride 0): neighbouring blocks take the
+                         // same rows of W for different replicas (see FwdArgs)
+    int skip_x;          // V is updated, X is left unwritten: the averaging step that follows forms
+                         // every replica's new weights from Xr and V itself (tau = 1, deferred update)
     int64_t total_blocks;
 };
 
@@ -618,8 +627,8 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
     const int64_t logical = xcd_logical_block(a.total_blocks);
     if (logical < 0) return;
     const int per_group = a.n_row_blocks * a.col_split;
-    const int g = static_cast<int>(logical / per_group);
-    const int rem = static_cast<int>(logical % per_group);
+    const int g = a.shared_w ? static_cast<int>(logical % a.n_groups) : static_cast<int>(logical / per_group);
+    const int rem = a.shared_w ? static_cast<int>(logical / a.n_groups) : static_cast<int>(logical % per_group);
     const int rb = rem / a.col_split, cs = rem % a.col_split;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 15, q = lane >> 4;
@@ -686,7 +695,11 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
                 // rows past d_in read the last row instead (no branch between the loads); their
                 // weights are zeroed when used and they are never stored
                 const int rr = row < a.d_in ? row : a.d_in - 1;
-                ww[r] = load_wm<WM>(Wr + static_cast<int64_t>(rr) * a.d_out, c0 + 4 * j, a.d_out, vec);
+                // (weights that all replicas share are wanted in the L2 by the neighbouring blocks)
+                if (WM == kWVectorStream && a.shared_w)
+                    ww[r] = load_wm<kWVector>(Wr + static_cast<int64_t>(rr) * a.d_out, c0 + 4 * j, a.d_out, vec);
+                else
+                    ww[r] = load_wm<WM>(Wr + static_cast<int64_t>(rr) * a.d_out, c0 + 4 * j, a.d_out, vec);
                 vv[r] = load_wm<WM>(Vw + static_cast<int64_t>(rr) * a.d_out, c0 + 4 * j, a.d_out, vec);
             }
         }
@@ -745,7 +758,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
             }
             const float vb = a.beta * v0 + (sb + a.wd * x);
             *bv = vb;
-            *bx = x - a.lr * vb;
+            if (!a.skip_x) *bx = x - a.lr * vb;
         }
         // dW tile: sum over the batch of A^T[k][b] dZ^T[c][b]
         f32x4 acc[4];
@@ -783,7 +796,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
             w[r].w -= a.lr * v[r].w;
             if (row < a.d_in) {
                 store_wm<WM>(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, v[r]);
-                store_wm<WM>(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, w[r]);
+                if (!a.skip_x) store_wm<WM>(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, w[r]);
             }
         }
         if (need_da) {
@@ -1216,6 +1229,8 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     a.dz_fm = eval ? nullptr : S.dz_fm[h->L];
     a.loss = S.loss + static_cast<int64_t>(loss_offset) * kLossParts;
     a.eval = eval ? 1 : 0;
+    a.n_groups = S.G;
+    a.shared_w = (!eval && h->lazy_rows && h->share_w_on) ? 1 : 0;
     // batch tiles per block: all of them, unless that leaves most of the chip idle
     int mt = mt_for(S.Bp);
     a.m_split = 1;
@@ -1346,6 +1361,9 @@ hipError_t launch_backward(lc_handle* h, int l) {
     a.stream = h->stream_weights ? 1 : 0;
     a.n_row_blocks = g.dp_in / 64;
     a.col_split = 1;
+    a.skip_x = h->defer_x ? 1 : 0;
+    a.n_groups = S.G;
+    a.shared_w = (h->lazy_rows && h->share_w_on) ? 1 : 0;
     if (l == 1) {
         // no dA: the columns can be shared out, to fill the chip and to keep the walk of a
         // workgroup short (measured: walks of 2-4 trips stream faster than long ones, a single

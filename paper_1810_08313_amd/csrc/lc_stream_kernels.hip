@@ -46,14 +46,30 @@ __device__ __forceinline__ float4 apply_block_momentum(const BlockMomentum& bm, 
     return xs;
 }
 
+// Deferred update (tau = 1 right after an averaging step): all replicas started the iteration from
+// the same model xb, the backward kernels wrote only the momentum rows V, and the rows handed to
+// the averaging kernels are those V: replica i's weights are formed here, with the expression and
+// the rounding of the update in the backward kernels (one fused multiply-add), and never stored.
+struct DeferredUpdate {
+    const float* xb;   // null: the rows are the weights themselves
+    float lr;
+};
+
+__device__ __forceinline__ float4 weights_from_momentum(const float4& xb, const float4& v, float lr) {
+    return make_float4(__builtin_fmaf(-lr, v.x, xb.x), __builtin_fmaf(-lr, v.y, xb.y),
+                       __builtin_fmaf(-lr, v.z, xb.z), __builtin_fmaf(-lr, v.w, xb.w));
+}
+
 // x_bar = (1/m) sum_i x^(i), written to every row of out_rows (in place when
 // out_rows == X) and/or to the single vector out_single.  The sum is carried in
 // double: adding m floats in double is exact for any realistic spread of
 // magnitudes, so the result is the correctly rounded mean whatever the order.
-__global__ __launch_bounds__(kThreads) void average_kernel(const float* __restrict__ X, float* out_rows,
-                                                           float* out_single, int m, int64_t Ps, BlockMomentum bm) {
+__global__ __launch_bounds__(kThreads) void average_kernel(const float* X, float* out_rows, float* out_single,
+                                                           int m, int64_t Ps, BlockMomentum bm, DeferredUpdate du) {
     const int64_t col = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
     if (col >= Ps) return;
+    float4 xb = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (du.xb) xb = *reinterpret_cast<const float4*>(du.xb + col);
     double s0 = 0, s1 = 0, s2 = 0, s3 = 0;
     for (int i0 = 0; i0 < m; i0 += kRowBatch) {
         float4 r[kRowBatch];
@@ -63,6 +79,7 @@ __global__ __launch_bounds__(kThreads) void average_kernel(const float* __restri
 #pragma unroll
         for (int u = 0; u < kRowBatch; ++u)
             if (i0 + u < m) {
+                if (du.xb) r[u] = weights_from_momentum(xb, r[u], du.lr);
                 s0 += static_cast<double>(r[u].x);
                 s1 += static_cast<double>(r[u].y);
                 s2 += static_cast<double>(r[u].z);
@@ -89,12 +106,21 @@ __global__ __launch_bounds__(kThreads) void average_kernel(const float* __restri
 //                   the other; consecutive blocks write consecutive addresses
 constexpr int kReduceCols = 8;   // float4 columns per thread in reduce_chunk
 
+template <bool DU>
 __global__ __launch_bounds__(kThreads) void reduce_chunk_kernel(const float* X, float* dst, int m, int64_t Ps,
-                                                                int64_t c_lo, int64_t c_hi, BlockMomentum bm) {
+                                                                int64_t c_lo, int64_t c_hi, BlockMomentum bm,
+                                                                DeferredUpdate du) {
     const int64_t base = c_lo / 4 + static_cast<int64_t>(blockIdx.x) * kThreads * kReduceCols;
     double s[kReduceCols][4];
+    float4 xb[DU ? kReduceCols : 1];
 #pragma unroll
-    for (int u = 0; u < kReduceCols; ++u) s[u][0] = s[u][1] = s[u][2] = s[u][3] = 0.0;
+    for (int u = 0; u < kReduceCols; ++u) {
+        s[u][0] = s[u][1] = s[u][2] = s[u][3] = 0.0;
+        if constexpr (DU) {
+            const int64_t c = (base + u * kThreads + threadIdx.x) * 4;
+            xb[u] = c < c_hi ? *reinterpret_cast<const float4*>(du.xb + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
     for (int i = 0; i < m; ++i) {
         float4 r[kReduceCols];
 #pragma unroll
@@ -104,6 +130,7 @@ __global__ __launch_bounds__(kThreads) void reduce_chunk_kernel(const float* X, 
         }
 #pragma unroll
         for (int u = 0; u < kReduceCols; ++u) {
+            if constexpr (DU) r[u] = weights_from_momentum(xb[u], r[u], du.lr);
             s[u][0] += static_cast<double>(r[u].x);
             s[u][1] += static_cast<double>(r[u].y);
             s[u][2] += static_cast<double>(r[u].z);
@@ -239,7 +266,12 @@ hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* 
     // a state larger than the caches: chunked reduce (into row 0, or into xbar when the broadcast
     // is deferred), then row-by-row broadcast
     const bool big = static_cast<double>(h->m) * static_cast<double>(h->Ps) * 4.0 > 512.0 * 1024 * 1024;
-    if (step && X == h->X && h->m >= 2 && h->avg_two_phase && big) {
+    // deferred update: the rows are the momentum rows, the common starting model is xbar (which
+    // each thread reads before it writes the new mean of the same columns there)
+    const DeferredUpdate du{h->defer_x ? h->xbar : nullptr, h->md.lr};
+    if (h->defer_x) X = h->V;
+    const bool own_rows = X == h->X || h->defer_x;
+    if (step && own_rows && h->m >= 2 && h->avg_two_phase && big) {
         timing_start(h, kTimeAvg);
         const int64_t chunk = h->avg_chunk_floats;
         float* dst = out_rows ? h->X : out_single;
@@ -247,8 +279,12 @@ hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* 
             const int64_t hi = lo + chunk < h->Ps ? lo + chunk : h->Ps;
             const int64_t nblk = ((hi - lo) / 4 + kThreads - 1) / kThreads;
             const int64_t nred = (nblk + kReduceCols - 1) / kReduceCols;
-            hipLaunchKernelGGL(reduce_chunk_kernel, dim3(static_cast<unsigned>(nred)), dim3(kThreads), 0, h->stream,
-                               h->X, dst, h->m, h->Ps, lo, hi, bm);
+            if (du.xb)
+                hipLaunchKernelGGL(reduce_chunk_kernel<true>, dim3(static_cast<unsigned>(nred)), dim3(kThreads), 0,
+                                   h->stream, X, dst, h->m, h->Ps, lo, hi, bm, du);
+            else
+                hipLaunchKernelGGL(reduce_chunk_kernel<false>, dim3(static_cast<unsigned>(nred)), dim3(kThreads), 0,
+                                   h->stream, X, dst, h->m, h->Ps, lo, hi, bm, du);
             if (out_rows)
                 hipLaunchKernelGGL(broadcast_chunk_kernel, dim3(static_cast<unsigned>(nblk * (h->m - 1))),
                                    dim3(kThreads), 0, h->stream, h->X, h->X, 1, h->Ps, lo, hi, nblk);
@@ -258,7 +294,7 @@ hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* 
     }
     if (step) timing_start(h, kTimeAvg);
     hipLaunchKernelGGL(average_kernel, dim3(blocks_for(h->Ps / 4)), dim3(kThreads), 0, h->stream, X, out_rows,
-                       out_single, h->m, h->Ps, bm);
+                       out_single, h->m, h->Ps, bm, du);
     if (step) timing_stop(h, kTimeAvg);
     return hipGetLastError();
 }

@@ -76,6 +76,7 @@ def test_init_rejects_bad_arguments(pkg):
     # switches of the resident step kernel: argument checks need no device
     assert L.lc_set_xcd_local_exchange(h, 0) == 0 and L.lc_set_xcd_local_exchange(None, 1) == -1
     assert L.lc_set_first_layer_fusion(h, 0) == 0 and L.lc_set_first_layer_fusion(None, 1) == -1
+    assert L.lc_set_deferred_update(h, 0) == 0 and L.lc_set_deferred_update(None, 1) == -1
     assert L.lc_set_resident(h, 0) == 0 and L.lc_set_resident(h, 1) == 0 and L.lc_set_resident(None, 1) == -1
     assert L.lc_set_barrier_polls(h, -1) == -1 and L.lc_set_barrier_polls(h, 0) == 0
     assert L.lc_resident_active(h) == -3 and L.lc_resident_active(None) == -1

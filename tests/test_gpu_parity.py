@@ -845,6 +845,81 @@ def test_lazy_broadcast_is_bit_identical_to_eager(pkg, orc, bf16):
     lazy.close()
 
 
+DEFER_CASES = [
+    # last layer with more than 128 inputs (its backward pass is the row-owner kernel), ragged everywhere
+    ([130, 70, 200, 7], 4, 48, False),
+    ([130, 70, 200, 7], 4, 48, True),
+    # unaligned weight rows, resident kernel switched off
+    ([67, 129, 10], 3, 33, False),
+]
+
+
+@pytest.mark.parametrize("dims,m,B,bf16", DEFER_CASES)
+def test_deferred_update_at_tau_1_is_bit_identical(pkg, orc, dims, m, B, bf16):
+    """tau = 1 under the deferred broadcast: the backward kernels write V only and the
+    averaging step forms x_bar - lr v_i itself.  Same bits as with the rows written."""
+    _say(f"deferred update dims={dims} bf16={bf16}")
+    ref, plain = _problem(pkg, orc, dims, m, B, wd=5e-4, bf16=bf16, resident=False)
+    _, defer = _problem(pkg, orc, dims, m, B, wd=5e-4, bf16=bf16, resident=False)
+    for r in (plain, defer):
+        r.set_lazy_broadcast(True)
+    plain.set_deferred_update(False)
+    for r in (plain, defer):
+        r.run(6, 1)
+    # the switch did something: from the second iteration on the rows of X stay unwritten
+    assert not bool((plain.X == defer.X).all().item())
+    assert plain.loss() == defer.loss()
+    for r in (plain, defer):
+        r.run(6, 3)              # longer periods in between write the rows again
+        r.local_periods(1, 4)    # ... and the other driver
+        r.set_lr(0.03)
+        r.run(3, 1)
+    Xp, Vp, kp = plain.get_state()
+    Xd, Vd, kd = defer.get_state()
+    assert kp == kd == 19
+    assert np.array_equal(Xp.view(np.uint32), Xd.view(np.uint32))
+    assert np.array_equal(Vp.view(np.uint32), Vd.view(np.uint32))
+    for tau, n in ((1, 6), (3, 2), (1, 4)):
+        for _ in range(n):
+            ref.local_steps(tau)
+            ref.average()
+    ref.set_lr(0.03)
+    for _ in range(3):
+        ref.local_steps(1)
+        ref.average()
+    _assert_close(Xd, ref.X, dims, (TOL16 if bf16 else TOL32) * 4, "X")
+    if not bf16:   # (after 19 iterations with bf16 operands a few ReLU gates have gone either way: V, one
+        _assert_close(Vd, ref.V, dims, TOL32 * 4, "V")   # step's worth of gradient, shows that; X does not)
+    plain.close()
+    defer.close()
+
+
+def test_deferred_update_with_chunked_averaging(pkg, orc):
+    """The same on a state above 512 MB, where the averaging step is the chunked reduce kernel:
+    against the run that writes the rows, bit for bit (that run is held to the oracle elsewhere)."""
+    dims, m, B = [8192, 8320, 10], 2, 32
+    _say("deferred update, chunked averaging")
+    data, labels = synth.gaussian_mixture(5, 200, dims[0], dims[-1], mean_sd=1.0)
+    data = synth.bf16_representable(data)
+    x1 = synth.init_params(5, dims)
+    out = []
+    for on in (False, True):
+        md = pkg.make_model(pkg.KIND_MLP, dims, B=B, N=200, E=100, lr=0.05, beta=0.9, wd=1e-4, bf16=True)
+        run = pkg.LocalSGD(m, md, 5, x1, data, labels)
+        run.set_lazy_broadcast(True)
+        run.set_deferred_update(on)
+        run.run(4, 1)
+        loss = run.loss()
+        X, V, k = run.get_state()
+        out.append((loss, X[:, ::97].copy(), V[:, ::97].copy(), X[0, -70000:].copy(), k))
+        run.close()
+        del X, V
+    assert out[0][0] == out[1][0] and out[0][4] == out[1][4] == 4
+    for a, b in zip(out[0][1:4], out[1][1:4]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    assert np.isfinite(out[0][0])
+
+
 # --------------------------------------------------------------- error paths
 
 def test_attach_errors_and_bad_tau(pkg):
