@@ -1199,6 +1199,14 @@ hipError_t launch_gather(lc_handle* h, bool eval, int64_t k_or_base, int n_steps
     return hipGetLastError();
 }
 
+// Replicas that read one model take the same weight tile in neighbouring blocks when the layer is
+// too large for an XCD's L2 to hold until the next replica comes by (measured: +14 % at m = 64 with
+// 16-25 MB layers; a few per cent slower for models that are cache-resident anyway, whose blocks
+// then no longer share their replica's activations).
+bool shared_weight_order(const lc_handle* h, const LayerGeom& g) {
+    return h->share_w_on && h->stream_weights && 4.0 * g.d_in * g.d_out >= 8.0 * 1024 * 1024;
+}
+
 hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     const ActSet& S = eval ? h->eval : h->train;
     const LayerGeom& g = h->layer[l];
@@ -1230,7 +1238,7 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     a.loss = S.loss + static_cast<int64_t>(loss_offset) * kLossParts;
     a.eval = eval ? 1 : 0;
     a.n_groups = S.G;
-    a.shared_w = (!eval && h->lazy_rows && h->share_w_on) ? 1 : 0;
+    a.shared_w = (!eval && h->lazy_rows && shared_weight_order(h, g)) ? 1 : 0;
     // batch tiles per block: all of them, unless that leaves most of the chip idle
     int mt = mt_for(S.Bp);
     a.m_split = 1;
@@ -1363,7 +1371,7 @@ hipError_t launch_backward(lc_handle* h, int l) {
     a.col_split = 1;
     a.skip_x = h->defer_x ? 1 : 0;
     a.n_groups = S.G;
-    a.shared_w = (h->lazy_rows && h->share_w_on) ? 1 : 0;
+    a.shared_w = (h->lazy_rows && shared_weight_order(h, g)) ? 1 : 0;
     if (l == 1) {
         // no dA: the columns can be shared out, to fill the chip and to keep the walk of a
         // workgroup short (measured: walks of 2-4 trips stream faster than long ones, a single
