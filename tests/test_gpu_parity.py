@@ -894,6 +894,29 @@ def test_deferred_update_at_tau_1_is_bit_identical(pkg, orc, dims, m, B, bf16):
     defer.close()
 
 
+@pytest.mark.parametrize("bf16", [True, False])
+def test_shared_model_block_order_against_oracle(pkg, orc, bf16):
+    """A first layer above 8 MB in a state above 256 MB: the steps that read one model for all
+    replicas hand the same weight tile to neighbouring blocks (another block numbering in the
+    forward and backward kernels).  tau = 1, three iterations, against the oracle."""
+    dims, m, B = [2048, 1100, 10], 16, 24
+    _say(f"shared-model block order bf16={bf16}")
+    ref, run = _problem(pkg, orc, dims, m, B, N=300, lr=0.05, wd=1e-4, bf16=bf16, mean_sd=0.03)   # overlapping classes
+    assert not run.resident_active()
+    run.set_lazy_broadcast(True)
+    run.run(3, 1)
+    for _ in range(3):
+        ref.local_steps(1)
+        ref.average()
+    X, V, k = run.get_state()
+    assert k == 3
+    assert bool((X[1:] == X[0:1]).all())
+    _assert_close(X, ref.X, dims, (TOL16 if bf16 else TOL32) * 3, "X")
+    _assert_close(V, ref.V, dims, (TOL16 if bf16 else TOL32) * 3, "V")
+    np.testing.assert_allclose(run.loss(), ref.loss(), rtol=2e-3 if bf16 else 1e-4)
+    run.close()
+
+
 def test_deferred_update_with_chunked_averaging(pkg, orc):
     """The same on a state above 512 MB, where the averaging step is the chunked reduce kernel:
     against the run that writes the rows, bit for bit (that run is held to the oracle elsewhere)."""
