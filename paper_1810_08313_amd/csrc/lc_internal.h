@@ -91,6 +91,7 @@ struct lc_handle {
     // queues such an iteration and its averaging step.
     bool defer_x_on, defer_x;
     bool share_w_on;          // block order of the steps that read one model for all replicas (see FwdArgs)
+    int share_w_set;          // ... replicas per set
     // resident local steps (small two-layer models): exchange buffer, barrier counters, switches
     float* res_a1x;         // [2 parities][m][dp1/16][Bp][16] exchange buffer of the resident kernel, null when the shape does not qualify
     unsigned* res_ctr;      // [0..63] arrival counters per replica, [64] error flag, [65] all-replica counter, [128..383] placement probe

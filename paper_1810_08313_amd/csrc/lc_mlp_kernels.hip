@@ -167,6 +167,22 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
     }
 }
 
+// Logical block -> (replica g, tile rem of the per_group tiles of a replica).
+//   set == 0  replica-major: a replica's blocks are neighbours and share its activations in the L2
+//   set >= 1  tile-major inside sets of `set` replicas (set divides n_groups): neighbouring blocks
+//             take the same weight tile for different replicas
+__device__ __forceinline__ void shared_order(int64_t logical, int per_group, int set, int& g, int& rem) {
+    if (set > 0) {
+        const int64_t per_set = static_cast<int64_t>(per_group) * set;
+        const int within = static_cast<int>(logical % per_set);
+        g = static_cast<int>(logical / per_set) * set + within % set;
+        rem = within / set;
+    } else {
+        g = static_cast<int>(logical / per_group);
+        rem = static_cast<int>(logical % per_group);
+    }
+}
+
 // -------------------------------------------------------------------- forward
 
 struct FwdArgs {
@@ -192,10 +208,10 @@ struct FwdArgs {
     float* loss;            // [G]
     int eval;               // 1: loss[g] = sum over valid samples; 0: mean over B
     const void* a_in_fm;    // [G][dp_in][Bp] of OT: the same activations feature-major (AFM instances)
-    int n_groups;           // G
-    int shared_w;           // every group reads the same weights from memory (x_stride 0, training step
-                            // right after an averaging step): neighbouring blocks take the same tile of W
-                            // for different replicas, so that it crosses HBM once per XCD, not once per replica
+    int shared_w;           // > 0: every group reads the same weights from memory (x_stride 0, training step
+                            // right after an averaging step) and neighbouring blocks take the same tile of W
+                            // for different replicas, in sets of this many replicas (see shared_order), so
+                            // that the tile crosses HBM once per set instead of once per replica
 };
 
 // One block = one replica x 64 output columns x MT batch tiles of 16 rows; its
@@ -227,8 +243,8 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
     const int64_t logical = xcd_logical_block(a.total_blocks);
     if (logical < 0) return;
     const int per_group = a.n_chunks * a.m_split;
-    const int g = a.shared_w ? static_cast<int>(logical % a.n_groups) : static_cast<int>(logical / per_group);
-    const int rem = a.shared_w ? static_cast<int>(logical / a.n_groups) : static_cast<int>(logical % per_group);
+    int g, rem;
+    shared_order(logical, per_group, a.shared_w, g, rem);
     const int c0 = (rem / a.m_split) * kColChunk;
     const int row0 = (rem % a.m_split) * MT * 16;   // first batch row of this block
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -590,9 +606,8 @@ struct BwdArgs {
     int stream;          // non-temporal weight loads and stores
     int n_row_blocks;    // row blocks per group (64 rows each)
     int col_split;       // workgroups sharing one row block's columns (1 when dA is needed)
-    int n_groups;        // G
-    int shared_w;        // all replicas read the same weights (xr_stride 0): neighbouring blocks take the
-                         // same rows of W for different replicas (see FwdArgs)
+    int shared_w;        // > 0: all replicas read the same weights (xr_stride 0) and neighbouring blocks take
+                         // the same rows of W for different replicas, in sets of this many (see FwdArgs)
     int skip_x;          // V is updated, X is left unwritten: the averaging step that follows forms
                          // every replica's new weights from Xr and V itself (tau = 1, deferred update)
     int64_t total_blocks;
@@ -627,8 +642,8 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
     const int64_t logical = xcd_logical_block(a.total_blocks);
     if (logical < 0) return;
     const int per_group = a.n_row_blocks * a.col_split;
-    const int g = a.shared_w ? static_cast<int>(logical % a.n_groups) : static_cast<int>(logical / per_group);
-    const int rem = a.shared_w ? static_cast<int>(logical / a.n_groups) : static_cast<int>(logical % per_group);
+    int g, rem;
+    shared_order(logical, per_group, a.shared_w, g, rem);
     const int rb = rem / a.col_split, cs = rem % a.col_split;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 15, q = lane >> 4;
@@ -1207,6 +1222,13 @@ bool shared_weight_order(const lc_handle* h, const LayerGeom& g) {
     return h->share_w_on && h->stream_weights && 4.0 * g.d_in * g.d_out >= 8.0 * 1024 * 1024;
 }
 
+// Replicas per set: 8 (one set per XCD at m = 64; sets of 4 to 32 measure the same, all replicas in
+// one set 3 % less: a set's activations and deltas then no longer fit the L2 beside the tiles).
+int shared_set(const lc_handle* h, int G) {
+    const int set = h->share_w_set;
+    return (set >= 1 && set < G && G % set == 0) ? set : G;
+}
+
 hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     const ActSet& S = eval ? h->eval : h->train;
     const LayerGeom& g = h->layer[l];
@@ -1237,8 +1259,7 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     a.dz_fm = eval ? nullptr : S.dz_fm[h->L];
     a.loss = S.loss + static_cast<int64_t>(loss_offset) * kLossParts;
     a.eval = eval ? 1 : 0;
-    a.n_groups = S.G;
-    a.shared_w = (!eval && h->lazy_rows && shared_weight_order(h, g)) ? 1 : 0;
+    a.shared_w = (!eval && h->lazy_rows && shared_weight_order(h, g)) ? shared_set(h, S.G) : 0;
     // batch tiles per block: all of them, unless that leaves most of the chip idle
     int mt = mt_for(S.Bp);
     a.m_split = 1;
@@ -1370,8 +1391,7 @@ hipError_t launch_backward(lc_handle* h, int l) {
     a.n_row_blocks = g.dp_in / 64;
     a.col_split = 1;
     a.skip_x = h->defer_x ? 1 : 0;
-    a.n_groups = S.G;
-    a.shared_w = (h->lazy_rows && shared_weight_order(h, g)) ? 1 : 0;
+    a.shared_w = (h->lazy_rows && shared_weight_order(h, g)) ? shared_set(h, S.G) : 0;
     if (l == 1) {
         // no dA: the columns can be shared out, to fill the chip and to keep the walk of a
         // workgroup short (measured: walks of 2-4 trips stream faster than long ones, a single

@@ -894,13 +894,13 @@ def test_deferred_update_at_tau_1_is_bit_identical(pkg, orc, dims, m, B, bf16):
     defer.close()
 
 
-@pytest.mark.parametrize("bf16", [True, False])
-def test_shared_model_block_order_against_oracle(pkg, orc, bf16):
+@pytest.mark.parametrize("bf16,m", [(True, 16), (False, 16), (False, 12)])   # two sets of 8 replicas; one set of 12
+def test_shared_model_block_order_against_oracle(pkg, orc, bf16, m):
     """A first layer above 8 MB in a state above 256 MB: the steps that read one model for all
     replicas hand the same weight tile to neighbouring blocks (another block numbering in the
     forward and backward kernels).  tau = 1, three iterations, against the oracle."""
-    dims, m, B = [2048, 1100, 10], 16, 24
-    _say(f"shared-model block order bf16={bf16}")
+    dims, B = [2048, 1100, 10], 24
+    _say(f"shared-model block order bf16={bf16} m={m}")
     ref, run = _problem(pkg, orc, dims, m, B, N=300, lr=0.05, wd=1e-4, bf16=bf16, mean_sd=0.03)   # overlapping classes
     assert not run.resident_active()
     run.set_lazy_broadcast(True)
