@@ -34,6 +34,7 @@ struct FirstArgs {
     int64_t x_stride;
     const float* Xr;      // where the weights are read: X, or the one averaged model (stride 0)
     int64_t xr_stride;
+    int shared_w;         // > 0: block order of steps in which all replicas read one model (see shared_order)
     int64_t w_off, b_off;
     int d_in, d_out, dp_in, dp_out;
     int B;
@@ -110,8 +111,9 @@ __global__ __launch_bounds__(256) void first_layer_kernel(FirstArgs a) {
 
     const int64_t logical = xcd_logical_block(a.total_blocks);
     if (logical < 0) return;
-    const int g = static_cast<int>(logical / a.n_chunks);
-    const int c0 = static_cast<int>(logical % a.n_chunks) * kColChunk;
+    int g, chunk;
+    shared_order(logical, a.n_chunks, a.shared_w, g, chunk);
+    const int c0 = chunk * kColChunk;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: step bases live in scalar registers
     const int j = lane & 15, q = lane >> 4;
@@ -152,7 +154,9 @@ __global__ __launch_bounds__(256) void first_layer_kernel(FirstArgs a) {
         const float* vb = Vw + static_cast<int64_t>(k0) * a.d_out;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            x.w[r] = load_wm<WM>(at_byte(wb, woff[r]), 0, a.d_out, true);
+            // (weights that all replicas share are wanted in the L2 by the neighbouring blocks)
+            if (WM == kWVectorStream && a.shared_w) x.w[r] = load_wm<kWVector>(at_byte(wb, woff[r]), 0, a.d_out, true);
+            else x.w[r] = load_wm<WM>(at_byte(wb, woff[r]), 0, a.d_out, true);
             x.v[r] = load_wm<WM>(at_byte(vb, woff[r]), 0, a.d_out, true);
         }
         const OT* ab = AT + static_cast<int64_t>(k0) * Bp;
@@ -358,6 +362,7 @@ hipError_t launch_first_layer(lc_handle* h) {
     a.x_stride = h->Ps;
     a.Xr = h->lazy_rows ? h->xbar : h->X;
     a.xr_stride = h->lazy_rows ? 0 : h->Ps;
+    a.shared_w = (h->lazy_rows && shared_weight_order(h, g)) ? shared_set(h, S.G) : 0;
     a.w_off = g.w_off;
     a.b_off = g.b_off;
     a.d_in = g.d_in;

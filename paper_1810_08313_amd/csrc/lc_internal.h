@@ -134,6 +134,8 @@ hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset);
 hipError_t launch_backward(lc_handle* h, int l);
 bool first_layer_kernel_ok(const lc_handle* h);   // layer 1: backward kernel that also runs the next step's forward
 hipError_t launch_first_layer(lc_handle* h);
+bool shared_weight_order(const lc_handle* h, const LayerGeom& g);   // tile-major block order on steps that read one model
+int shared_set(const lc_handle* h, int G);                          // ... replicas per set
 bool head_is_fused(const lc_handle* h);   // last layer: forward + softmax + backward in one kernel
 hipError_t launch_head(lc_handle* h);
 

@@ -167,22 +167,6 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
     }
 }
 
-// Logical block -> (replica g, tile rem of the per_group tiles of a replica).
-//   set == 0  replica-major: a replica's blocks are neighbours and share its activations in the L2
-//   set >= 1  tile-major inside sets of `set` replicas (set divides n_groups): neighbouring blocks
-//             take the same weight tile for different replicas
-__device__ __forceinline__ void shared_order(int64_t logical, int per_group, int set, int& g, int& rem) {
-    if (set > 0) {
-        const int64_t per_set = static_cast<int64_t>(per_group) * set;
-        const int within = static_cast<int>(logical % per_set);
-        g = static_cast<int>(logical / per_set) * set + within % set;
-        rem = within / set;
-    } else {
-        g = static_cast<int>(logical / per_group);
-        rem = static_cast<int>(logical % per_group);
-    }
-}
-
 // -------------------------------------------------------------------- forward
 
 struct FwdArgs {

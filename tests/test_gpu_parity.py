@@ -894,22 +894,26 @@ def test_deferred_update_at_tau_1_is_bit_identical(pkg, orc, dims, m, B, bf16):
     defer.close()
 
 
-@pytest.mark.parametrize("bf16,m", [(True, 16), (False, 16), (False, 12)])   # two sets of 8 replicas; one set of 12
-def test_shared_model_block_order_against_oracle(pkg, orc, bf16, m):
+@pytest.mark.parametrize("bf16,m,d1,tau,K", [
+    (True, 16, 1100, 1, 3), (False, 16, 1100, 1, 3),   # two sets of 8 replicas
+    (False, 12, 1100, 1, 3),                           # one set of 12
+    (True, 16, 1152, 2, 4),                            # first layer by the column-owner kernel, first step of a period
+])
+def test_shared_model_block_order_against_oracle(pkg, orc, bf16, m, d1, tau, K):
     """A first layer above 8 MB in a state above 256 MB: the steps that read one model for all
     replicas hand the same weight tile to neighbouring blocks (another block numbering in the
-    forward and backward kernels).  tau = 1, three iterations, against the oracle."""
-    dims, B = [2048, 1100, 10], 24
-    _say(f"shared-model block order bf16={bf16} m={m}")
+    forward, backward and first-layer kernels).  A few periods against the oracle."""
+    dims, B = [2048, d1, 10], 24
+    _say(f"shared-model block order bf16={bf16} m={m} d1={d1} tau={tau}")
     ref, run = _problem(pkg, orc, dims, m, B, N=300, lr=0.05, wd=1e-4, bf16=bf16, mean_sd=0.03)   # overlapping classes
     assert not run.resident_active()
     run.set_lazy_broadcast(True)
-    run.run(3, 1)
-    for _ in range(3):
-        ref.local_steps(1)
+    run.run(K, tau)
+    for _ in range(K // tau):
+        ref.local_steps(tau)
         ref.average()
     X, V, k = run.get_state()
-    assert k == 3
+    assert k == K
     assert bool((X[1:] == X[0:1]).all())
     _assert_close(X, ref.X, dims, (TOL16 if bf16 else TOL32) * 3, "X")
     _assert_close(V, ref.V, dims, (TOL16 if bf16 else TOL32) * 3, "V")
