@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblocalcomm.so")
-SOURCES = ["lc_api.hip", "lc_stream_kernels.hip", "lc_mlp_kernels.hip", "lc_resident_kernels.hip", "lc_first_layer_kernels.hip"]
+SOURCES = ["lc_api.hip", "lc_stream_kernels.hip", "lc_mlp_kernels.hip", "lc_resident_kernels.hip", "lc_first_layer_kernels.hip",
+           "lc_sync_kernels.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -192,8 +192,14 @@ int one_local_step(lc_handle* h, bool next_gathered) {
             if (!forward_fuses_softmax(h)) LC_HIP(h, launch_softmax(h, false, 0));
         }
         for (int l = head_is_fused(h) ? h->L - 1 : h->L; l >= 1; --l) {
-            if (l == 1 && first_fused) LC_HIP(h, launch_first_layer(h));
-            else LC_HIP(h, launch_backward(h, l));
+            if (l == 1 && first_fused) {
+                LC_HIP(h, launch_first_layer(h));
+            } else if (l == 1 && h->defer_x && sync_first_layer_ok(h)) {
+                LC_HIP(h, launch_sync_first_layer(h));   // ... and the layer's part of the averaging step
+                h->sync1_done = true;
+            } else {
+                LC_HIP(h, launch_backward(h, l));
+            }
         }
         h->a1_ready = first_fused;
     }
@@ -265,7 +271,7 @@ int run_periods(lc_handle* h, int tau, int n_periods, bool average) {
                     h->train.cur_slot = t;
                     const int r = one_local_step(h, u + 1 < in_period);
                     if (r != LC_OK) {
-                        h->defer_x = false;
+                        h->defer_x = h->sync1_done = false;
                         return r;
                     }
                 }
@@ -276,6 +282,7 @@ int run_periods(lc_handle* h, int tau, int n_periods, bool average) {
                 if (average) {
                     const int r = lc_average(h);   // (reads V instead of X while defer_x is set)
                     h->defer_x = false;
+                    h->sync1_done = false;
                     if (r != LC_OK) return r;
                 }
             }
@@ -395,6 +402,9 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     h->lazy_enabled = h->lazy_rows = h->lazy_enabled_step = false;
     h->defer_x_on = true;
     h->defer_x = false;
+    h->sync1_on = true;
+    if (const char* e = getenv("LC_SYNC_FIRST_LAYER")) h->sync1_on = atoi(e) != 0;   // tuning knob for measurement runs
+    h->sync1_done = false;
     h->loss_parts_train = h->loss_parts_eval = 1;
     (void)carve(h, nullptr);
     *out = h;

@@ -755,9 +755,9 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) sb += to_f32(f.v[e]);
             }
-            const float vb = a.beta * v0 + (sb + a.wd * x);
+            const float vb = momentum_update(a.beta, v0, sb, a.wd, x);
             *bv = vb;
-            if (!a.skip_x) *bx = x - a.lr * vb;
+            if (!a.skip_x) *bx = weight_update(x, a.lr, vb);
         }
         // dW tile: sum over the batch of A^T[k][b] dZ^T[c][b]
         f32x4 acc[4];
@@ -785,14 +785,14 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         for (int r = 0; r < 4; ++r) {
             const int row = k0 + 4 * q + r;
             const float4 gr = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
-            v[r].x = a.beta * v[r].x + (gr.x + a.wd * w[r].x);
-            v[r].y = a.beta * v[r].y + (gr.y + a.wd * w[r].y);
-            v[r].z = a.beta * v[r].z + (gr.z + a.wd * w[r].z);
-            v[r].w = a.beta * v[r].w + (gr.w + a.wd * w[r].w);
-            w[r].x -= a.lr * v[r].x;
-            w[r].y -= a.lr * v[r].y;
-            w[r].z -= a.lr * v[r].z;
-            w[r].w -= a.lr * v[r].w;
+            v[r].x = momentum_update(a.beta, v[r].x, gr.x, a.wd, w[r].x);
+            v[r].y = momentum_update(a.beta, v[r].y, gr.y, a.wd, w[r].y);
+            v[r].z = momentum_update(a.beta, v[r].z, gr.z, a.wd, w[r].z);
+            v[r].w = momentum_update(a.beta, v[r].w, gr.w, a.wd, w[r].w);
+            w[r].x = weight_update(w[r].x, a.lr, v[r].x);
+            w[r].y = weight_update(w[r].y, a.lr, v[r].y);
+            w[r].z = weight_update(w[r].z, a.lr, v[r].z);
+            w[r].w = weight_update(w[r].w, a.lr, v[r].w);
             if (row < a.d_in) {
                 store_wm<WM>(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, v[r]);
                 if (!a.skip_x) store_wm<WM>(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, w[r]);

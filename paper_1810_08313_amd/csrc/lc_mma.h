@@ -166,6 +166,15 @@ __device__ __forceinline__ void store_wm(float* row, int c, int d_out, bool vec,
     }
 }
 
+// The momentum-SGD update with its roundings spelled out: v' = fma(beta, v, fma(wd, w, g)) and
+// w' = fma(-lr, v', w).  Kernels whose results are compared bit for bit (the backward kernel, the
+// tau = 1 first-layer kernel, the averaging kernels that form x_bar - lr v themselves) must not
+// leave the choice of which products are fused to the compiler's contraction pass.
+__device__ __forceinline__ float momentum_update(float beta, float v, float g, float wd, float w) {
+    return __builtin_fmaf(beta, v, __builtin_fmaf(wd, w, g));
+}
+__device__ __forceinline__ float weight_update(float w, float lr, float v) { return __builtin_fmaf(-lr, v, w); }
+
 __device__ __forceinline__ void wave_sync_lds() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();

@@ -65,8 +65,9 @@ __device__ __forceinline__ float4 weights_from_momentum(const float4& xb, const 
 // double: adding m floats in double is exact for any realistic spread of
 // magnitudes, so the result is the correctly rounded mean whatever the order.
 __global__ __launch_bounds__(kThreads) void average_kernel(const float* X, float* out_rows, float* out_single,
-                                                           int m, int64_t Ps, BlockMomentum bm, DeferredUpdate du) {
-    const int64_t col = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
+                                                           int m, int64_t Ps, BlockMomentum bm, DeferredUpdate du,
+                                                           int64_t col0) {
+    const int64_t col = col0 + (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
     if (col >= Ps) return;
     float4 xb = make_float4(0.f, 0.f, 0.f, 0.f);
     if (du.xb) xb = *reinterpret_cast<const float4*>(du.xb + col);
@@ -271,11 +272,13 @@ hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* 
     const DeferredUpdate du{h->defer_x ? h->xbar : nullptr, h->md.lr};
     if (h->defer_x) X = h->V;
     const bool own_rows = X == h->X || h->defer_x;
+    // columns that the first layer's tau = 1 kernel has averaged already (layer 1 is stored first)
+    const int64_t col0 = (h->defer_x && h->sync1_done) ? static_cast<int64_t>(h->layer[1].d_in) * h->layer[1].d_out : 0;
     if (step && own_rows && h->m >= 2 && h->avg_two_phase && big) {
         timing_start(h, kTimeAvg);
         const int64_t chunk = h->avg_chunk_floats;
         float* dst = out_rows ? h->X : out_single;
-        for (int64_t lo = 0; lo < h->Ps; lo += chunk) {
+        for (int64_t lo = col0; lo < h->Ps; lo += chunk) {
             const int64_t hi = lo + chunk < h->Ps ? lo + chunk : h->Ps;
             const int64_t nblk = ((hi - lo) / 4 + kThreads - 1) / kThreads;
             const int64_t nred = (nblk + kReduceCols - 1) / kReduceCols;
@@ -293,8 +296,8 @@ hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* 
         return hipGetLastError();
     }
     if (step) timing_start(h, kTimeAvg);
-    hipLaunchKernelGGL(average_kernel, dim3(blocks_for(h->Ps / 4)), dim3(kThreads), 0, h->stream, X, out_rows,
-                       out_single, h->m, h->Ps, bm, du);
+    hipLaunchKernelGGL(average_kernel, dim3(blocks_for((h->Ps - col0) / 4)), dim3(kThreads), 0, h->stream, X,
+                       out_rows, out_single, h->m, h->Ps, bm, du, col0);
     if (step) timing_stop(h, kTimeAvg);
     return hipGetLastError();
 }

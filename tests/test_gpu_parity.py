@@ -898,6 +898,7 @@ def test_deferred_update_at_tau_1_is_bit_identical(pkg, orc, dims, m, B, bf16):
     (True, 16, 1100, 1, 3), (False, 16, 1100, 1, 3),   # two sets of 8 replicas
     (False, 12, 1100, 1, 3),                           # one set of 12
     (True, 16, 1152, 2, 4),                            # first layer by the column-owner kernel, first step of a period
+    (True, 16, 1152, 1, 3), (False, 12, 1152, 1, 3),   # first layer by the tile-owner kernel that also averages it
 ])
 def test_shared_model_block_order_against_oracle(pkg, orc, bf16, m, d1, tau, K):
     """A first layer above 8 MB in a state above 256 MB: the steps that read one model for all
