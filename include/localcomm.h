@@ -222,7 +222,9 @@ int lc_set_first_layer_fusion(lc_handle* h, int on);
  * kernels then leave the rows of X unwritten, and the averaging step reads the rows of V and
  * forms each replica's weights on the fly (same expression, same rounding) before it adds them
  * up in double: 12 instead of 16 bytes per parameter, replica and iteration, bit-identical
- * results.  Applies to LC_KIND_MLP models on the launch-per-layer path whose last layer has more
+ * results.  A first layer of 8 MB or more with rows of a multiple of 64 columns goes further: one
+ * kernel owns its weights by tile, walks over the replicas, updates their momentum tiles and
+ * writes the layer's new average itself (8 bytes per parameter and replica).  Applies to LC_KIND_MLP models on the launch-per-layer path whose last layer has more
  * than 128 inputs, not while block momentum is on, and not to lc_local_steps() + lc_average()
  * called one by one (the library cannot know that an averaging step follows).  Default on. */
 int lc_set_deferred_update(lc_handle* h, int on);
