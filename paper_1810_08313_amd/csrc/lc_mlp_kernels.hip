@@ -1010,9 +1010,9 @@ __global__ __launch_bounds__(512) void head_kernel(HeadArgs a) {
         float* bx = a.X + g * a.x_stride + a.b_off + tid;
         float* bv = a.V + g * a.x_stride + a.b_off + tid;
         const float x = a.Xr[g * a.xr_stride + a.b_off + tid];
-        const float vb = a.beta * *bv + (sb + a.wd * x);
+        const float vb = momentum_update(a.beta, *bv, sb, a.wd, x);
         *bv = vb;
-        *bx = x - a.lr * vb;
+        *bx = weight_update(x, a.lr, vb);
     }
     // ... then the weight rows, 16 per wavefront and trip
     OT* pbm = need_da ? static_cast<OT*>(a.dzp_bm) + static_cast<int64_t>(g) * Bp * a.dp_in : nullptr;
@@ -1047,14 +1047,14 @@ __global__ __launch_bounds__(512) void head_kernel(HeadArgs a) {
         for (int r = 0; r < 4; ++r) {
             const int row = k0 + 4 * q + r;
             const float4 gr = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
-            v[r].x = a.beta * v[r].x + (gr.x + a.wd * w[r].x);
-            v[r].y = a.beta * v[r].y + (gr.y + a.wd * w[r].y);
-            v[r].z = a.beta * v[r].z + (gr.z + a.wd * w[r].z);
-            v[r].w = a.beta * v[r].w + (gr.w + a.wd * w[r].w);
-            w[r].x -= a.lr * v[r].x;
-            w[r].y -= a.lr * v[r].y;
-            w[r].z -= a.lr * v[r].z;
-            w[r].w -= a.lr * v[r].w;
+            v[r].x = momentum_update(a.beta, v[r].x, gr.x, a.wd, w[r].x);
+            v[r].y = momentum_update(a.beta, v[r].y, gr.y, a.wd, w[r].y);
+            v[r].z = momentum_update(a.beta, v[r].z, gr.z, a.wd, w[r].z);
+            v[r].w = momentum_update(a.beta, v[r].w, gr.w, a.wd, w[r].w);
+            w[r].x = weight_update(w[r].x, a.lr, v[r].x);
+            w[r].y = weight_update(w[r].y, a.lr, v[r].y);
+            w[r].z = weight_update(w[r].z, a.lr, v[r].z);
+            w[r].w = weight_update(w[r].w, a.lr, v[r].w);
             if (row < a.d_in) {
                 store_w4(Vw + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream, v[r]);
                 store_w4(W + static_cast<int64_t>(row) * a.d_out, 4 * j, a.d_out, vec, stream, w[r]);

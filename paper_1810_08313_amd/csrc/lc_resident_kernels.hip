@@ -453,14 +453,14 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
             for (int w = 0; w < Bp / 4; ++w) db += first ? colsum1[w][c] : colsum2[w][c];
             if (first) {
                 if (c_base + c < a.d1) {
-                    const float vb = beta * vb1s[c] + (db + a.wd * b1s[c]);
+                    const float vb = momentum_update(beta, vb1s[c], db, a.wd, b1s[c]);
                     vb1s[c] = vb;
-                    b1s[c] -= a.lr * vb;
+                    b1s[c] = weight_update(b1s[c], a.lr, vb);
                 }
             } else if (c < a.d2) {
-                const float vb = beta * vb2s[c] + (db + a.wd * b2s[c]);
+                const float vb = momentum_update(beta, vb2s[c], db, a.wd, b2s[c]);
                 vb2s[c] = vb;
-                b2s[c] -= a.lr * vb;
+                b2s[c] = weight_update(b2s[c], a.lr, vb);
             }
         }
         // ---- (5) dW_2[C, :] = A_1[:, C]^T dZ_2 and the update of the own rows (16 x 16 values: plain FMAs)
@@ -470,9 +470,9 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
                 float gw = 0.f;
                 for (int b = 0; b < Bp; ++b) gw += a1s[b][kk] * z2s[b][c2];
                 const float w = w2s[c2][kk];
-                const float v = beta * v2s[c2][kk] + (gw + a.wd * w);
+                const float v = momentum_update(beta, v2s[c2][kk], gw, a.wd, w);
                 v2s[c2][kk] = v;
-                w2s[c2][kk] = w - a.lr * v;
+                w2s[c2][kk] = weight_update(w, a.lr, v);
             }
         }
         // ---- (6) dW_1[:, C] = A_0^T dZ_1[:, C] and the update of the slice
@@ -494,9 +494,9 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const float w = w1s[4 * q + r][k];
-                    const float v = beta * v1[i][r] + (acc[r] + a.wd * w);
+                    const float v = momentum_update(beta, v1[i][r], acc[r], a.wd, w);
                     v1[i][r] = v;
-                    w1s[4 * q + r][k] = w - a.lr * v;
+                    w1s[4 * q + r][k] = weight_update(w, a.lr, v);
                 }
             }
         }
@@ -662,9 +662,9 @@ __global__ __launch_bounds__(kResThreads) void resident1_kernel(Res1Args a) {
         } else if (wave == 1 && lane < a.d1) {
             float db = 0.f;
             for (int w = 0; w < Bp / 4; ++w) db += colsum[w][lane];
-            const float vb = beta * vbs[lane] + (db + a.wd * bs[lane]);
+            const float vb = momentum_update(beta, vbs[lane], db, a.wd, bs[lane]);
             vbs[lane] = vb;
-            bs[lane] -= a.lr * vb;
+            bs[lane] = weight_update(bs[lane], a.lr, vb);
         }
         // ---- dW = A_0^T dZ and the update; tile kt = 16 rows of W
         for (int kt = wave; kt < a.dp0 / 16; kt += kResWaves) {
@@ -681,9 +681,9 @@ __global__ __launch_bounds__(kResThreads) void resident1_kernel(Res1Args a) {
                 const int k = 16 * kt + 4 * q + r;
                 if (k < a.d0 && j < a.d1) {
                     const float w = ws[j][k];
-                    const float v = beta * vs[j][k] + (acc[r] + a.wd * w);
+                    const float v = momentum_update(beta, vs[j][k], acc[r], a.wd, w);
                     vs[j][k] = v;
-                    ws[j][k] = w - a.lr * v;
+                    ws[j][k] = weight_update(w, a.lr, v);
                 }
             }
         }

@@ -159,15 +159,16 @@ __global__ __launch_bounds__(kThreads) void broadcast_chunk_kernel(const float* 
     st_stream(X + row * Ps + col, *reinterpret_cast<const float4*>(src + col));
 }
 
+// (the roundings of lc_mma.h's momentum_update / weight_update: two fused multiply-adds each)
 __device__ __forceinline__ void sgd_update4(float4& x, float4& v, const float4& g, float lr, float beta, float wd) {
-    v.x = beta * v.x + (g.x + wd * x.x);
-    v.y = beta * v.y + (g.y + wd * x.y);
-    v.z = beta * v.z + (g.z + wd * x.z);
-    v.w = beta * v.w + (g.w + wd * x.w);
-    x.x -= lr * v.x;
-    x.y -= lr * v.y;
-    x.z -= lr * v.z;
-    x.w -= lr * v.w;
+    v.x = __builtin_fmaf(beta, v.x, __builtin_fmaf(wd, x.x, g.x));
+    v.y = __builtin_fmaf(beta, v.y, __builtin_fmaf(wd, x.y, g.y));
+    v.z = __builtin_fmaf(beta, v.z, __builtin_fmaf(wd, x.z, g.z));
+    v.w = __builtin_fmaf(beta, v.w, __builtin_fmaf(wd, x.w, g.w));
+    x.x = __builtin_fmaf(-lr, v.x, x.x);
+    x.y = __builtin_fmaf(-lr, v.y, x.y);
+    x.z = __builtin_fmaf(-lr, v.z, x.z);
+    x.w = __builtin_fmaf(-lr, v.w, x.w);
 }
 
 // g <- G + wd x; v <- beta v + g; x <- x - lr v over the whole [m, Ps] block.
