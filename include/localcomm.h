@@ -107,6 +107,11 @@ int64_t lc_row_stride(int64_t P);
  * mix = SplitMix64 output function, G = 0x9E3779B97F4A7C15 (sampling with
  * replacement from the whole set, an independent stream per worker).
  * The iteration counter starts at k = 0.  No device memory is touched.
+ * Four environment variables are read here, for measurement runs only (results are bit-identical
+ * whatever they say): LC_AVG_CHUNK_MB (1..1024, column chunk of the two-kernel averaging step),
+ * LC_AVG_TWO_PHASE (0: one averaging kernel at every size), LC_SHARED_W_ORDER (0: replica-major
+ * block order everywhere; n: sets of n replicas, see lc_set_lazy_broadcast), LC_SYNC_FIRST_LAYER
+ * (0: no tile-owner first-layer kernel at tau = 1, see lc_set_deferred_update).
  * Errors: LC_ERR_ARG (m < 1, null), LC_ERR_MODEL (P != lc_param_count, bad dims,
  * B outside 1..128, E > N). */
 int lc_init(int m, int64_t P, const lc_model* model, uint64_t seed, lc_handle** out);
@@ -167,7 +172,10 @@ int lc_local_periods(lc_handle* h, int tau, int n_periods);
  * step after it; at tau = 1 the traffic per iteration falls from about 28 to 16 bytes per
  * parameter.  Results are bit-identical to the eager form.  While a broadcast is pending the rows
  * of X in device memory are STALE; every entry point of this library accounts for that, but a
- * caller who reads X directly must call lc_materialize() first.  Turning the mode off materialises. */
+ * caller who reads X directly must call lc_materialize() first.  Turning the mode off materialises.
+ * In a step that reads the one model for all replicas, layers of 8 MB and more (in a state above
+ * 256 MB) are worked through tile by tile for sets of 8 replicas at a time instead of replica by
+ * replica, so that a weight tile is fetched once per set. */
 int lc_set_lazy_broadcast(lc_handle* h, int on);
 int lc_materialize(lc_handle* h);
 
