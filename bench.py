@@ -38,26 +38,26 @@ FLAT = {"cfg5a": (16, 25_600_000), "cfg5b": (8, 138_000_000)}
 # layers' launches of one iteration, the busy share weighted by launch duration); for the resident
 # path it is the one kernel.  Summaries with the commands are in profiles/pmc_traffic_mfma_<workload>.txt.
 PMC = {
-    "cfg2": {"traffic": (28.115e6 + 2.389e6) / 2, "mfma_busy_pct": (8.21 * 8.6 + 1.21 * 8.9) / 17.5},
+    "cfg2": {"traffic": (28.115e6 + 2.389e6) / 2, "mfma_busy_pct": (8.19 * 8.6 + 1.21 * 8.9) / 17.5},
     # layer 1: first_layer_kernel where the next step's input is at hand (18 of 20 steps at tau=20,
     # 9 of 10 at tau=10; 16 steps are gathered per launch), backward_kernel otherwise
-    "cfg3": {"traffic": ((0.9 * 841.585e6 + 0.1 * 822.539e6) + 288.484e6 + 15.974e6) / 3,
-             "mfma_busy_pct": (0.9 * 7.58 * 199.0 + 0.1 * 3.20 * 162.0 + 4.84 * 64.3 + 1.17 * 9.7) /
+    "cfg3": {"traffic": ((0.9 * 841.605e6 + 0.1 * 822.536e6) + 288.527e6 + 15.974e6) / 3,
+             "mfma_busy_pct": (0.9 * 7.58 * 199.0 + 0.1 * 3.20 * 162.0 + 4.88 * 64.3 + 1.17 * 9.7) /
                               (0.9 * 199.0 + 0.1 * 162.0 + 64.3 + 9.7)},
-    "cfg4": {"traffic": ((0.9 * 6423.644e6 + 0.1 * 6466.273e6) + 2 * 4341.936e6 + 46.474e6) / 4,
-             "mfma_busy_pct": (0.9 * 2.40 * 1278 + 0.1 * 0.87 * 1184 + 1.67 * 1669 + 1.22 * 28) /
+    "cfg4": {"traffic": ((0.9 * 6422.756e6 + 0.1 * 6466.302e6) + 2 * 4342.029e6 + 46.472e6) / 4,
+             "mfma_busy_pct": (0.9 * 2.39 * 1278 + 0.1 * 0.86 * 1184 + 1.67 * 1669 + 1.21 * 28) /
                               (0.9 * 1278 + 0.1 * 1184 + 1669 + 28)},
 }
 # the same two workloads with --no-first-layer-fusion (backward_kernel for every layer)
 PMC_UNFUSED = {
-    "cfg3": {"traffic": (822.539e6 + 288.484e6 + 15.974e6) / 3,
-             "mfma_busy_pct": (3.20 * 162.0 + 4.84 * 64.3 + 1.17 * 9.7) / 236.0},
-    "cfg4": {"traffic": (6466.273e6 + 2 * 4341.936e6 + 46.474e6) / 4,
-             "mfma_busy_pct": (0.87 * 1184 + 1.67 * 1669 + 1.22 * 28) / 2881},
+    "cfg3": {"traffic": (822.536e6 + 288.527e6 + 15.974e6) / 3,
+             "mfma_busy_pct": (3.20 * 162.0 + 4.88 * 64.3 + 1.17 * 9.7) / 236.0},
+    "cfg4": {"traffic": (6466.302e6 + 2 * 4342.029e6 + 46.472e6) / 4,
+             "mfma_busy_pct": (0.86 * 1184 + 1.67 * 1669 + 1.21 * 28) / 2881},
 }
 PMC_RESIDENT = {
     "cfg1": {"traffic": 0.982e6, "mfma_busy_pct": 0.08},     # per launch of 32 local steps and 8 averaging steps
-    "cfg2": {"traffic": 44.760e6, "mfma_busy_pct": 12.03},   # per launch of 5 local steps
+    "cfg2": {"traffic": 44.759e6, "mfma_busy_pct": 12.05},   # per launch of 5 local steps
 }
 
 
