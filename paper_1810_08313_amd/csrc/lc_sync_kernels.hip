@@ -55,12 +55,12 @@ __global__ __launch_bounds__(256) void sync_first_layer_kernel(SyncArgs a) {
     // the tile of the shared model, rows k0 + 4 q + r, columns c0 + 4 j .. + 3 (rows past d_in read
     // the last row; they are never stored)
     float4 w[4];
-    int64_t at[4];
+    int at[4];   // (offsets inside one model: below 2^31 for any layer this kernel takes)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int row = k0 + 4 * q + r;
         const int rr = row < a.d_in ? row : a.d_in - 1;
-        at[r] = a.w_off + static_cast<int64_t>(rr) * a.d_out + c0 + 4 * j;
+        at[r] = static_cast<int>(a.w_off + static_cast<int64_t>(rr) * a.d_out + c0 + 4 * j);
         w[r] = *reinterpret_cast<const float4*>(a.xbar + at[r]);
     }
     const bool bias_job = rb == cc % a.n_row_blocks && tid < kColChunk && c0 + tid < a.d_out;
@@ -71,14 +71,16 @@ __global__ __launch_bounds__(256) void sync_first_layer_kernel(SyncArgs a) {
     for (int r = 0; r < 4; ++r) sum[r][0] = sum[r][1] = sum[r][2] = sum[r][3] = 0.0;
 
     float4 v[4], vn[4];
-    Frag<OT> af[NS], afn[NS], st_t[NS];
-    auto issue_loads = [&](int g, float4 (&vv)[4], Frag<OT> (&aa)[NS]) {
+    Frag<OT> af[NS], st_t[NS];
+    auto load_rows = [&](int g) {   // this lane's A_0^T operands of replica g
+        const OT* AT = static_cast<const OT*>(a.a_fm) + static_cast<int64_t>(g) * a.dp_in * Bp;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) af[s] = load8(AT + static_cast<int64_t>(k0 + j) * Bp + 32 * s + 8 * q);
+    };
+    auto issue_loads = [&](int g, float4 (&vv)[4]) {
         const float* Vg = a.V + static_cast<int64_t>(g) * a.x_stride;
 #pragma unroll
         for (int r = 0; r < 4; ++r) vv[r] = load_wm<kWVectorStream>(Vg + at[r], 0, a.d_out, true);
-        const OT* AT = static_cast<const OT*>(a.a_fm) + static_cast<int64_t>(g) * a.dp_in * Bp;
-#pragma unroll
-        for (int s = 0; s < NS; ++s) aa[s] = load8(AT + static_cast<int64_t>(k0 + j) * Bp + 32 * s + 8 * q);
         // the dZ^T slice is one contiguous run of 64 * Bp elements
         const OT* src_t = static_cast<const OT*>(a.dz_fm) + (static_cast<int64_t>(g) * a.dp_out + c0) * Bp;
 #pragma unroll
@@ -93,14 +95,15 @@ __global__ __launch_bounds__(256) void sync_first_layer_kernel(SyncArgs a) {
         }
     };
 
-    issue_loads(0, v, af);
+    issue_loads(0, v);
+    load_rows(0);
     stage_to_lds(0);
     __syncthreads();
 
     for (int g = 0; g < a.G; ++g) {
         const int buf = g & 1;
         const bool has_next = g + 1 < a.G;
-        if (has_next) issue_loads(g + 1, vn, afn);
+        if (has_next) issue_loads(g + 1, vn);
 
         // bias of these 64 columns for replica g (one thread per column): the momentum entry is
         // updated here, the averaging kernels form x_bar - lr v from it like for every other layer
@@ -129,6 +132,7 @@ __global__ __launch_bounds__(256) void sync_first_layer_kernel(SyncArgs a) {
                 acc[t] = mma8(af[s], bf, acc[t]);
             }
         }
+        if (has_next) load_rows(g + 1);   // (the operand registers are free again; no second set)
         // momentum update, the replica's weights, their contribution to the mean
         float* Vg = a.V + static_cast<int64_t>(g) * a.x_stride;
 #pragma unroll
@@ -151,8 +155,6 @@ __global__ __launch_bounds__(256) void sync_first_layer_kernel(SyncArgs a) {
             stage_to_lds(buf ^ 1);   // (its last readers passed the barrier of the previous replica)
 #pragma unroll
             for (int r = 0; r < 4; ++r) v[r] = vn[r];
-#pragma unroll
-            for (int s = 0; s < NS; ++s) af[s] = afn[s];
         }
         __syncthreads();
     }
