@@ -111,7 +111,7 @@ int64_t lc_row_stride(int64_t P);
  * whatever they say): LC_AVG_CHUNK_MB (1..1024, column chunk of the two-kernel averaging step),
  * LC_AVG_TWO_PHASE (0: one averaging kernel at every size), LC_SHARED_W_ORDER (0: replica-major
  * block order everywhere; n: sets of n replicas, see lc_set_lazy_broadcast), LC_SYNC_FIRST_LAYER
- * (0: no tile-owner first-layer kernel at tau = 1, see lc_set_deferred_update).
+ * (0: no tile-owner kernels at tau = 1, 1: for the first layer only; see lc_set_deferred_update).
  * Errors: LC_ERR_ARG (m < 1, null), LC_ERR_MODEL (P != lc_param_count, bad dims,
  * B outside 1..128, E > N). */
 int lc_init(int m, int64_t P, const lc_model* model, uint64_t seed, lc_handle** out);
@@ -230,9 +230,11 @@ int lc_set_first_layer_fusion(lc_handle* h, int on);
  * kernels then leave the rows of X unwritten, and the averaging step reads the rows of V and
  * forms each replica's weights on the fly (same expression, same rounding) before it adds them
  * up in double: 12 instead of 16 bytes per parameter, replica and iteration, bit-identical
- * results.  A first layer of 8 MB or more with rows of a multiple of 64 columns goes further: one
- * kernel owns its weights by tile, walks over the replicas, updates their momentum tiles and
- * writes the layer's new average itself (8 bytes per parameter and replica).  Applies to LC_KIND_MLP models on the launch-per-layer path whose last layer has more
+ * results.  Layers of 8 MB or more with rows of a multiple of 64 columns (the last layer excepted)
+ * go further: one kernel owns such a layer's weights by tile, walks over the replicas, updates
+ * their momentum tiles and writes the layer's new average itself (8 bytes per parameter and
+ * replica); above the first layer a pass over the old weights forms the deltas of the layer below
+ * beforehand.  Applies to LC_KIND_MLP models on the launch-per-layer path whose last layer has more
  * than 128 inputs, not while block momentum is on, and not to lc_local_steps() + lc_average()
  * called one by one (the library cannot know that an averaging step follows).  Default on. */
 int lc_set_deferred_update(lc_handle* h, int on);

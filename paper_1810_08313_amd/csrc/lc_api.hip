@@ -194,9 +194,10 @@ int one_local_step(lc_handle* h, bool next_gathered) {
         for (int l = head_is_fused(h) ? h->L - 1 : h->L; l >= 1; --l) {
             if (l == 1 && first_fused) {
                 LC_HIP(h, launch_first_layer(h));
-            } else if (l == 1 && h->defer_x && sync_first_layer_ok(h)) {
-                LC_HIP(h, launch_sync_first_layer(h));   // ... and the layer's part of the averaging step
-                h->sync1_done = true;
+            } else if (h->defer_x && sync_layer_ok(h, l)) {
+                if (l > 1) LC_HIP(h, launch_backward(h, l, true));   // dZ_{l-1} from the weights of before the update
+                LC_HIP(h, launch_sync_layer(h, l));   // dW_l, V, and the layer's part of the averaging step
+                h->sync_done |= 1u << l;
             } else {
                 LC_HIP(h, launch_backward(h, l));
             }
@@ -271,7 +272,8 @@ int run_periods(lc_handle* h, int tau, int n_periods, bool average) {
                     h->train.cur_slot = t;
                     const int r = one_local_step(h, u + 1 < in_period);
                     if (r != LC_OK) {
-                        h->defer_x = h->sync1_done = false;
+                        h->defer_x = false;
+                        h->sync_done = 0;
                         return r;
                     }
                 }
@@ -282,7 +284,7 @@ int run_periods(lc_handle* h, int tau, int n_periods, bool average) {
                 if (average) {
                     const int r = lc_average(h);   // (reads V instead of X while defer_x is set)
                     h->defer_x = false;
-                    h->sync1_done = false;
+                    h->sync_done = 0;
                     if (r != LC_OK) return r;
                 }
             }
@@ -402,9 +404,12 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     h->lazy_enabled = h->lazy_rows = h->lazy_enabled_step = false;
     h->defer_x_on = true;
     h->defer_x = false;
-    h->sync1_on = true;
-    if (const char* e = getenv("LC_SYNC_FIRST_LAYER")) h->sync1_on = atoi(e) != 0;   // tuning knob for measurement runs
-    h->sync1_done = false;
+    h->sync1_on = h->sync_all_on = true;
+    if (const char* e = getenv("LC_SYNC_FIRST_LAYER")) {   // tuning knob for measurement runs: 0 off, 1 layer 1 only
+        h->sync1_on = atoi(e) != 0;
+        h->sync_all_on = atoi(e) > 1;
+    }
+    h->sync_done = 0;
     h->loss_parts_train = h->loss_parts_eval = 1;
     (void)carve(h, nullptr);
     *out = h;

@@ -92,7 +92,8 @@ struct lc_handle {
     bool defer_x_on, defer_x;
     // tau = 1, first layer: backward pass, update of V and the layer's averaging in one kernel; sync1_done
     // is set while the averaging step of the iteration still has to skip the layer
-    bool sync1_on, sync1_done;
+    bool sync1_on, sync_all_on;   // layer 1 / the layers above it as well
+    unsigned sync_done;           // bit l: the iteration in progress has averaged layer l's weights already
     bool share_w_on;          // block order of the steps that read one model for all replicas (see FwdArgs)
     int share_w_set;          // ... replicas per set
     // resident local steps (small two-layer models): exchange buffer, barrier counters, switches
@@ -134,11 +135,11 @@ hipError_t launch_gather(lc_handle* h, bool eval, int64_t k_or_base, int n_steps
 hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset);
 bool forward_fuses_softmax(const lc_handle* h);  // last layer's kernel also does a3
 hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset);
-hipError_t launch_backward(lc_handle* h, int l);
+hipError_t launch_backward(lc_handle* h, int l, bool da_only = false);   // da_only: dZ_{l-1} only, no update
 bool first_layer_kernel_ok(const lc_handle* h);   // layer 1: backward kernel that also runs the next step's forward
 hipError_t launch_first_layer(lc_handle* h);
-bool sync_first_layer_ok(const lc_handle* h);     // layer 1 at tau = 1: backward, update of V and averaging of the layer
-hipError_t launch_sync_first_layer(lc_handle* h);
+bool sync_layer_ok(const lc_handle* h, int l);    // layer l at tau = 1: dW, update of V and averaging of the layer by tile
+hipError_t launch_sync_layer(lc_handle* h, int l);
 bool shared_weight_order(const lc_handle* h, const LayerGeom& g);   // tile-major block order on steps that read one model
 int shared_set(const lc_handle* h, int G);                          // ... replicas per set
 bool head_is_fused(const lc_handle* h);   // last layer: forward + softmax + backward in one kernel

@@ -612,7 +612,9 @@ struct BwdArgs {
 // in memory; dA is complete when the wavefront has walked its rows, so nothing
 // is reduced across workgroups.  When dA is not needed (first layer) the
 // columns may additionally be split over several workgroups.
-template <typename OT, int NT, int WM>
+// DAO instances (tau = 1, layers whose update and averaging a tile-owner kernel does afterwards)
+// form dZ_{l-1} only: the same walk over W_l without V, dW, the update or any store to X and V.
+template <typename OT, int NT, int WM, bool DAO = false>
 __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
     constexpr int kPad = sizeof(OT) == 2 ? 8 : 4;
     constexpr int Bp = 16 * NT;
@@ -666,8 +668,10 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
 
     // this lane's A operands for the dW product: row k0 + j of A_{l-1}^T, all batch steps
     Frag<OT> af[NS];
+    if constexpr (!DAO) {
 #pragma unroll
-    for (int s = 0; s < NS; ++s) af[s] = load8(AT + static_cast<int64_t>(k0 + j) * Bp + 32 * s + 8 * q);
+        for (int s = 0; s < NS; ++s) af[s] = load8(AT + static_cast<int64_t>(k0 + j) * Bp + 32 * s + 8 * q);
+    }
 
     // ReLU gates of this lane's dA entries, fetched now (one bit each) instead of after the walk
     uint32_t gate = 0;
@@ -699,13 +703,15 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
                     ww[r] = load_wm<kWVector>(Wr + static_cast<int64_t>(rr) * a.d_out, c0 + 4 * j, a.d_out, vec);
                 else
                     ww[r] = load_wm<WM>(Wr + static_cast<int64_t>(rr) * a.d_out, c0 + 4 * j, a.d_out, vec);
-                vv[r] = load_wm<WM>(Vw + static_cast<int64_t>(rr) * a.d_out, c0 + 4 * j, a.d_out, vec);
+                if constexpr (!DAO) vv[r] = load_wm<WM>(Vw + static_cast<int64_t>(rr) * a.d_out, c0 + 4 * j, a.d_out, vec);
             }
         }
-        // the dZ^T slice is one contiguous run of 64 * Bp elements
-        const OT* src_t = dZT + static_cast<int64_t>(c0) * Bp;
+        if constexpr (!DAO) {
+            // the dZ^T slice is one contiguous run of 64 * Bp elements
+            const OT* src_t = dZT + static_cast<int64_t>(c0) * Bp;
 #pragma unroll
-        for (int s = 0; s < NS; ++s) st_t[s] = load8(src_t + static_cast<int64_t>(tid + 256 * s) * 8);
+            for (int s = 0; s < NS; ++s) st_t[s] = load8(src_t + static_cast<int64_t>(tid + 256 * s) * 8);
+        }
         if (need_da) {
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
@@ -715,11 +721,13 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         }
     };
     auto stage_to_lds = [&]() {
+        if constexpr (!DAO) {
 #pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            const int p = tid + 256 * s;
-            const int c = p / (Bp / 8), seg = p % (Bp / 8);
-            *reinterpret_cast<Frag<OT>*>(&dzt_lds[(c & 3) * 16 + (c >> 2)][seg * 8]) = st_t[s];
+            for (int s = 0; s < NS; ++s) {
+                const int p = tid + 256 * s;
+                const int c = p / (Bp / 8), seg = p % (Bp / 8);
+                *reinterpret_cast<Frag<OT>*>(&dzt_lds[(c & 3) * 16 + (c >> 2)][seg * 8]) = st_t[s];
+            }
         }
         if (need_da) {
 #pragma unroll
@@ -742,7 +750,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         // bias of these 64 columns: db_l = sum_b dZ_l from the staged slice, then the same update
         // (one thread per column).  Every row block of the replica walks this chunk; the job goes
         // to them in turn, so that no workgroup carries it on all of its trips and finishes late.
-        if (rb == chunk_at(i) % a.n_row_blocks && tid < kColChunk && c0 + tid < a.d_out) {
+        if (!DAO && rb == chunk_at(i) % a.n_row_blocks && tid < kColChunk && c0 + tid < a.d_out) {
             float* bx = a.X + g * a.x_stride + a.b_off + c0 + tid;
             float* bv = a.V + g * a.x_stride + a.b_off + c0 + tid;
             const float x = a.Xr[g * a.xr_stride + a.b_off + c0 + tid];   // requested before the sum below
@@ -761,14 +769,16 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         }
         // dW tile: sum over the batch of A^T[k][b] dZ^T[c][b]
         f32x4 acc[4];
+        if constexpr (!DAO) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < NS; ++s) {
+            for (int s = 0; s < NS; ++s) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const Frag<OT> bf = *reinterpret_cast<const Frag<OT>*>(&dzt_lds[t * 16 + j][32 * s + 8 * q]);
-                acc[t] = mma8(af[s], bf, acc[t]);
+                for (int t = 0; t < 4; ++t) {
+                    const Frag<OT> bf = *reinterpret_cast<const Frag<OT>*>(&dzt_lds[t * 16 + j][32 * s + 8 * q]);
+                    acc[t] = mma8(af[s], bf, acc[t]);
+                }
             }
         }
         if (need_da) {
@@ -782,7 +792,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         }
         // update and store
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < 4 && !DAO; ++r) {
             const int row = k0 + 4 * q + r;
             const float4 gr = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
             v[r].x = momentum_update(a.beta, v[r].x, gr.x, a.wd, w[r].x);
@@ -818,7 +828,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 w[r] = wn[r];
-                v[r] = vn[r];
+                if constexpr (!DAO) v[r] = vn[r];
             }
         }
     }
@@ -1136,6 +1146,17 @@ hipError_t launch_bwd_nt(const BwdArgs& a, int nt, unsigned grid, hipStream_t s)
     }
     return hipGetLastError();
 }
+// dZ_{l-1} only (see backward_kernel); for layers with 16-byte aligned rows of a multiple of 64 columns
+template <typename OT>
+hipError_t launch_bwd_da_only(const BwdArgs& a, int nt, unsigned grid, hipStream_t s) {
+    switch (nt) {
+        case 2: hipLaunchKernelGGL((backward_kernel<OT, 2, kWVectorStream, true>), dim3(grid), dim3(256), 0, s, a); break;
+        case 4: hipLaunchKernelGGL((backward_kernel<OT, 4, kWVectorStream, true>), dim3(grid), dim3(256), 0, s, a); break;
+        case 8: hipLaunchKernelGGL((backward_kernel<OT, 8, kWVectorStream, true>), dim3(grid), dim3(256), 0, s, a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
 template <typename OT>
 hipError_t launch_bwd_wm(const BwdArgs& a, int nt, unsigned grid, hipStream_t s) {
     switch (weight_mode(a.vec != 0, a.stream != 0, a.d_out)) {
@@ -1343,7 +1364,7 @@ hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset) {
     return hipGetLastError();
 }
 
-hipError_t launch_backward(lc_handle* h, int l) {
+hipError_t launch_backward(lc_handle* h, int l, bool da_only) {
     const ActSet& S = h->train;
     const LayerGeom& g = h->layer[l];
     const bool bf16 = h->md.gemm == LC_GEMM_BF16;
@@ -1389,8 +1410,16 @@ hipError_t launch_backward(lc_handle* h, int l) {
     a.total_blocks = static_cast<int64_t>(S.G) * a.n_row_blocks * a.col_split;
     const unsigned grid = xcd_grid(a.total_blocks);
     timing_start(h, kTimeBwd);
-    const hipError_t e = bf16 ? launch_bwd_wm<bf16_t>(a, S.Bp / 16, grid, h->stream)
-                              : launch_bwd_wm<float>(a, S.Bp / 16, grid, h->stream);
+    hipError_t e;
+    if (da_only) {
+        // (same conditions as the tile-owner kernel that follows; the columns are not shared out here)
+        if (l < 2 || !a.vec || g.d_out % kColChunk != 0 || !a.stream) return hipErrorInvalidValue;
+        e = bf16 ? launch_bwd_da_only<bf16_t>(a, S.Bp / 16, grid, h->stream)
+                 : launch_bwd_da_only<float>(a, S.Bp / 16, grid, h->stream);
+    } else {
+        e = bf16 ? launch_bwd_wm<bf16_t>(a, S.Bp / 16, grid, h->stream)
+                 : launch_bwd_wm<float>(a, S.Bp / 16, grid, h->stream);
+    }
     timing_stop(h, kTimeBwd);
     return e;
 }

@@ -66,9 +66,9 @@ __device__ __forceinline__ float4 weights_from_momentum(const float4& xb, const 
 // magnitudes, so the result is the correctly rounded mean whatever the order.
 __global__ __launch_bounds__(kThreads) void average_kernel(const float* X, float* out_rows, float* out_single,
                                                            int m, int64_t Ps, BlockMomentum bm, DeferredUpdate du,
-                                                           int64_t col0) {
-    const int64_t col = col0 + (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
-    if (col >= Ps) return;
+                                                           int64_t c_lo, int64_t c_hi) {
+    const int64_t col = c_lo + (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
+    if (col >= c_hi) return;
     float4 xb = make_float4(0.f, 0.f, 0.f, 0.f);
     if (du.xb) xb = *reinterpret_cast<const float4*>(du.xb + col);
     double s0 = 0, s1 = 0, s2 = 0, s3 = 0;
@@ -273,32 +273,54 @@ hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* 
     const DeferredUpdate du{h->defer_x ? h->xbar : nullptr, h->md.lr};
     if (h->defer_x) X = h->V;
     const bool own_rows = X == h->X || h->defer_x;
-    // columns that the first layer's tau = 1 kernel has averaged already (layer 1 is stored first)
-    const int64_t col0 = (h->defer_x && h->sync1_done) ? static_cast<int64_t>(h->layer[1].d_in) * h->layer[1].d_out : 0;
+    // column ranges still to be averaged: everything, minus the weights of the layers that a
+    // tile-owner kernel of this tau = 1 iteration has averaged already (multiples of 4 columns)
+    int64_t r_lo[LC_MAX_LAYERS + 2], r_hi[LC_MAX_LAYERS + 2];
+    int n_r = 0;
+    {
+        int64_t lo = 0;
+        for (int l = 1; l <= h->L && h->defer_x; ++l) {
+            if (!(h->sync_done >> l & 1u)) continue;
+            const int64_t w_lo = h->layer[l].w_off, w_hi = h->layer[l].b_off;
+            if (w_lo > lo) { r_lo[n_r] = lo; r_hi[n_r] = w_lo; ++n_r; }
+            lo = w_hi;
+        }
+        if (lo < h->Ps) { r_lo[n_r] = lo; r_hi[n_r] = h->Ps; ++n_r; }
+    }
     if (step && own_rows && h->m >= 2 && h->avg_two_phase && big) {
         timing_start(h, kTimeAvg);
         const int64_t chunk = h->avg_chunk_floats;
         float* dst = out_rows ? h->X : out_single;
-        for (int64_t lo = col0; lo < h->Ps; lo += chunk) {
-            const int64_t hi = lo + chunk < h->Ps ? lo + chunk : h->Ps;
-            const int64_t nblk = ((hi - lo) / 4 + kThreads - 1) / kThreads;
-            const int64_t nred = (nblk + kReduceCols - 1) / kReduceCols;
-            if (du.xb)
-                hipLaunchKernelGGL(reduce_chunk_kernel<true>, dim3(static_cast<unsigned>(nred)), dim3(kThreads), 0,
-                                   h->stream, X, dst, h->m, h->Ps, lo, hi, bm, du);
-            else
-                hipLaunchKernelGGL(reduce_chunk_kernel<false>, dim3(static_cast<unsigned>(nred)), dim3(kThreads), 0,
-                                   h->stream, X, dst, h->m, h->Ps, lo, hi, bm, du);
-            if (out_rows)
-                hipLaunchKernelGGL(broadcast_chunk_kernel, dim3(static_cast<unsigned>(nblk * (h->m - 1))),
-                                   dim3(kThreads), 0, h->stream, h->X, h->X, 1, h->Ps, lo, hi, nblk);
+        for (int r = 0; r < n_r; ++r) {
+            if (r_hi[r] - r_lo[r] <= 256 * 1024) {
+                // a short range (biases, a small last layer): one thread per 16-byte column walks the
+                // rows with several loads in flight; the chunked kernel would put it all on one workgroup
+                hipLaunchKernelGGL(average_kernel, dim3(blocks_for((r_hi[r] - r_lo[r]) / 4)), dim3(kThreads), 0,
+                                   h->stream, X, out_rows, out_single, h->m, h->Ps, bm, du, r_lo[r], r_hi[r]);
+                continue;
+            }
+            for (int64_t lo = r_lo[r]; lo < r_hi[r]; lo += chunk) {
+                const int64_t hi = lo + chunk < r_hi[r] ? lo + chunk : r_hi[r];
+                const int64_t nblk = ((hi - lo) / 4 + kThreads - 1) / kThreads;
+                const int64_t nred = (nblk + kReduceCols - 1) / kReduceCols;
+                if (du.xb)
+                    hipLaunchKernelGGL(reduce_chunk_kernel<true>, dim3(static_cast<unsigned>(nred)), dim3(kThreads), 0,
+                                       h->stream, X, dst, h->m, h->Ps, lo, hi, bm, du);
+                else
+                    hipLaunchKernelGGL(reduce_chunk_kernel<false>, dim3(static_cast<unsigned>(nred)), dim3(kThreads),
+                                       0, h->stream, X, dst, h->m, h->Ps, lo, hi, bm, du);
+                if (out_rows)
+                    hipLaunchKernelGGL(broadcast_chunk_kernel, dim3(static_cast<unsigned>(nblk * (h->m - 1))),
+                                       dim3(kThreads), 0, h->stream, h->X, h->X, 1, h->Ps, lo, hi, nblk);
+            }
         }
         timing_stop(h, kTimeAvg);
         return hipGetLastError();
     }
     if (step) timing_start(h, kTimeAvg);
-    hipLaunchKernelGGL(average_kernel, dim3(blocks_for((h->Ps - col0) / 4)), dim3(kThreads), 0, h->stream, X,
-                       out_rows, out_single, h->m, h->Ps, bm, du, col0);
+    for (int r = 0; r < n_r; ++r)
+        hipLaunchKernelGGL(average_kernel, dim3(blocks_for((r_hi[r] - r_lo[r]) / 4)), dim3(kThreads), 0, h->stream, X,
+                           out_rows, out_single, h->m, h->Ps, bm, du, r_lo[r], r_hi[r]);
     if (step) timing_stop(h, kTimeAvg);
     return hipGetLastError();
 }

@@ -179,26 +179,29 @@ hipError_t launch_sync1(const SyncArgs& a, int nt, unsigned grid, hipStream_t st
 
 }  // namespace
 
-// Layer 1 of models with at least two layers, stored first in the parameter vector, whose rows are
-// 16-byte aligned and a multiple of 64 columns long; large layers only (the ones the shared-model
-// block order is for): small ones are cache-resident and gain nothing.
-bool sync_first_layer_ok(const lc_handle* h) {
-    if (h->md.kind != LC_KIND_MLP || h->L < 2 || !h->sync1_on) return false;
-    const LayerGeom& g = h->layer[1];
+// Layers of models with at least two layers whose rows are 16-byte aligned and a multiple of 64
+// columns long; large layers only (the ones the shared-model block order is for): small ones are
+// cache-resident and gain nothing.  The last layer keeps its own kernels (its forward pass forms
+// the loss and dZ_L).
+bool sync_layer_ok(const lc_handle* h, int l) {
+    if (h->md.kind != LC_KIND_MLP || h->L < 2 || !h->sync1_on || l < 1 || l >= h->L) return false;
+    const LayerGeom& g = h->layer[l];
     const ActSet& S = h->train;
-    if (g.w_off != 0 || g.d_out % kColChunk != 0 || h->Ps % 4 != 0) return false;
+    if (g.w_off % 4 != 0 || g.d_out % kColChunk != 0 || h->Ps % 4 != 0) return false;
     if (S.Bp != 32 && S.Bp != 64 && S.Bp != 128) return false;
     if (g.dp_in % 64 != 0 || g.d_in < 1) return false;
+    if (l > 1 && !h->sync_all_on) return false;
     return shared_weight_order(h, g);
 }
 
-// Backward pass of layer 1 for every replica, the update of V, and the new averaged first-layer
-// weights written over the old ones in xbar.  Only inside a tau = 1 iteration whose replicas all
-// start from xbar (lc_handle::defer_x).
-hipError_t launch_sync_first_layer(lc_handle* h) {
+// dW_l of every replica from A_{l-1}^T and dZ_l, the update of V, and the new averaged weights of
+// the layer written over the old ones in xbar.  Only inside a tau = 1 iteration whose replicas all
+// start from xbar (lc_handle::defer_x); for l > 1 after dZ_{l-1} has been formed from the old
+// weights (launch_backward(h, l, true)).
+hipError_t launch_sync_layer(lc_handle* h, int l) {
     const ActSet& S = h->train;
-    const LayerGeom& g = h->layer[1];
-    if (!sync_first_layer_ok(h) || !h->defer_x || !h->lazy_rows) return hipErrorInvalidValue;
+    if (!sync_layer_ok(h, l) || !h->defer_x || !h->lazy_rows) return hipErrorInvalidValue;
+    const LayerGeom& g = h->layer[l];
     const bool bf16 = h->md.gemm == LC_GEMM_BF16;
     SyncArgs a;
     a.V = h->V;
@@ -212,9 +215,13 @@ hipError_t launch_sync_first_layer(lc_handle* h) {
     a.dp_out = g.dp_out;
     a.B = S.B;
     a.G = S.G;
-    const size_t slot_bytes = static_cast<size_t>(S.G) * S.Bp * g.dp_in * (bf16 ? 2 : 4);
-    a.a_fm = static_cast<const char*>(S.a_fm[0]) + static_cast<size_t>(S.cur_slot) * slot_bytes;
-    a.dz_fm = S.dz_fm[1];
+    if (l == 1) {
+        const size_t slot_bytes = static_cast<size_t>(S.G) * S.Bp * g.dp_in * (bf16 ? 2 : 4);
+        a.a_fm = static_cast<const char*>(S.a_fm[0]) + static_cast<size_t>(S.cur_slot) * slot_bytes;
+    } else {
+        a.a_fm = S.a_fm[l - 1];
+    }
+    a.dz_fm = S.dz_fm[l];
     a.lr = h->md.lr;
     a.beta = effective_beta(h);
     a.wd = h->md.wd;
