@@ -12,7 +12,7 @@ from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
 
-from .build import LIB, build
+from .build import LIB, LIB_F32ACC, build
 
 MAX_LAYERS = 8
 KIND_QUAD, KIND_MLP = 0, 1
@@ -105,7 +105,37 @@ def lib() -> C.CDLL:
     L.orc_run_ex.restype = C.c_int
     L.orc_run_ex.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int64, C.c_int, C.c_double, C.c_int, C.c_int, lp, fp,
                              C.c_int, lp, C.POINTER(C.c_int), fp, C.c_int, C.POINTER(C.c_int), lp]
+    L.orc_acc_bytes.restype = C.c_int
+    L.orc_acc_bytes.argtypes = []
+    assert L.orc_acc_bytes() == 8, "the oracle accumulates in double"
     _lib = L
+    return L
+
+
+_probe = None
+
+
+def f32acc_probe() -> C.CDLL:
+    """The same source compiled with fp32 accumulators in the matrix products (same order of
+    additions).  A sensitivity probe: tests use it to SHOW how far gradients move and which ReLU
+    gates change side when only the summation precision changes.  Only the two stateless pieces
+    are exposed, and nothing is ever compared with the HIP path through it."""
+    global _probe
+    if _probe is not None:
+        return _probe
+    if not os.path.exists(LIB_F32ACC):
+        build()
+    L = C.CDLL(LIB_F32ACC)
+    fp, ip, lp = C.POINTER(C.c_float), C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+    mp = C.POINTER(OrcModel)
+    L.orc_acc_bytes.restype = C.c_int
+    L.orc_acc_bytes.argtypes = []
+    assert L.orc_acc_bytes() == 4
+    L.orc_mlp_loss_grad.restype = C.c_float
+    L.orc_mlp_loss_grad.argtypes = [mp, fp, fp, ip, lp, fp]
+    L.orc_mlp_preactivations.restype = None
+    L.orc_mlp_preactivations.argtypes = [mp, fp, fp, lp, fp]
+    _probe = L
     return L
 
 
@@ -160,27 +190,32 @@ def next_tau_ex(F0: float, Fl: float, tau0: int, tau_prev: int, gamma: float = 0
 
 
 def mlp_loss_grad(md: OrcModel, x: np.ndarray, data: np.ndarray, labels: np.ndarray,
-                  idx: Sequence[int], want_grad: bool = True) -> Tuple[float, Optional[np.ndarray]]:
+                  idx: Sequence[int], want_grad: bool = True, f32acc: bool = False) -> Tuple[float, Optional[np.ndarray]]:
+    """f32acc=True asks the fp32-accumulation probe instead of the oracle (sensitivity only)."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     data = np.ascontiguousarray(data, dtype=np.float32)
     labels = np.ascontiguousarray(labels, dtype=np.int32)
     ix = np.ascontiguousarray(idx, dtype=np.int64)
     assert ix.size == md.B
     g = np.zeros_like(x) if want_grad else None
-    loss = lib().orc_mlp_loss_grad(C.byref(md), _f(x), _f(data), labels.ctypes.data_as(C.POINTER(C.c_int32)),
+    L = f32acc_probe() if f32acc else lib()
+    loss = L.orc_mlp_loss_grad(C.byref(md), _f(x), _f(data), labels.ctypes.data_as(C.POINTER(C.c_int32)),
                                    ix.ctypes.data_as(C.POINTER(C.c_int64)), _f(g) if want_grad else None)
     return float(loss), g
 
 
-def mlp_preactivations(md: OrcModel, x: np.ndarray, data: np.ndarray, idx: Sequence[int]) -> List[np.ndarray]:
-    """Pre-ReLU values of the hidden layers, one [B, d_l] array per hidden layer."""
+def mlp_preactivations(md: OrcModel, x: np.ndarray, data: np.ndarray, idx: Sequence[int],
+                       f32acc: bool = False) -> List[np.ndarray]:
+    """Pre-ReLU values of the hidden layers, one [B, d_l] array per hidden layer.
+    f32acc=True asks the fp32-accumulation probe instead of the oracle (sensitivity only)."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     data = np.ascontiguousarray(data, dtype=np.float32)
     ix = np.ascontiguousarray(idx, dtype=np.int64)
     hidden = [md.dims[l] for l in range(1, md.n_layers)]
     z = np.zeros((md.B, max(1, sum(hidden))), np.float32)
     if hidden:
-        lib().orc_mlp_preactivations(C.byref(md), _f(x), _f(data), ix.ctypes.data_as(C.POINTER(C.c_int64)), _f(z))
+        L = f32acc_probe() if f32acc else lib()
+        L.orc_mlp_preactivations(C.byref(md), _f(x), _f(data), ix.ctypes.data_as(C.POINTER(C.c_int64)), _f(z))
     out, o = [], 0
     for d in hidden:
         out.append(z[:, o:o + d].copy())

@@ -11,6 +11,19 @@
 #include <omp.h>
 #endif
 
+/* Accumulator of the matrix-product reductions (forward products, dW, db, dA).  double is the
+ * oracle.  Compiled with -DORC_ACC_FLOAT the same loops add in fp32, in the same order: a second
+ * library that exists only so that tests can SHOW how far a result moves, and which ReLU gates
+ * change side, when nothing but the summation precision changes.  It is never what the HIP path
+ * is compared with. */
+#ifdef ORC_ACC_FLOAT
+typedef float orc_acc;
+#else
+typedef double orc_acc;
+#endif
+
+int orc_acc_bytes(void) { return (int)sizeof(orc_acc); }
+
 struct orc_state {
     int m;
     int64_t P;
@@ -111,20 +124,20 @@ int64_t orc_param_count(const orc_model* md) {
  * hidden activation to bf16 when it is produced.  zpre (optional) receives the
  * values before the ReLU. */
 static void forward_sample(const orc_model* md, const float* w_op, const float* x,
-                           float* const* act, double* acc, int q, float* const* zpre) {
+                           float* const* act, orc_acc* acc, int q, float* const* zpre) {
     int64_t off = 0;
     for (int l = 1; l <= md->n_layers; ++l) {
         const int din = md->dims[l - 1], dout = md->dims[l];
         const float* W = w_op + off;
         const float* bias = x + off + (int64_t)din * dout;
-        for (int c = 0; c < dout; ++c) acc[c] = 0.0;
+        for (int c = 0; c < dout; ++c) acc[c] = 0;
         for (int kk = 0; kk < din; ++kk) {
-            const double a = (double)act[l - 1][kk];
+            const orc_acc a = (orc_acc)act[l - 1][kk];
             const float* wr = W + (int64_t)kk * dout;
-            for (int c = 0; c < dout; ++c) acc[c] += a * (double)wr[c];
+            for (int c = 0; c < dout; ++c) acc[c] += a * (orc_acc)wr[c];
         }
         for (int c = 0; c < dout; ++c) {
-            float z = (float)(acc[c] + (double)bias[c]);
+            float z = (float)(acc[c] + (orc_acc)bias[c]);
             if (zpre && zpre[l]) zpre[l][c] = z;
             if (l < md->n_layers) {
                 z = z > 0.0f ? z : 0.0f;
@@ -185,7 +198,7 @@ float orc_mlp_loss_grad(const orc_model* md, const float* x, const float* data,
         A[l] = (float*)malloc(sizeof(float) * (size_t)B * md->dims[l]);
         dZ[l] = (l >= 1) ? (float*)malloc(sizeof(float) * (size_t)B * md->dims[l]) : NULL;
     }
-    double* acc = (double*)malloc(sizeof(double) * (size_t)(dmax > B ? dmax : B));
+    orc_acc* acc = (orc_acc*)malloc(sizeof(orc_acc) * (size_t)(dmax > B ? dmax : B));
     double* p = (double*)malloc(sizeof(double) * (size_t)C);
 
     double loss_sum = 0.0;
@@ -217,18 +230,18 @@ float orc_mlp_loss_grad(const orc_model* md, const float* x, const float* data,
             const float* W = w_op + offs[l];
             /* dW_l = A_{l-1}^T dZ_l */
             for (int kk = 0; kk < din; ++kk) {
-                for (int c = 0; c < dout; ++c) acc[c] = 0.0;
+                for (int c = 0; c < dout; ++c) acc[c] = 0;
                 for (int b = 0; b < B; ++b) {
-                    const double a = (double)A[l - 1][(int64_t)b * din + kk];
+                    const orc_acc a = (orc_acc)A[l - 1][(int64_t)b * din + kk];
                     const float* dz = dZ[l] + (int64_t)b * dout;
-                    for (int c = 0; c < dout; ++c) acc[c] += a * (double)dz[c];
+                    for (int c = 0; c < dout; ++c) acc[c] += a * (orc_acc)dz[c];
                 }
                 for (int c = 0; c < dout; ++c) gW[(int64_t)kk * dout + c] = (float)acc[c];
             }
             /* db_l = sum_b dZ_l */
             for (int c = 0; c < dout; ++c) {
-                double s = 0.0;
-                for (int b = 0; b < B; ++b) s += (double)dZ[l][(int64_t)b * dout + c];
+                orc_acc s = 0;
+                for (int b = 0; b < B; ++b) s += (orc_acc)dZ[l][(int64_t)b * dout + c];
                 gb[c] = (float)s;
             }
             /* dZ_{l-1} = (dZ_l W_l^T) .* [A_{l-1} > 0]   (derivative of ReLU at 0 is 0) */
@@ -237,8 +250,8 @@ float orc_mlp_loss_grad(const orc_model* md, const float* x, const float* data,
                     const float* dz = dZ[l] + (int64_t)b * dout;
                     for (int kk = 0; kk < din; ++kk) {
                         const float* wr = W + (int64_t)kk * dout;
-                        double s = 0.0;
-                        for (int c = 0; c < dout; ++c) s += (double)dz[c] * (double)wr[c];
+                        orc_acc s = 0;
+                        for (int c = 0; c < dout; ++c) s += (orc_acc)dz[c] * (orc_acc)wr[c];
                         float d = A[l - 1][(int64_t)b * din + kk] > 0.0f ? (float)s : 0.0f;
                         dZ[l - 1][(int64_t)b * din + kk] = q ? orc_bf16_round(d) : d;
                     }
@@ -274,7 +287,7 @@ void orc_mlp_preactivations(const orc_model* md, const float* x, const float* da
             off += nw + md->dims[l];
         }
     }
-    double* acc = (double*)malloc(sizeof(double) * (size_t)dmax);
+    orc_acc* acc = (orc_acc*)malloc(sizeof(orc_acc) * (size_t)dmax);
     float* buf[ORC_MAX_LAYERS + 1];
     for (int l = 0; l <= L; ++l) buf[l] = (float*)malloc(sizeof(float) * (size_t)md->dims[l]);
     for (int b = 0; b < B; ++b) {
@@ -315,7 +328,7 @@ int orc_next_tau(double F0, double Fl, int tau0) {
 int orc_next_tau_ex(double F0, double Fl, int tau0, int tau_prev, double gamma, int slack,
                     double lr0, double lrl, int lr_changed) {
     if (!(F0 > 0.0) || !(Fl >= 0.0) || !isfinite(F0) || !isfinite(Fl) || tau0 < 1 || tau_prev < 1) return -1;
-    if (!(gamma > 0.0) || !(gamma <= 1.0) || slack < 0) return -1;
+    if (!(gamma > 0.0) || !(gamma < 1.0) || slack < 0) return -1;   /* Sec. 4.3.1: a decay factor below 1 */
     if (!(lr0 > 0.0) || !(lrl > 0.0) || !isfinite(lr0) || !isfinite(lrl)) return -1;
     const double ratio = Fl / F0;
     const double coupling = lr0 / lrl;
@@ -500,7 +513,7 @@ double orc_loss(orc_state* s) {
         {
             float* buf[ORC_MAX_LAYERS + 1];
             for (int l = 1; l <= L; ++l) buf[l] = (float*)malloc(sizeof(float) * (size_t)md->dims[l]);
-            double* acc = (double*)malloc(sizeof(double) * (size_t)dmax);
+            orc_acc* acc = (orc_acc*)malloc(sizeof(orc_acc) * (size_t)dmax);
 #ifdef _OPENMP
 #pragma omp for schedule(static)
 #endif

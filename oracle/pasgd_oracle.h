@@ -23,7 +23,9 @@
  * rounding against torch's conversion; the refined controller against exact
  * rational arithmetic and its driver against the quadratic closed form; block
  * momentum against synchronous momentum SGD (tau=1), plain averaging
- * (beta_glob=0) and a quadratic recurrence.  No function here is "parity unpinned".
+ * (beta_glob=0) and a quadratic recurrence; the pre-activation observer against an
+ * fp64 numpy forward pass (values and layout); the index stream against a Python
+ * restatement of its chaining.  No function here is "parity unpinned".
  */
 #ifndef PASGD_ORACLE_H
 #define PASGD_ORACLE_H
@@ -53,6 +55,12 @@ typedef struct {
 typedef struct orc_state orc_state;
 
 /* --- pieces ---------------------------------------------------------------- */
+
+/* sizeof the accumulator of the matrix-product reductions: 8 in the oracle.  The same source
+ * compiled with -DORC_ACC_FLOAT (libpasgd_oracle_f32acc.so) reports 4: a sensitivity probe that
+ * adds in fp32 in the same order, used by tests only to show which results and ReLU gates move
+ * with the summation precision -- never as the reference of a comparison with the HIP path. */
+int orc_acc_bytes(void);
 
 /* SplitMix64 output function (Steele, Lea & Flood 2014; Vigna's reference). */
 uint64_t orc_mix64(uint64_t z);

@@ -71,6 +71,33 @@ def test_index_workers_are_independent_streams(orc):
     assert len(a & c) <= 2
 
 
+def _mix_py(z):
+    """SplitMix64 output function (Steele, Lea & Flood 2014), written out in Python integers."""
+    z &= M64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & M64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & M64
+    return z ^ (z >> 31)
+
+
+def test_index_chaining_matches_the_stated_formula(orc):
+    """The documented stream: idx = mix(mix(mix(seed + G (k+1)) + G (i+1)) + G (b+1)) mod N --
+    iteration first, then worker, then position in the batch, all in arithmetic modulo 2^64.
+    A transposed argument, a missing +1 or another order of the three draws fails here."""
+    g = np.random.default_rng(17)
+    cases = [(0, 0, 0, 0, 7), (2**64 - 1, 3, 2**40, 127, 50000), (11, 63, 123456789, 31, 2**31 - 1)]
+    for _ in range(300):
+        cases.append((int(g.integers(0, 2**63)) * 2 + int(g.integers(0, 2)), int(g.integers(0, 65535)),
+                      int(g.integers(0, 2**45)), int(g.integers(0, 128)), int(g.integers(1, 2**31 - 1))))
+    for seed, i, k, b, N in cases:
+        h = _mix_py(seed + GAMMA * (k + 1))
+        h = _mix_py(h + GAMMA * (i + 1))
+        h = _mix_py(h + GAMMA * (b + 1))
+        assert orc.index(seed, i, k, b, N) == h % N, (seed, i, k, b, N)
+    # the three arguments are not interchangeable
+    assert len({orc.index(5, 1, 2, 3, 10**9), orc.index(5, 2, 1, 3, 10**9), orc.index(5, 3, 2, 1, 10**9),
+                orc.index(5, 1, 3, 2, 10**9)}) == 4
+
+
 # ------------------------------------------------------------------ bf16 round
 
 def test_bf16_round_matches_torch_conversion(orc):
@@ -137,6 +164,86 @@ def test_loss_and_grad_against_definition_and_finite_differences(orc, dims):
         xm[j] -= h
         fd = (_np_loss(xp, dims, xb, yb) - _np_loss(xm, dims, xb, yb)) / (2 * h)
         assert abs(fd - grad[j]) < 5e-6 + 1e-4 * abs(fd), (j, fd, grad[j])
+
+
+def _np_preactivations(x, dims, xb, bf16):
+    """Z_l of the hidden layers in float64 numpy; with bf16 the operands (inputs, weights, hidden
+    activations) are rounded through torch's conversion, biases and sums are not."""
+    q = (lambda t: torch.from_numpy(np.asarray(t, np.float32)).to(torch.bfloat16).to(torch.float64).numpy()) \
+        if bf16 else (lambda t: np.asarray(t, np.float64))
+    a = q(xb)
+    out = []
+    layers = _unpack(x, dims)
+    for W, b in layers[:-1]:
+        z = a @ q(W) + b.astype(np.float64)
+        out.append(z)
+        a = q(np.maximum(z, 0.0).astype(np.float32))   # activations are stored as fp32, then rounded
+    return out
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("dims,B", [([7, 5, 3], 4), ([9, 6, 11, 4], 5), ([12, 8, 5, 7, 3], 3), ([6, 4], 2)])
+def test_preactivations_against_numpy_forward_values_and_layout(orc, dims, B, bf16):
+    """The observer that tells the GPU tests which ReLU gates are too close to zero to call: its
+    values against a float64 numpy forward pass, and its layout -- one [B, d_l] block per hidden
+    layer, sample-major, layers side by side in one row of d_1 + ... + d_{L-1} values.  The
+    layer widths all differ, so a transposed or shifted block cannot pass."""
+    g = np.random.default_rng(sum(dims) + B)
+    N = 30
+    data = g.standard_normal((N, dims[0])).astype(np.float32)
+    if bf16:
+        data = synth.bf16_representable(data)
+    x = (g.standard_normal(synth.param_count(dims)) * 0.4).astype(np.float32)
+    idx = g.integers(0, N, B)
+    md = orc.make_model(orc.KIND_MLP, dims, B=B, N=N, bf16=bf16)
+    got = orc.mlp_preactivations(md, x, data, idx)
+    want = _np_preactivations(x, dims, data[idx], bf16)
+    assert len(got) == len(dims) - 2 == len(want)
+    for l, (zg, zw) in enumerate(zip(got, want), start=1):
+        assert zg.shape == (B, dims[l]) and zg.dtype == np.float32
+        # layer 1 sums exact products in double on both sides: agreement to the fp32 store.  Above
+        # it a hidden activation that sits on a bf16 rounding boundary may round the other way in
+        # the fp32-stored oracle than in float64 numpy (2^-8 of one term): allow for that.
+        tol = 2e-7 if (not bf16 or l == 1) else 2e-3
+        assert np.abs(zg - zw).max() <= tol * max(1.0, np.abs(zw).max()), (l, np.abs(zg - zw).max())
+    # the gates the oracle's backward pass uses are the signs of these values: a unit whose
+    # pre-activation is positive passes its delta on, any other does not
+    if len(dims) == 3 and not bf16:
+        labels = g.integers(0, dims[-1], N).astype(np.int32)
+        _, grad = orc.mlp_loss_grad(md, x, data, labels, idx)
+        W1g = grad[:dims[0] * dims[1]].reshape(dims[0], dims[1])
+        dead = np.nonzero((got[0] <= 0).all(axis=0))[0]
+        for j in dead:
+            assert np.abs(W1g[:, j]).max() == 0.0
+
+
+def test_f32acc_probe_is_the_same_computation_in_another_precision(orc):
+    """The fp32-accumulation build of the oracle's source (a sensitivity probe, never a reference):
+    same results to fp32 summation error, not the same bits, and where its pre-activations change
+    sign against the oracle's they are tiny on both sides.  This is the evidence behind the gate
+    masks of the GPU tests: which units can fall either way is decided by |z| against the
+    summation error, nothing else."""
+    dims, B, N = [300, 200, 60, 10], 16, 200
+    g = np.random.default_rng(3)
+    data = g.standard_normal((N, dims[0])).astype(np.float32)
+    labels = g.integers(0, dims[-1], N).astype(np.int32)
+    x = synth.init_params(9, dims)
+    idx = g.integers(0, N, B)
+    md = orc.make_model(orc.KIND_MLP, dims, B=B, N=N)
+    z64 = orc.mlp_preactivations(md, x, data, idx)
+    z32 = orc.mlp_preactivations(md, x, data, idx, f32acc=True)
+    l64, g64 = orc.mlp_loss_grad(md, x, data, labels, idx)
+    l32, g32 = orc.mlp_loss_grad(md, x, data, labels, idx, f32acc=True)
+    assert not np.array_equal(g64, g32)
+    assert abs(l64 - l32) < 1e-5 * abs(l64)
+    for a, b in zip(z64, z32):
+        rms = float(np.sqrt(np.mean(a.astype(np.float64) ** 2)))
+        assert np.abs(a - b).max() < 2e-5 * rms
+        flipped = (a > 0) != (b > 0)
+        assert np.abs(a[flipped]).max(initial=0.0) < 2e-5 * rms
+    # with no gate between the two sides the gradients agree to summation error
+    if not any(((a > 0) != (b > 0)).any() for a, b in zip(z64, z32)):
+        assert np.abs(g64 - g32).max() < 1e-4 * np.abs(g64).max()
 
 
 def _torch_params(x, dims, dtype=torch.float64):

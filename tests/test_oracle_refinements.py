@@ -40,7 +40,7 @@ def test_candidate_taken_only_if_strictly_smaller(orc):
     # slack s: the candidate must satisfy c + s < tau_prev
     assert orc.next_tau_ex(1.0, 0.25, 20, 12, 0.5, 1) == 10  # 11 < 12
     assert orc.next_tau_ex(1.0, 0.25, 20, 11, 0.5, 1) == 6   # 11 < 11 fails: ceil(5.5)
-    for bad in [dict(gamma=0.0), dict(gamma=1.5), dict(slack=-1), dict(lr0=0.0), dict(lrl=-1.0)]:
+    for bad in [dict(gamma=0.0), dict(gamma=1.0), dict(gamma=1.5), dict(slack=-1), dict(lr0=0.0), dict(lrl=-1.0)]:
         kw = dict(gamma=0.5, slack=0, lr0=1.0, lrl=1.0)
         kw.update(bad)
         assert orc.next_tau_ex(1.0, 0.5, 20, 20, **kw) < 0
