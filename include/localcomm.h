@@ -64,8 +64,8 @@ typedef enum { LC_SAMPLE_REPLACEMENT = 0, LC_SAMPLE_PARTITION = 1 } lc_sampler;
  *                 weights and momentum fp32); the dataset is then bf16 too.
  *   sampler     : LC_SAMPLE_REPLACEMENT draws every sample with replacement from the
  *                 whole set (the index stream documented at lc_init).
- *                 LC_SAMPLE_PARTITION follows Sec. 5.1 ("each worker machine is assigned
- *                 with a partition which will be randomly shuffled after every epoch"):
+ *                 LC_SAMPLE_PARTITION follows the data handling of Sec. 5.1 (every worker owns a
+ *                 fixed share of the training set and reshuffles that share once per epoch):
  *                 worker i of m owns samples [floor(i N / m), floor((i+1) N / m)); an epoch
  *                 is S = floor(floor(N / m) / B) iterations; in epoch e = k / S the worker
  *                 walks a pseudo-random permutation of its partition, B positions per
@@ -100,8 +100,8 @@ int64_t lc_param_count(const lc_model* model);
 /* Distance in floats between consecutive rows of X and of V. */
 int64_t lc_row_stride(int64_t P);
 
-/* Create a run of m workers with P parameters each (Sec. 2, PASGD: "m worker
- * nodes ... all workers start at the same initial point").  seed keys the
+/* Create a run of m workers with P parameters each (Sec. 2, PASGD: the m workers
+ * begin from one common model x_1).  seed keys the
  * mini-batch index stream: sample b of worker i at local iteration k is
  *   idx = mix(mix(mix(seed + G (k+1)) + G (i+1)) + G (b+1)) mod N,
  * mix = SplitMix64 output function, G = 0x9E3779B97F4A7C15 (sampling with
@@ -265,7 +265,7 @@ int adacomm_next_tau(double F0, double Fl, int tau0);
  *   c = ceil( sqrt( (lr0 / lrl) * Fl / F0 ) * tau0 )      (Sec. 4.3.2, practical coupling; lr0 = lrl
  *                                                           gives the basic rule)
  * Saturation refinement (Sec. 4.3.1): c is taken only if c + slack < tau_prev,
- * otherwise the period becomes ceil(gamma * tau_prev), 0 < gamma <= 1 (the paper uses 1/2).  At the
+ * otherwise the period becomes ceil(gamma * tau_prev), 0 < gamma < 1 (the paper uses 1/2).  At the
  * first decision after a learning-rate change (lr_changed != 0) c is taken as it is: the coupling
  * exists to let the period grow there.  Evaluated in IEEE double in this order: Fl/F0, lr0/lrl,
  * their product, sqrt, times tau0, ceil; gamma * tau_prev, ceil.  Returns the period >= 1 or
@@ -306,7 +306,10 @@ int lc_grid_search_tau0(lc_handle* h, const int32_t* taus, int n, int64_t K, dou
  * (counted from 0 at lc_init, increasing) the rate is lr_val[j].  Changes take effect at
  * averaging steps only; with postpone_lr != 0 a due change waits until the period has reached 1
  * (Sec. 4.3.2: the period is brought down to 1 first, the rate is lowered only then).  sched_lr (host, capacity cap) receives the rate in force after each decision.
- * F_0 is always evaluated, so interval >= 1 is required. */
+ * F_0 is always evaluated, so interval >= 1 is required.  The call begins a schedule: F_0 and
+ * lr0 are taken at entry and the period starts at tau0.  It is not a resume point (a caller that
+ * continues an earlier schedule keeps F_0, lr0 and the period itself and decides with
+ * adacomm_next_tau_ex, which takes all of them as arguments). */
 int lc_run_ex(lc_handle* h, int64_t K, int tau0, int64_t interval, int refine, double gamma, int slack,
               int n_lr, const int64_t* lr_at, const float* lr_val, int postpone_lr,
               int64_t* sched_k, int32_t* sched_tau, float* sched_lr, int cap, int32_t* n_sched,
@@ -318,8 +321,8 @@ int lc_run_ex(lc_handle* h, int64_t K, int tau0, int64_t interval, int refine, d
  * lc_set_state with equal rows, or after lc_average), sets the global buffer u = 0 and clears the
  * local buffers.  While the mode is on, lc_average() (also inside lc_run / lc_run_ex) computes
  *     G = (x_sync - x_bar) / lr ;  u <- beta_glob u + G ;  x_sync <- x_sync - lr u
- * writes x_sync to every row and clears every worker's local momentum buffer ("we restart
- * momentum SGD on local models after every averaging step"; the paper uses beta_glob = 0.3 with
+ * writes x_sync to every row and clears every worker's local momentum buffer (Sec. 5.3.1: local
+ * momentum SGD begins afresh after each averaging step; the paper uses beta_glob = 0.3 with
  * local momentum 0.9).  G is read as the averaged model change per unit learning rate, which for
  * plain local SGD is the paper's accumulated mean gradient.  u and x_sync live in the scratch
  * buffer.  lc_block_momentum_end() returns to plain averaging.  lc_get_block_momentum() copies
@@ -357,9 +360,15 @@ int lc_get_last_indices(lc_handle* h, int32_t* idx_host);
  * lc_timing_read() synchronises and returns the number of launches and their
  * summed duration since lc_timing_begin().  which: 0 = backward+update kernel,
  * 1 = forward kernel, 2 = averaging kernel, 3 = update-from-gradient kernel,
- * 4 = fused update+average kernel. */
+ * 4 = fused update+average kernel.  If an event could not be created or recorded since
+ * lc_timing_begin(), lc_timing_read() returns LC_ERR_HIP instead of incomplete figures. */
 int lc_timing_begin(lc_handle* h, int which);
 int lc_timing_read(lc_handle* h, int64_t* launches, double* total_ms);
+/* Narrows class 0 to the launches that work on layer `layer` (1..L; 0 = every layer) and to one
+ * kernel (0 = any, 1 = row-owner backward kernel, 2 = first-layer kernel that also runs the next
+ * forward pass, 3 = tile-owner kernel of tau = 1, 4 = fused last-layer kernel, 5 = resident step
+ * kernel, which counts as layer 0).  Call after lc_timing_begin(), which resets both to 0. */
+int lc_timing_select(lc_handle* h, int layer, int kernel);
 
 #ifdef __cplusplus
 }

@@ -20,6 +20,8 @@ KIND_QUAD, KIND_MLP = 0, 1
 GEMM_FP32, GEMM_BF16 = 0, 1
 SAMPLE_REPLACEMENT, SAMPLE_PARTITION = 0, 1
 TIME_BWD, TIME_FWD, TIME_AVG, TIME_UPD, TIME_UPDAVG, TIME_NONE = 0, 1, 2, 3, 4, -1
+# kernels of class TIME_BWD, for lc_timing_select()
+BWD_ANY, BWD_ROW_OWNER, BWD_FIRST_LAYER, BWD_TILE_OWNER, BWD_HEAD, BWD_RESIDENT = 0, 1, 2, 3, 4, 5
 
 
 class LcModel(C.Structure):
@@ -132,6 +134,8 @@ def lib() -> C.CDLL:
     L.lc_get_last_indices.argtypes = [vp, vp]
     L.lc_timing_begin.restype = C.c_int
     L.lc_timing_begin.argtypes = [vp, C.c_int]
+    L.lc_timing_select.restype = C.c_int
+    L.lc_timing_select.argtypes = [vp, C.c_int, C.c_int]
     L.lc_timing_read.restype = C.c_int
     L.lc_timing_read.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
     _lib = L
@@ -401,6 +405,9 @@ class LocalSGD:
 
     def timing_begin(self, which: int) -> None:
         self._check(self._L.lc_timing_begin(self._h, int(which)), "lc_timing_begin")
+
+    def timing_select(self, layer: int, kernel: int) -> None:
+        self._check(self._L.lc_timing_select(self._h, int(layer), int(kernel)), "lc_timing_select")
 
     def timing_read(self) -> Tuple[int, float]:
         n, ms = C.c_int64(0), C.c_double(0.0)

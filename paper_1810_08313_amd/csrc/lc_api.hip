@@ -24,22 +24,35 @@ using namespace lc;
 
 namespace lc {
 
-void timing_start(lc_handle* h, int which) {
-    if (h->timing_which != which) return;
+// does this launch belong to what lc_timing_begin() / lc_timing_select() asked for?
+static bool timing_wanted(const lc_handle* h, int which, int layer, int kernel) {
+    if (h->timing_which != which) return false;
+    if (h->timing_layer != 0 && layer != h->timing_layer) return false;
+    return h->timing_kernel == 0 || kernel == h->timing_kernel;
+}
+
+void timing_start(lc_handle* h, int which, int layer, int kernel) {
+    if (!timing_wanted(h, which, layer, kernel)) return;
     if (h->ev_used + 2 > h->ev_pool.size()) {
         for (int i = 0; i < 256; ++i) {
             hipEvent_t e;
-            if (hipEventCreate(&e) != hipSuccess) return;
+            const hipError_t rc = hipEventCreate(&e);
+            if (rc != hipSuccess) {   // reported by lc_timing_read(): a count that silently stops would be wrong
+                h->timing_err = static_cast<int>(rc);
+                return;
+            }
             h->ev_pool.push_back(e);
         }
     }
-    (void)hipEventRecord(h->ev_pool[h->ev_used], h->stream);
+    const hipError_t rc = hipEventRecord(h->ev_pool[h->ev_used], h->stream);
+    if (rc != hipSuccess) h->timing_err = static_cast<int>(rc);
 }
 
-void timing_stop(lc_handle* h, int which) {
-    if (h->timing_which != which) return;
+void timing_stop(lc_handle* h, int which, int layer, int kernel) {
+    if (!timing_wanted(h, which, layer, kernel)) return;
     if (h->ev_used + 2 > h->ev_pool.size()) return;
-    (void)hipEventRecord(h->ev_pool[h->ev_used + 1], h->stream);
+    const hipError_t rc = hipEventRecord(h->ev_pool[h->ev_used + 1], h->stream);
+    if (rc != hipSuccess) h->timing_err = static_cast<int>(rc);
     h->ev_used += 2;
 }
 
@@ -398,6 +411,8 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     h->res_spin_limit = 400000;   // several hundred milliseconds of polling
     h->timing_which = kTimeNone;
     h->ev_used = 0;
+    h->timing_err = 0;
+    h->timing_layer = h->timing_kernel = 0;
     h->bm_on = false;
     h->bm_beta = 0.f;
     h->v_cleared = false;
@@ -669,7 +684,7 @@ int adacomm_next_tau(double F0, double Fl, int tau0) {
 int adacomm_next_tau_ex(double F0, double Fl, int tau0, int tau_prev, double gamma, int slack, double lr0,
                         double lrl, int lr_changed) {
     if (!(F0 > 0.0) || !(Fl >= 0.0) || !isfinite(F0) || !isfinite(Fl) || tau0 < 1 || tau_prev < 1) return LC_ERR_ARG;
-    if (!(gamma > 0.0) || !(gamma <= 1.0) || slack < 0) return LC_ERR_ARG;
+    if (!(gamma > 0.0) || !(gamma < 1.0) || slack < 0) return LC_ERR_ARG;   // Sec. 4.3.1: a decay factor below 1
     if (!(lr0 > 0.0) || !(lrl > 0.0) || !isfinite(lr0) || !isfinite(lrl)) return LC_ERR_ARG;
     volatile double ratio = Fl / F0;
     volatile double coupling = lr0 / lrl;
@@ -959,6 +974,16 @@ int lc_get_last_indices(lc_handle* h, int32_t* idx_host) {
 int lc_timing_begin(lc_handle* h, int which) {
     if (!h || which < kTimeNone || which > kTimeUpdAvg) return LC_ERR_ARG;
     h->timing_which = which;
+    h->timing_layer = h->timing_kernel = 0;
+    h->ev_used = 0;
+    h->timing_err = 0;
+    return LC_OK;
+}
+
+int lc_timing_select(lc_handle* h, int layer, int kernel) {
+    if (!h || layer < 0 || layer > LC_MAX_LAYERS || kernel < kBwdAny || kernel > kBwdResident) return LC_ERR_ARG;
+    h->timing_layer = layer;
+    h->timing_kernel = kernel;
     h->ev_used = 0;
     return LC_OK;
 }
@@ -967,6 +992,12 @@ int lc_timing_read(lc_handle* h, int64_t* launches, double* total_ms) {
     if (!h || !launches || !total_ms) return LC_ERR_ARG;
     if (!h->attached) return LC_ERR_STATE;
     LC_HIP(h, hipStreamSynchronize(h->stream));
+    if (h->timing_err) {   // an event could not be created or recorded: the figures would be incomplete
+        h->last_hip = h->timing_err;
+        h->timing_err = 0;
+        h->ev_used = 0;
+        return LC_ERR_HIP;
+    }
     double sum = 0.0;
     for (size_t i = 0; i + 1 < h->ev_used; i += 2) {
         float ms = 0.f;

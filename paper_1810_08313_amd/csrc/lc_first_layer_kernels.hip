@@ -381,10 +381,10 @@ hipError_t launch_first_layer(lc_handle* h) {
     a.n_chunks = g.d_out / kColChunk;
     a.total_blocks = static_cast<int64_t>(S.G) * a.n_chunks;
     const unsigned grid = static_cast<unsigned>((a.total_blocks + kXcds - 1) / kXcds * kXcds);
-    timing_start(h, kTimeBwd);
+    timing_start(h, kTimeBwd, 1, kBwdFirstLayer);
     const hipError_t e = bf16 ? launch_fl<bf16_t>(a, S.Bp / 16, h->stream_weights, grid, h->stream)
                               : launch_fl<float>(a, S.Bp / 16, h->stream_weights, grid, h->stream);
-    timing_stop(h, kTimeBwd);
+    timing_stop(h, kTimeBwd, 1, kBwdFirstLayer);
     return e;
 }
 

@@ -28,6 +28,8 @@ inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 
 // Kernel classes for lc_timing_begin().
 enum TimedKernel { kTimeBwd = 0, kTimeFwd = 1, kTimeAvg = 2, kTimeUpd = 3, kTimeUpdAvg = 4, kTimeNone = -1 };
+// Kernels of the backward class, for lc_timing_select().
+enum BwdKernel { kBwdAny = 0, kBwdRowOwner = 1, kBwdFirstLayer = 2, kBwdTileOwner = 3, kBwdHead = 4, kBwdResident = 5 };
 
 // One layer of the per-replica MLP as the kernels see it.
 struct LayerGeom {
@@ -118,6 +120,8 @@ struct lc_handle {
     int timing_which;
     std::vector<hipEvent_t> ev_pool;
     size_t ev_used;
+    int timing_layer, timing_kernel;   // lc_timing_select(): backward-class launches of this layer / kernel only (0 = all)
+    int timing_err;         // hipError_t of an event that could not be created or recorded since lc_timing_begin
 };
 
 namespace lc {
@@ -152,7 +156,8 @@ hipError_t probe_block_placement(lc_handle* h);   // synchronises the stream onc
 hipError_t launch_resident(lc_handle* h, int slot0, int n_steps, int period);  // the steps gathered into slots slot0 .. slot0+n_steps-1
 
 // timing helpers used by the launchers
-void timing_start(lc_handle* h, int which);
-void timing_stop(lc_handle* h, int which);
+// (layer, kernel: what a backward-class launch works on, for lc_timing_select(); 0 elsewhere)
+void timing_start(lc_handle* h, int which, int layer = 0, int kernel = 0);
+void timing_stop(lc_handle* h, int which, int layer = 0, int kernel = 0);
 
 }  // namespace lc

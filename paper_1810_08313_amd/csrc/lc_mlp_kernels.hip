@@ -1329,7 +1329,7 @@ hipError_t launch_head(lc_handle* h) {
     a.vec = (g.d_out % 4 == 0 && g.w_off % 4 == 0) ? 1 : 0;
     a.stream = 0;   // the last layer is small: keep it cached
     const dim3 grid(S.G), block(512);
-    timing_start(h, kTimeBwd);
+    timing_start(h, kTimeBwd, L, kBwdHead);
     const int nt = S.Bp / 16;
     if (bf16) {
         if (nt == 2) hipLaunchKernelGGL((head_kernel<bf16_t, 2>), grid, block, 0, h->stream, a);
@@ -1340,7 +1340,7 @@ hipError_t launch_head(lc_handle* h) {
         else if (nt == 4) hipLaunchKernelGGL((head_kernel<float, 4>), grid, block, 0, h->stream, a);
         else hipLaunchKernelGGL((head_kernel<float, 8>), grid, block, 0, h->stream, a);
     }
-    timing_stop(h, kTimeBwd);
+    timing_stop(h, kTimeBwd, L, kBwdHead);
     return hipGetLastError();
 }
 
@@ -1409,18 +1409,18 @@ hipError_t launch_backward(lc_handle* h, int l, bool da_only) {
     }
     a.total_blocks = static_cast<int64_t>(S.G) * a.n_row_blocks * a.col_split;
     const unsigned grid = xcd_grid(a.total_blocks);
-    timing_start(h, kTimeBwd);
+    // (same conditions as the tile-owner kernel that follows; the columns are not shared out here)
+    if (da_only && (l < 2 || !a.vec || g.d_out % kColChunk != 0 || !a.stream)) return hipErrorInvalidValue;
+    timing_start(h, kTimeBwd, l, kBwdRowOwner);
     hipError_t e;
     if (da_only) {
-        // (same conditions as the tile-owner kernel that follows; the columns are not shared out here)
-        if (l < 2 || !a.vec || g.d_out % kColChunk != 0 || !a.stream) return hipErrorInvalidValue;
         e = bf16 ? launch_bwd_da_only<bf16_t>(a, S.Bp / 16, grid, h->stream)
                  : launch_bwd_da_only<float>(a, S.Bp / 16, grid, h->stream);
     } else {
         e = bf16 ? launch_bwd_wm<bf16_t>(a, S.Bp / 16, grid, h->stream)
                  : launch_bwd_wm<float>(a, S.Bp / 16, grid, h->stream);
     }
-    timing_stop(h, kTimeBwd);
+    timing_stop(h, kTimeBwd, l, kBwdRowOwner);
     return e;
 }
 

@@ -779,7 +779,7 @@ hipError_t launch_resident1(lc_handle* h, int slot0, int n_steps, int period) {
     if (period < 0 || (period > 0 && (n_steps % period != 0 || !h->res_avx || S.G > 256))) return hipErrorInvalidValue;
     if (S.Bp != 32 && S.Bp != 64) return hipErrorInvalidValue;
     if (a.dp0 > kResMaxD1 || a.d1 > 16) return hipErrorInvalidValue;
-    timing_start(h, kTimeBwd);
+    timing_start(h, kTimeBwd, 0, kBwdResident);
     const dim3 grid(static_cast<unsigned>(S.G)), block(kResThreads);
     if (S.Bp == 32) {
         if (bf16) hipLaunchKernelGGL((resident1_kernel<bf16_t, 2>), grid, block, 0, h->stream, a);
@@ -790,7 +790,7 @@ hipError_t launch_resident1(lc_handle* h, int slot0, int n_steps, int period) {
     }
     h->loss_parts_train = 1;
     if (period > 0) h->res_garrivals += static_cast<unsigned>(n_steps / period) * static_cast<unsigned>(S.G);
-    timing_stop(h, kTimeBwd);
+    timing_stop(h, kTimeBwd, 0, kBwdResident);
     return hipGetLastError();
 }
 
@@ -852,7 +852,7 @@ hipError_t launch_resident(lc_handle* h, int slot0, int n_steps, int period) {
     if (total > 256 || a.G > 64 || !h->res_a1x) return hipErrorInvalidValue;
     const unsigned grid = static_cast<unsigned>((total + kXcds - 1) / kXcds * kXcds);
     if (S.Bp != 32 && S.Bp != 64) return hipErrorInvalidValue;
-    timing_start(h, kTimeBwd);
+    timing_start(h, kTimeBwd, 0, kBwdResident);
     if (S.Bp == 32) {
         if (bf16) hipLaunchKernelGGL((resident_kernel<bf16_t, 2>), dim3(grid), dim3(kResThreads), 0, h->stream, a);
         else hipLaunchKernelGGL((resident_kernel<float, 2>), dim3(grid), dim3(kResThreads), 0, h->stream, a);
@@ -863,7 +863,7 @@ hipError_t launch_resident(lc_handle* h, int slot0, int n_steps, int period) {
     h->loss_parts_train = 1;
     h->res_arrivals += static_cast<unsigned>(n_steps) * static_cast<unsigned>(a.NB);   // wraps like the counters do
     if (period > 0) h->res_garrivals += static_cast<unsigned>(n_steps / period) * static_cast<unsigned>(total);
-    timing_stop(h, kTimeBwd);
+    timing_stop(h, kTimeBwd, 0, kBwdResident);
     return hipGetLastError();
 }
 

@@ -229,10 +229,10 @@ hipError_t launch_sync_layer(lc_handle* h, int l) {
     a.n_cc = g.d_out / kColChunk;
     a.total_blocks = static_cast<int64_t>(a.n_row_blocks) * a.n_cc;
     const unsigned grid = static_cast<unsigned>((a.total_blocks + kXcds - 1) / kXcds * kXcds);
-    timing_start(h, kTimeBwd);
+    timing_start(h, kTimeBwd, l, kBwdTileOwner);
     const hipError_t e = bf16 ? launch_sync1<bf16_t>(a, S.Bp / 16, grid, h->stream)
                               : launch_sync1<float>(a, S.Bp / 16, grid, h->stream);
-    timing_stop(h, kTimeBwd);
+    timing_stop(h, kTimeBwd, l, kBwdTileOwner);
     return e;
 }
 
