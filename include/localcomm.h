@@ -46,7 +46,8 @@ typedef enum {
     LC_ERR_NONFINITE = -7,  /* the evaluated loss is not finite */
     LC_ERR_UNSUPPORTED = -8, /* shape outside what the kernels handle */
     LC_ERR_SYNC = -9,        /* a replica-wide barrier of the resident step kernel timed out */
-    LC_ERR_PLACEMENT = -10   /* a workgroup of the resident step kernel ran on another XCD than the probe predicted */
+    LC_ERR_PLACEMENT = -10,  /* a workgroup of the resident step kernel ran on another XCD than the probe predicted */
+    LC_ERR_TOO_LARGE = -11   /* more parameters than the library's static scratch holds (LC_STATIC_MAX_PARAMS) */
 } lc_status;
 
 typedef enum { LC_KIND_QUAD = 0, LC_KIND_MLP = 1 } lc_kind;
@@ -330,6 +331,31 @@ int lc_run_ex(lc_handle* h, int64_t K, int tau0, int64_t interval, int refine, d
 int lc_block_momentum_begin(lc_handle* h, float beta_glob);
 int lc_block_momentum_end(lc_handle* h);
 int lc_get_block_momentum(lc_handle* h, float* u_host, float* x_sync_host);
+
+/* The block-momentum averaging step for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arithmetic and same
+ * kernel as lc_average() while block momentum is on, but no handle, no workspace and no allocation
+ * of any kind (no hipMalloc / hipFree, no host allocation, no memset node: clearing is done by small
+ * fill kernels): the global buffer u and the last synchronised model x_sync live in an array of
+ * 2 * LC_STATIC_MAX_PARAMS floats inside the library's device image, which every GPU the library
+ * runs on holds until the process ends.
+ *   X          : device fp32 [m, row_stride], 256-byte aligned; row_stride a multiple of 4 floats,
+ *                >= P; entries of a row beyond P must be zero and stay zero.
+ *   V          : device fp32 [m, row_stride], 256-byte aligned, or NULL: the workers' local momentum
+ *                buffers, cleared by both forms of the call (Sec. 5.3.1: local momentum restarts).
+ *   begin != 0 : the rows of X are synchronised; record row 0 as x_sync, set u = 0.  X is not changed.
+ *                (What lc_block_momentum_begin() does.)
+ *   begin == 0 : x_bar = mean of the rows; G = (x_sync - x_bar) / lr; u <- beta_glob u + G;
+ *                x_sync <- x_sync - lr u; every row of X <- x_sync.
+ * Asynchronous on `stream`.  All calls on one GPU share the one array, which keeps what the last
+ * call left there: one block-momentum run per GPU at a time, a new run starts with begin != 0, and
+ * calls that overlap on one GPU (other streams, other threads) race.  The array's address is looked
+ * up once per device, at the first call on that device.
+ * Errors: LC_ERR_ARG (null X, m < 1, P < 1, bad stride, lr <= 0, beta_glob outside [0, 1)),
+ * LC_ERR_ALIGN, LC_ERR_TOO_LARGE (P > LC_STATIC_MAX_PARAMS), LC_ERR_HIP. */
+#define LC_STATIC_MAX_PARAMS 4456448
+int lc_average_block_momentum_static(float* X, float* V, int m, int64_t P, int64_t row_stride, float lr,
+                                     float beta_glob, int begin, void* stream);
 
 /* One (momentum-)SGD update of every worker from explicit gradients G (device,
  * fp32 [m, lc_row_stride(P)], 256-byte aligned): g <- G + wd x; v <- beta v + g;

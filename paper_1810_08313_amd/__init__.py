@@ -12,7 +12,7 @@ from .binding import (  # noqa: F401
     LcModel,
     LocalSGD,
     adacomm_next_tau,
-    adacomm_next_tau_ex,
+    adacomm_next_tau_ex, average_block_momentum_static, STATIC_MAX_PARAMS,
     lc_param_count,
     lc_row_stride,
     lib,

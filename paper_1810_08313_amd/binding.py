@@ -134,6 +134,9 @@ def lib() -> C.CDLL:
     L.lc_get_last_indices.argtypes = [vp, vp]
     L.lc_timing_begin.restype = C.c_int
     L.lc_timing_begin.argtypes = [vp, C.c_int]
+    L.lc_average_block_momentum_static.restype = C.c_int
+    L.lc_average_block_momentum_static.argtypes = [vp, vp, C.c_int, C.c_int64, C.c_int64, C.c_float, C.c_float,
+                                                   C.c_int, vp]
     L.lc_timing_select.restype = C.c_int
     L.lc_timing_select.argtypes = [vp, C.c_int, C.c_int]
     L.lc_timing_read.restype = C.c_int
@@ -174,6 +177,21 @@ def adacomm_next_tau(F0: float, Fl: float, tau0: int) -> int:
     if t < 0:
         raise LcError(t, "adacomm_next_tau")
     return t
+
+
+STATIC_MAX_PARAMS = 4456448
+
+
+def average_block_momentum_static(X, V, P: int, lr: float, beta_glob: float, begin: bool, stream=None) -> None:
+    """lc_average_block_momentum_static on torch device tensors X (and V or None) of shape
+    [m, row_stride]; raises LcError on a negative status."""
+    import torch
+    assert X.dtype == torch.float32 and X.is_contiguous() and X.dim() == 2
+    st = (stream or torch.cuda.current_stream(X.device)).cuda_stream
+    rc = lib().lc_average_block_momentum_static(X.data_ptr(), V.data_ptr() if V is not None else None, int(X.shape[0]),
+                                                int(P), int(X.shape[1]), float(lr), float(beta_glob), int(bool(begin)), st)
+    if rc != 0:
+        raise LcError(rc, "lc_average_block_momentum_static")
 
 
 def adacomm_next_tau_ex(F0: float, Fl: float, tau0: int, tau_prev: int, gamma: float = 0.5, slack: int = 0,

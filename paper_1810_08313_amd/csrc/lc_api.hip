@@ -324,6 +324,7 @@ const char* lc_strerror(int status) {
         case LC_ERR_UNSUPPORTED: return "shape not supported";
         case LC_ERR_SYNC: return "replica barrier timed out in the resident step kernel";
         case LC_ERR_PLACEMENT: return "resident step kernel: a workgroup ran on another XCD than the placement probe predicted";
+        case LC_ERR_TOO_LARGE: return "more parameters than the library's static scratch holds";
         default: return "unknown status";
     }
 }

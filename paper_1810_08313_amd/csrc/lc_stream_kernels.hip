@@ -4,7 +4,14 @@
 // objective.  Every thread owns one 16-byte column of the [m, Ps] matrix, so
 // the reduction over the m axis happens in registers and each row is read and
 // written in fully coalesced 1 KiB wavefront segments.
+#include <mutex>
+
 #include "lc_internal.h"
+
+// Scratch of lc_average_block_momentum_static(): u in the first half, x_sync in the second.  In
+// host code this name is only a handle for hipGetSymbolAddress(); the device address is looked up
+// once per device (static_scratch() below) and that pointer is what kernels and copies get.
+static __device__ __align__(256) float scratch[2 * LC_STATIC_MAX_PARAMS];
 
 namespace lc {
 
@@ -325,6 +332,47 @@ hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* 
     return hipGetLastError();
 }
 
+namespace {
+
+// Start of a block-momentum run in the static scratch: u = 0, x_sync = row 0 of X, V = 0.
+__global__ __launch_bounds__(kThreads) void static_begin_kernel(const float* X, float* V, float* u, float* xs, int m,
+                                                                int64_t Ps, int64_t cols) {
+    const int64_t col = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
+    if (col >= cols) return;
+    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+    *reinterpret_cast<float4*>(u + col) = zero;
+    *reinterpret_cast<float4*>(xs + col) = *reinterpret_cast<const float4*>(X + col);
+    if (V)
+        for (int i = 0; i < m; ++i) *reinterpret_cast<float4*>(V + static_cast<int64_t>(i) * Ps + col) = zero;
+}
+
+__global__ __launch_bounds__(kThreads) void zero_rows_kernel(float* V, int m, int64_t Ps, int64_t cols) {
+    const int64_t col = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
+    if (col >= cols) return;
+    for (int i = 0; i < m; ++i)
+        *reinterpret_cast<float4*>(V + static_cast<int64_t>(i) * Ps + col) = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+float* g_static_ptr[kMaxDevices];   // device address of `scratch` on each device, once looked up
+
+// Device address of the static scratch on the current device (each GPU holds its own copy).
+int static_scratch(float** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LC_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LC_ERR_HIP;
+        g_static_ptr[dev] = static_cast<float*>(p);
+    }
+    *out = g_static_ptr[dev];
+    return LC_OK;
+}
+
+}  // namespace
+
 hipError_t launch_broadcast_xbar(lc_handle* h) {
     const int64_t chunk = h->avg_chunk_floats;
     for (int64_t lo = 0; lo < h->Ps; lo += chunk) {
@@ -369,3 +417,30 @@ hipError_t launch_quad_loss(lc_handle* h, int* n_partial) {
 }
 
 }  // namespace lc
+
+extern "C" int lc_average_block_momentum_static(float* X, float* V, int m, int64_t P, int64_t row_stride, float lr,
+                                                float beta_glob, int begin, void* stream) {
+    using namespace lc;
+    if (!X || m < 1 || m > 65535 || P < 1 || row_stride < P || row_stride % 4 != 0) return LC_ERR_ARG;
+    if (!(lr > 0.f) || !(beta_glob >= 0.f) || !(beta_glob < 1.f)) return LC_ERR_ARG;
+    if (P > LC_STATIC_MAX_PARAMS) return LC_ERR_TOO_LARGE;
+    if ((reinterpret_cast<uintptr_t>(X) & 255u) != 0 || (reinterpret_cast<uintptr_t>(V) & 255u) != 0) return LC_ERR_ALIGN;
+    float* base = nullptr;
+    const int rc = static_scratch(&base);
+    if (rc != LC_OK) return rc;
+    float* u = base;
+    float* xs = base + LC_STATIC_MAX_PARAMS;
+    const int64_t cols = round_up(P, 4);   // (<= row_stride, and <= LC_STATIC_MAX_PARAMS, a multiple of 4)
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const dim3 grid(blocks_for(cols / 4)), block(kThreads);
+    if (begin) {
+        hipLaunchKernelGGL(static_begin_kernel, grid, block, 0, st, X, V, u, xs, m, row_stride, cols);
+    } else {
+        const BlockMomentum bm{u, xs, beta_glob, lr, 1.f / lr};
+        const DeferredUpdate du{nullptr, lr};
+        hipLaunchKernelGGL(average_kernel, grid, block, 0, st, X, X, static_cast<float*>(nullptr), m, row_stride, bm,
+                           du, static_cast<int64_t>(0), cols);
+        if (V) hipLaunchKernelGGL(zero_rows_kernel, grid, block, 0, st, V, m, row_stride, cols);
+    }
+    return hipGetLastError() == hipSuccess ? LC_OK : LC_ERR_HIP;
+}
