@@ -52,7 +52,7 @@ def test_weight_drift_widens_the_bound_and_masks_accumulate(orc):
     md = orc.make_model(orc.KIND_MLP, dims, B=B, N=N, bf16=True)
     idx = batch_indices(orc, md, 4, 0, 0, 1)
     fresh = undecided_gates(orc, md, x, data, idx)
-    moved = (x + np.float32(2e-3) * synth.init_params(5, dims)).astype(np.float32)   # as after a few steps
+    moved = (x + np.float32(0.5) * synth.init_params(5, dims)).astype(np.float32)   # far from where the sides agreed
     drift = undecided_gates(orc, md, moved, data, idx, x0=x)
     again = undecided_gates(orc, md, moved, data, idx)
     for l in again:
