@@ -1108,6 +1108,17 @@ def test_shared_model_block_order_against_oracle(pkg, orc, bf16, m, d0, d1, tau,
         assert np.array_equal(X.view(np.uint32), Xp.view(np.uint32))
         assert np.array_equal(V.view(np.uint32), Vp.view(np.uint32))
         plain.close()
+        # ... and those unforced iterations against the oracle: the buffers at the bar outside the units
+        # whose gate is open to summation order or, from the second iteration on, to weights that
+        # have drifted across a bf16 rounding boundary
+        masks = UnitMasks()
+        for j in range(K // tau):
+            _ref_steps(orc, ref, 11, tau, masks, fresh=j == 0)
+            ref.average()
+        _say(f"  unforced: masked units (any worker) { {l: int(u.sum()) for l, u in masks.union(range(m)).items()} }")
+        _assert_close(X[0], ref.X[0], dims, tol, "unforced: X", _xmask(ref, masks.union(range(m))), over="skip")
+        for i in range(m):
+            _assert_close(V[i], ref.V[i], dims, tol, f"unforced: V[{i}]", masks.of(i), over="skip")
     run.close()
 
 
