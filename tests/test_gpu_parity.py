@@ -1117,8 +1117,13 @@ def test_shared_model_block_order_against_oracle(pkg, orc, bf16, m, d0, d1, tau,
             ref.average()
         _say(f"  unforced: masked units (any worker) { {l: int(u.sum()) for l, u in masks.union(range(m)).items()} }")
         _assert_close(X[0], ref.X[0], dims, tol, "unforced: X", _xmask(ref, masks.union(range(m))), over="skip")
+        # (a buffer passes through the gates of every layer above its own: only the blocks with no
+        # undecided unit above them can be held to the bar after unforced steps; the forced periods
+        # above hold all of them)
         for i in range(m):
-            _assert_close(V[i], ref.V[i], dims, tol, f"unforced: V[{i}]", masks.of(i), over="skip")
+            mk = masks.of(i)
+            below = {l for l in range(1, len(dims) - 1) if any(mk[j].any() for j in mk if j > l)}
+            _assert_close(V[i], ref.V[i], dims, tol, f"unforced: V[{i}]", mk, over="skip", skip_layers=below)
     run.close()
 
 
