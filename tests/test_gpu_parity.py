@@ -1153,6 +1153,64 @@ def test_deferred_update_with_chunked_averaging(pkg, orc):
     assert np.isfinite(out[0][0])
 
 
+# ------------------------------------------------------------ degenerate cases
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("dims,m,B,resident", [
+    ([20, 6], 1, 1, True),          # one worker, one sample per batch, softmax regression (resident kernel)
+    ([20, 6], 1, 1, False),         # ... launch-per-layer kernels
+    ([9, 5, 1], 2, 3, True),        # a single class: the loss is 0 and the gradient is the weight decay alone
+    ([9, 5, 1], 2, 3, False),
+    ([1, 1, 2], 3, 2, False),       # one input feature, one hidden unit
+    ([33, 17, 4], 1, 128, False),   # one worker, the largest batch
+])
+def test_degenerate_shapes(pkg, orc, dims, m, B, resident, bf16):
+    """The smallest and the most lopsided problems the interface admits: m = 1 (the averaging step
+    is the identity, bit for bit), B = 1, one class, one feature, B = 128."""
+    _say(f"degenerate dims={dims} m={m} B={B} resident={resident} bf16={bf16}")
+    ref, run = _problem(pkg, orc, dims, m, B, N=50, E=50, wd=1e-2, lr=0.05, bf16=bf16, resident=resident)
+    tol = TOL16 if bf16 else TOL32
+    for tau in (1, 3):
+        masks = UnitMasks()
+        _ref_steps(orc, ref, 11, tau, masks)
+        run.local_steps(tau)
+        X, V = _check_workers(run, ref, dims, tol, f"after {tau} steps", masks, max_masked=1.0, over="skip")
+        _check_losses(run, ref, tol, "local losses")
+        if dims[-1] == 1:
+            assert float(np.abs(run.local_losses()).max()) == 0.0
+        ref.average()
+        run.average()
+        Xa, Va, _ = run.get_state()
+        if m == 1:
+            assert np.array_equal(Xa.view(np.uint32), X.view(np.uint32))     # the mean of one model is that model
+        assert np.array_equal(Va.view(np.uint32), V.view(np.uint32))
+        assert abs(run.loss() - ref.loss()) < max(tol, 1e-4) * max(ref.loss(), 1e-3)
+        _force(run, ref)
+    run.close()
+
+
+def test_run_of_zero_iterations_and_single_sample_dataset(pkg, orc):
+    """lc_run with K = 0 decides nothing and touches nothing; N = E = 1 makes every batch the same
+    sample B times (sampling with replacement)."""
+    _say("K = 0, N = 1")
+    dims, m, B = [12, 7, 3], 3, 4
+    ref, run = _problem(pkg, orc, dims, m, B, N=1, E=1)
+    X0, V0, _ = run.get_state()
+    sched, rounds = run.run(0, 5)
+    assert sched == [(0, 5)] and rounds == 0 and run.k == 0
+    sched, rounds = run.run(0, 5, adaptive=True, interval=3)
+    assert sched == [(0, 5)] and rounds == 0
+    X1, V1, _ = run.get_state()
+    assert np.array_equal(X0, X1) and np.array_equal(V0, V1)
+    masks = UnitMasks()
+    _ref_steps(orc, ref, 11, 2, masks)
+    run.local_steps(2)
+    assert np.array_equal(run.last_indices(), np.zeros((m, B), np.int32))
+    X, V = _check_workers(run, ref, dims, TOL32, "N = 1", masks, max_masked=1.0, over="skip")
+    assert all(np.array_equal(X[i], X[0]) for i in range(1, m))     # every worker saw the same batch
+    run.close()
+
+
 # --------------------------------------------------------------- error paths
 
 def test_attach_errors_and_bad_tau(pkg):
