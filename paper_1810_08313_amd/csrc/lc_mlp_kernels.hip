@@ -1406,6 +1406,13 @@ hipError_t launch_backward(lc_handle* h, int l, bool da_only) {
         int want = static_cast<int>((1024 + base - 1) / base);
         if (want < n_cc / 4) want = n_cc / 4;
         a.col_split = want < 1 ? 1 : (want > n_cc ? n_cc : want);
+        // a state that streams from memory: as few trips per workgroup as the per-workgroup set-up
+        // (staging the dZ slice, the A operands: proportional to the batch tile) allows -- one at
+        // 32 samples, four at 128.  Many short-lived workgroups sweep memory in dispatch order and
+        // stream faster than few long walks (3072x2048 layer, 64 replicas, B = 32: 5.24 TB/s with 1
+        // workgroup per row block, 5.55 with 8, 5.9 with 32; 3072x1024, 16 replicas, B = 128:
+        // 155 us with 4 or 8 per row block, 191 us with 16)
+        if (h->stream_weights && a.col_split < n_cc * 32 / S.Bp) a.col_split = n_cc * 32 / S.Bp;
     }
     a.total_blocks = static_cast<int64_t>(S.G) * a.n_row_blocks * a.col_split;
     const unsigned grid = xcd_grid(a.total_blocks);
