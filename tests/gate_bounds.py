@@ -24,6 +24,12 @@ oracle's own forward pass, layer by layer:
                  i.e. a share of the distance travelled since the state was forced.  fp32 operands
                  take that as it is; bf16 operands take one bf16 ulp for the weights whose master
                  lies that close to a point where its bf16 rounding changes.
+                 A unit that had an undecided gate in an earlier unforced step (`suspect`) is another
+                 matter: if its gate did fall the other way, its whole column of W_l differs by one
+                 sample's term of that step's update, which is of the size of the column's movement
+                 itself.  For such columns dw = |x - x0| + rms, with any operands, and what their
+                 activations then may differ by reaches the layer above like any other input
+                 uncertainty.
 
 A gate is undecided where |z_l[b, j]| <= dz_l[b, j]; a unit is masked when any sample's gate is.
 Inputs (layer 0) are exact on both sides.  All of it uses oracle values only.
@@ -68,10 +74,12 @@ def _bf16(v: np.ndarray) -> np.ndarray:
 
 
 def undecided_gates(orc, omd, x: np.ndarray, data: np.ndarray, idx: Sequence[int],
-                    x0: np.ndarray = None, eps_sum: float = EPS_SUM) -> Dict[int, np.ndarray]:
+                    x0: np.ndarray = None, eps_sum: float = EPS_SUM,
+                    suspect: Dict[int, np.ndarray] = None) -> Dict[int, np.ndarray]:
     """{hidden layer l: bool [B, d_l]} of the gates that summation order may decide, for one
     worker with master parameters x on the samples idx.  x0: the parameters at which both sides
-    were last bit-identical (None: they are now)."""
+    were last bit-identical (None: they are now).  suspect: {layer: bool [d_l]} units that had an
+    undecided gate in a step since then."""
     L = omd.n_layers
     dims = [omd.dims[l] for l in range(L + 1)]
     bf16 = bool(omd.bf16)
@@ -98,12 +106,14 @@ def undecided_gates(orc, omd, x: np.ndarray, data: np.ndarray, idx: Sequence[int
                 dw = np.where(_to_boundary_ulps(W) * _ulp32(W) <= drift, 65536.0 * _ulp32(W), 0.0)
             else:
                 dw = drift
+            if suspect and l in suspect and suspect[l].any():
+                dw[:, suspect[l]] = (moved + np.sqrt(np.mean(moved * moved)))[:, suspect[l]]
             dz += np.minimum(a @ dw, IN_SIGMAS * np.sqrt((a * a) @ (dw * dw)))
         out[l] = np.abs(z) <= dz
         act = np.maximum(zs[l - 1], np.float32(0.0))
         if bf16:
             near = (_to_boundary_ulps(act) * _ulp32(act) <= dz) & (z > -dz)
-            da = np.where(near, 65536.0 * _ulp32(np.maximum(act, dz.astype(np.float32))), 0.0)
+            da = np.where(near, np.maximum(65536.0 * _ulp32(np.maximum(act, dz.astype(np.float32))), dz), 0.0)
             a = _bf16(act).astype(np.float64)
         else:
             da = np.where(z > -dz, dz, 0.0)

@@ -74,7 +74,7 @@ def _assert_close(got, want, dims, tol, what, masked=None, max_masked=0.5, skip_
         g, w = got[..., sl].astype(np.float64), want[..., sl].astype(np.float64)
         if layer in masked and masked[layer].any() and not (bias_only and name[0] == "W"):
             keep = ~masked[layer]
-            if (~keep).mean() > max_masked and over == "skip":
+            if ((~keep).mean() > max_masked or not keep.any()) and over == "skip":
                 _say(f"  {what} {name}: {int((~keep).sum())} of {keep.size} units undecided, block not compared")
                 continue
             assert (~keep).mean() <= max_masked, f"{what} {name}: {int((~keep).sum())} of {keep.size} units masked"
@@ -143,7 +143,8 @@ def _note_gates(orc, ref, seed, masks, ids, fresh):
         if fresh:
             masks.origin[i] = ref.X[i].copy()
         idx = batch_indices(orc, ref.md, seed, i, ref.k, ref.m)
-        masks.add(i, undecided_gates(orc, ref.md, ref.X[i], data, idx, None if fresh else masks.origin[i]))
+        masks.add(i, undecided_gates(orc, ref.md, ref.X[i], data, idx, None if fresh else masks.origin[i],
+                                     suspect=None if fresh else masks.of(i)))
 
 
 def _ref_steps(orc, ref, seed, tau, masks=None, ids=None, fresh=True):
@@ -157,15 +158,25 @@ def _ref_steps(orc, ref, seed, tau, masks=None, ids=None, fresh=True):
         ref.local_steps(1, ids=None if every else ids)
 
 
-def _check_workers(run, ref, dims, tol, what, masks=None, ids=None, buffers=True, max_masked=0.5, over="fail"):
-    """State of the GPU run against the oracle's, worker by worker, at the bar `tol`."""
+def _check_workers(run, ref, dims, tol, what, masks=None, ids=None, buffers=True, max_masked=0.5, over="fail",
+                   below="assert"):
+    """State of the GPU run against the oracle's, worker by worker, at the bar `tol`.
+    below="skip": a layer's gradient passes through the gates of every layer above it, so a gate
+    that fell the other way up there moves all of the blocks below a little (by unit it cannot be
+    left out): the buffers -- and with the 1e-4 bar of fp32 operands the parameters -- of layers
+    below a layer with an undecided unit are then not compared for that worker.  The tests on
+    chosen shapes do not need this; the sweep over random shapes, some of them deep and narrow, does."""
     X, V, k = run.get_state()
     assert k == ref.k, (what, k, ref.k)
     for i in (range(ref.m) if ids is None else ids):
         mk = masks.of(i) if masks is not None else None
+        skip = set()
+        if below == "skip" and mk:
+            skip = {l for l in range(1, len(dims) - 1) if any(mk[j].any() for j in mk if j > l)}
         if buffers:
-            _assert_close(V[i], ref.V[i], dims, tol, f"{what}: V[{i}]", mk, max_masked, over=over)
-        _assert_close(X[i], ref.X[i], dims, tol, f"{what}: X[{i}]", _xmask(ref, mk), max_masked, over=over)
+            _assert_close(V[i], ref.V[i], dims, tol, f"{what}: V[{i}]", mk, max_masked, skip, over=over)
+        _assert_close(X[i], ref.X[i], dims, tol, f"{what}: X[{i}]", _xmask(ref, mk), max_masked,
+                      set() if ref.md.bf16 else skip, over=over)
     return X, V
 
 
@@ -407,7 +418,8 @@ def test_round_of_local_steps_then_average(pkg, orc, bf16):
         run.local_steps(tau)
         _say(f"  masked units of worker 0 {masks.counts(0)}; drift of the masters "
              f"{_drift(run.get_state()[0][0], ref.X[0], x_start, dims, masks.of(0))}")
-        _check_workers(run, ref, dims, tol, f"before average {r}", masks, max_masked=0.7)
+        # (five unforced steps: the 33 units of the second hidden layer may all have had an undecided gate by then)
+        _check_workers(run, ref, dims, tol, f"before average {r}", masks, over="skip")
         ref.average()
         run.average()
         X, V, k = run.get_state()
@@ -548,7 +560,7 @@ def test_first_layer_fusion_across_steps(pkg, orc, dims, m, B, bf16):
         run.local_steps(tau)
         sep.local_steps(tau)
         done += tau
-        over = "skip" if tau > 8 else "fail"   # (the 18-step call: many unforced steps)
+        over = "skip" if tau > 1 else "fail"   # (unforced steps: a 24-unit layer fills up with undecided units)
         _check_workers(run, ref, dims, tol, f"after {done}", masks, over=over)
         _check_workers(sep, ref, dims, tol, f"separate forward after {done}", masks, over=over)
         _check_losses(run, ref, tol, f"local losses after {done}")
@@ -1151,6 +1163,51 @@ def test_deferred_update_with_chunked_averaging(pkg, orc):
     for a, b in zip(out[0][1:4], out[1][1:4]):
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
     assert np.isfinite(out[0][0])
+
+
+# -------------------------------------------------------------- random shapes
+
+def _random_case(seed):
+    g = np.random.default_rng(1000 + seed)
+    L = int(g.integers(1, 5))
+    pick = lambda: int(g.choice([int(g.integers(1, 300)), int(g.choice([16, 64, 128, 192, 256])), int(g.integers(1, 20))]))
+    dims = [pick() for _ in range(L)] + [int(g.choice([int(g.integers(1, 12)), int(g.integers(12, 80))]))]
+    return dict(dims=dims, m=int(g.integers(1, 7)), B=int(g.choice([int(g.integers(1, 129)), 32, 64, 128])),
+                beta=float(g.choice([0.0, 0.9])), wd=float(g.choice([0.0, 1e-3])), bf16=bool(g.integers(0, 2)),
+                resident=bool(g.integers(0, 2)), lazy=bool(g.integers(0, 2)))
+
+
+@pytest.mark.parametrize("seed", range(int(os.environ.get("LC_TEST_RANDOM_CASES", "48"))))   # (more for a one-off sweep)
+def test_random_shapes_two_calls_and_average(pkg, orc, seed):
+    """Shapes nobody picked: 1 to 4 layers of random widths (odd, tiny, multiples of 64), 1 to 6
+    workers, any batch size up to 128, with and without momentum, weight decay, bf16 operands, the
+    resident kernel and the deferred broadcast.  One step, then two more in one call, each from the
+    oracle's state, model and buffers at the bar; then the averaging step, bit for bit against the
+    mean of the rows the GPU held."""
+    c = _random_case(seed)
+    dims, m, B = c["dims"], c["m"], c["B"]
+    _say(f"random case {seed}: {c}")
+    ref, run = _problem(pkg, orc, dims, m, B, N=150, E=120, lr=0.05, beta=c["beta"], wd=c["wd"], bf16=c["bf16"],
+                        resident=c["resident"], seed=100 + seed)
+    run.set_lazy_broadcast(c["lazy"])
+    tol = TOL16 if c["bf16"] else TOL32
+    for tau in (1, 2):
+        masks = UnitMasks()
+        _ref_steps(orc, ref, 100 + seed, tau, masks)
+        run.local_steps(tau)
+        X, V = _check_workers(run, ref, dims, tol, f"{tau} step(s)", masks, max_masked=1.0, over="skip", below="skip")
+        _check_losses(run, ref, tol, "local losses")
+        _force(run, ref)
+    ref.average()
+    run.average()
+    Xa, Va, k = run.get_state()
+    want = ref.X[0]
+    assert k == ref.k == 3
+    assert np.array_equal(Xa[0].view(np.uint32), want.view(np.uint32))       # same rows in, same mean out
+    assert all(np.array_equal(Xa[i], Xa[0]) for i in range(1, m))
+    assert np.array_equal(Va.view(np.uint32), ref.V.view(np.uint32))
+    assert abs(run.loss() - ref.loss()) < max(tol, 1e-4) * max(ref.loss(), 1e-3)
+    run.close()
 
 
 # ------------------------------------------------------------ degenerate cases
