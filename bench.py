@@ -61,6 +61,8 @@ def parse():
                     help="resident kernel: exchange through device scope (see lc_set_xcd_local_exchange)")
     ap.add_argument("--no-deferred-update", action="store_true",
                     help="at tau = 1 write every replica's weights in the step (lc_set_deferred_update(0))")
+    ap.add_argument("--no-implicit-momentum", action="store_true",
+                    help="momentum rows read and written in every step (lc_set_implicit_momentum(0))")
     ap.add_argument("--no-first-layer-fusion", action="store_true",
                     help="separate first-layer forward launch in every step (see lc_set_first_layer_fusion)")
     return ap.parse_args()
@@ -107,6 +109,7 @@ def make_run(args, pkg, synth, name, cache):
     run.set_resident(not args.layer_kernels)
     run.set_first_layer_fusion(not args.no_first_layer_fusion)
     run.set_deferred_update(not args.no_deferred_update)
+    run.set_implicit_momentum(0 if args.no_implicit_momentum else 1)
     run.set_xcd_local_exchange(not args.agent_scope_exchange)
     return w, run
 
@@ -148,7 +151,9 @@ def dominant_kernel(run, w, K2, tau0):
 def layer_bytes(w, rec, tau0, args):
     """Algorithmic HBM bytes of one launch of a backward-class kernel on one layer: W and V of
     every replica read and written once (16 B per parameter); the tile-owner kernel of tau = 1
-    reads and writes V only and the one averaged model once (8 m + 8 B per weight)."""
+    reads and writes V only and the one averaged model once (8 m + 8 B per weight).  (With
+    implicit momentum the steps inside a period move 12 B per parameter; the figure stays the
+    algorithm's 16, the counter traffic shows what moved.)"""
     l = rec["layer"]
     n = w.dims[l - 1] * w.dims[l] + w.dims[l]
     if rec["kernel_id"] == 3:
@@ -183,7 +188,8 @@ def bench_mlp(args, pkg, synth, name, cache, headline=True):
            "averaging_rounds": last["rounds"], "tau_schedule": last["sched"][:16],
            "deferred_broadcast": not args.eager, "resident_step_kernel": resident,
            "first_layer_fusion": not args.no_first_layer_fusion,
-           "deferred_update_at_tau_1": not args.no_deferred_update and not args.eager}
+           "deferred_update_at_tau_1": not args.no_deferred_update and not args.eager,
+           "implicit_momentum_inside_periods": not args.no_implicit_momentum and w.bf16 and 8.0 * w.m * w.P > 256 * 2**20}
     if name == "cfg3":
         cfg["note"] = ("at this configuration's own learning rate and momentum the averaged model stays near ln 10 "
                        "with periods of 20, so the rule keeps tau near tau0: an adapting tau is not exercised here")

@@ -240,6 +240,24 @@ int lc_set_first_layer_fusion(lc_handle* h, int on);
  * called one by one (the library cannot know that an averaging step follows).  Default on. */
 int lc_set_deferred_update(lc_handle* h, int on);
 
+/* Implicit momentum inside a period (Sec. 2: tau local updates between two averaging steps; Sec. 5.3:
+ * one momentum buffer per worker).  The update x_{k+1} = x_k - lr v_{k+1} lets v_k be read off two
+ * consecutive models, v_k = (x_{k-1} - x_k) / lr.  For the layers this applies to, the steps of a
+ * period except the last keep x_k and x_{k-1} in the two row buffers (the caller's X and V) instead
+ * of x_k and v_k, read both and write x_{k+1} over x_{k-1}: 12 instead of 16 bytes per parameter,
+ * replica and step.  The last step of every period -- and of every lc_local_steps() call -- writes
+ * x to X and v to V again, so every entry point of this library finds and leaves the documented
+ * state; only a caller who reads X or V while an asynchronous call is still running sees the
+ * intermediate form.  The recovered momentum differs from the stored one by the rounding of x_k,
+ * ulp(x) / (2 lr): relative to v about 6e-8 divided by the relative size of one step (1e-4 .. 1e-3
+ * in training).  That is far below the rounding of bf16 operands and above that of fp32 operands.
+ *   mode 1 (default): layers of at least 1 MB, the last layer excepted, of LC_KIND_MLP runs with
+ *           LC_GEMM_BF16 whose state exceeds the caches (X and V above 256 MB), on the
+ *           launch-per-layer path, while block momentum is off and lr > 0;
+ *   mode 2: every layer but the last, with either operand type and at any size;
+ *   mode 0: off -- x in X and v in V after every step. */
+int lc_set_implicit_momentum(lc_handle* h, int mode);
+
 /* 1 if lc_local_steps() of this (attached) handle takes the resident step kernel, else 0. */
 int lc_resident_active(const lc_handle* h);
 

@@ -87,6 +87,8 @@ def lib() -> C.CDLL:
     L.lc_average.argtypes = [vp]
     L.lc_set_lazy_broadcast.restype = C.c_int
     L.lc_set_lazy_broadcast.argtypes = [vp, C.c_int]
+    L.lc_set_implicit_momentum.restype = C.c_int
+    L.lc_set_implicit_momentum.argtypes = [vp, C.c_int]
     L.lc_set_resident.restype = C.c_int
     L.lc_set_resident.argtypes = [vp, C.c_int]
     L.lc_resident_active.restype = C.c_int
@@ -309,6 +311,10 @@ class LocalSGD:
 
     def set_deferred_update(self, on: bool) -> None:
         self._check(self._L.lc_set_deferred_update(self._h, int(bool(on))), "lc_set_deferred_update")
+
+    def set_implicit_momentum(self, mode: int) -> None:
+        """0 off, 1 where it pays (default), 2 wherever the kernels allow (see lc_set_implicit_momentum)."""
+        self._check(self._L.lc_set_implicit_momentum(self._h, int(mode)), "lc_set_implicit_momentum")
 
     def set_first_layer_fusion(self, on: bool) -> None:
         self._check(self._L.lc_set_first_layer_fusion(self._h, int(bool(on))), "lc_set_first_layer_fusion")

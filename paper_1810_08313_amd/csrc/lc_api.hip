@@ -184,7 +184,10 @@ int materialise(lc_handle* h) {
 // next_gathered: the step after this one belongs to the same call and its mini-batch is already
 // in the next input slot, so the first layer's backward kernel may run that step's first-layer
 // forward pass on the weights it has just updated.
-int one_local_step(lc_handle* h, bool next_gathered) {
+// implicit_out: the step may leave the large layers with their momentum in implicit form (it is
+// not the last step of its period or of the call).
+int one_local_step(lc_handle* h, bool next_gathered, bool implicit_out = false) {
+    h->imp_out = implicit_out;
     if (h->md.kind == LC_KIND_QUAD) {
         const int rc = materialise(h);
         if (rc != LC_OK) return rc;
@@ -283,7 +286,8 @@ int run_periods(lc_handle* h, int tau, int n_periods, bool average) {
                 h->defer_x = defer;
                 for (int u = 0; u < in_period; ++u, ++t) {
                     h->train.cur_slot = t;
-                    const int r = one_local_step(h, u + 1 < in_period);
+                    // (the last step of a period, and of what this chunk holds of it, leaves x in X and v in V)
+                    const int r = one_local_step(h, u + 1 < in_period, !defer && u + 1 < in_period);
                     if (r != LC_OK) {
                         h->defer_x = false;
                         h->sync_done = 0;
@@ -402,6 +406,9 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     h->res_on = true;
     h->res_fuse_always = false;
     h->fl_on = true;
+    h->imp_mode = 1;
+    h->imp_out = false;
+    for (int l = 0; l <= LC_MAX_LAYERS; ++l) h->imp[l] = ImpState{false, kBufX, kBufV};
     h->a1_ready = false;
     h->res_local_on = true;
     h->res_xcc_known = false;
@@ -515,6 +522,8 @@ int lc_local_periods(lc_handle* h, int tau, int n_periods) {
 int lc_average(lc_handle* h) {
     const int rc = require_attached(h);
     if (rc != LC_OK) return rc;
+    for (int l = 1; l <= h->L; ++l)
+        if (h->imp[l].active) return LC_ERR_STATE;   // (cannot happen: every call ends with x in X and v in V)
     if (h->lazy_rows) {
         if (!h->bm_on) return LC_OK;   // already synchronised: averaging again changes nothing
         const int mrc = materialise(h);   // block momentum moves even a synchronised model (u decays)
@@ -560,6 +569,12 @@ int lc_set_xcd_local_exchange(lc_handle* h, int on) {
 int lc_set_first_layer_fusion(lc_handle* h, int on) {
     if (!h) return LC_ERR_ARG;
     h->fl_on = on != 0;
+    return LC_OK;
+}
+
+int lc_set_implicit_momentum(lc_handle* h, int mode) {
+    if (!h || mode < 0 || mode > 2) return LC_ERR_ARG;
+    h->imp_mode = mode;
     return LC_OK;
 }
 

@@ -29,11 +29,15 @@ namespace {
 constexpr int kFlWaves = 4;
 
 struct FirstArgs {
-    float* X;
-    float* V;
+    float* X;             // where the new parameters are written
+    float* V;             // where the new momentum is written, or null (implicit momentum, see BwdArgs::Aux)
     int64_t x_stride;
-    const float* Xr;      // where the weights are read: X, or the one averaged model (stride 0)
+    const float* Xr;      // where the weights are read: X, the one averaged model (stride 0), or the other row buffer
     int64_t xr_stride;
+    const float* Aux;     // the momentum rows, or (imp_in) the parameters of one step earlier
+    int64_t aux_stride;
+    int imp_in;
+    float inv_lr;
     int shared_w;         // > 0: block order of steps in which all replicas read one model (see shared_order)
     int64_t w_off, b_off;
     int d_in, d_out, dp_in, dp_out;
@@ -120,7 +124,8 @@ __global__ __launch_bounds__(256) void first_layer_kernel(FirstArgs a) {
 
     float* W = a.X + g * a.x_stride + a.w_off;
     const float* Wr = a.Xr + g * a.xr_stride + a.w_off;
-    float* Vw = a.V + g * a.x_stride + a.w_off;
+    float* Vw = a.V ? a.V + g * a.x_stride + a.w_off : nullptr;
+    const float* Va = a.Aux + g * a.aux_stride + a.w_off;
     const OT* AT = static_cast<const OT*>(a.a_fm) + static_cast<int64_t>(g) * a.dp_in * Bp;
     const OT* AN = static_cast<const OT*>(a.an_bm) + static_cast<int64_t>(g) * Bp * a.dp_in;
     const int n_steps = a.d_in / 16;
@@ -151,7 +156,7 @@ __global__ __launch_bounds__(256) void first_layer_kernel(FirstArgs a) {
         // sits between the loads
         const int k0 = 16 * (s < n_steps ? s : n_steps - 1);
         const float* wb = Wr + static_cast<int64_t>(k0) * a.d_out;
-        const float* vb = Vw + static_cast<int64_t>(k0) * a.d_out;
+        const float* vb = Va + static_cast<int64_t>(k0) * a.d_out;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             // (weights that all replicas share are wanted in the L2 by the neighbouring blocks)
@@ -181,14 +186,14 @@ __global__ __launch_bounds__(256) void first_layer_kernel(FirstArgs a) {
     // bias of these columns: db_1 = sum_b dZ_1, the same update; kept for the forward epilogue
     if (tid < kColChunk) {
         float* bx = a.X + g * a.x_stride + a.b_off + c0 + tid;
-        float* bv = a.V + g * a.x_stride + a.b_off + c0 + tid;
         const float x = a.Xr[g * a.xr_stride + a.b_off + c0 + tid];
-        const float vb0 = *bv;
+        float vb0 = a.Aux[g * a.aux_stride + a.b_off + c0 + tid];
+        if (a.imp_in) vb0 = (vb0 - x) * a.inv_lr;
         const OT* zr = dzt[(tid & 3) * 16 + (tid >> 2)];
         float sb = 0.f;
         for (int b = 0; b < a.B; ++b) sb += to_f32(zr[b]);
         const float vb = a.beta * vb0 + (sb + a.wd * x);
-        *bv = vb;
+        if (a.V) a.V[g * a.x_stride + a.b_off + c0 + tid] = vb;
         *bx = x - a.lr * vb;
         bias_s[tid] = x - a.lr * vb;
     }
@@ -201,7 +206,7 @@ __global__ __launch_bounds__(256) void first_layer_kernel(FirstArgs a) {
 
     auto process = [&](int s, Set& x) {
         float* ws = W + static_cast<int64_t>(16 * s) * a.d_out;
-        float* vs = Vw + static_cast<int64_t>(16 * s) * a.d_out;
+        float* vs = Vw ? Vw + static_cast<int64_t>(16 * s) * a.d_out : nullptr;
         // dW tile: sum over the batch of A_0^T[k][b] dZ_1^T[c][b]
         f32x4 acc[4];
 #pragma unroll
@@ -217,6 +222,12 @@ __global__ __launch_bounds__(256) void first_layer_kernel(FirstArgs a) {
         for (int r = 0; r < 4; ++r) {
             consume_here(x.w[r]);
             consume_here(x.v[r]);
+            if (a.imp_in) {   // the tile holds the parameters of one step earlier: v = (x_prev - x) / lr
+                x.v[r].x = (x.v[r].x - x.w[r].x) * a.inv_lr;
+                x.v[r].y = (x.v[r].y - x.w[r].y) * a.inv_lr;
+                x.v[r].z = (x.v[r].z - x.w[r].z) * a.inv_lr;
+                x.v[r].w = (x.v[r].w - x.w[r].w) * a.inv_lr;
+            }
             x.v[r].x = a.beta * x.v[r].x + (acc[0][r] + a.wd * x.w[r].x);
             x.v[r].y = a.beta * x.v[r].y + (acc[1][r] + a.wd * x.w[r].y);
             x.v[r].z = a.beta * x.v[r].z + (acc[2][r] + a.wd * x.w[r].z);
@@ -225,7 +236,7 @@ __global__ __launch_bounds__(256) void first_layer_kernel(FirstArgs a) {
             x.w[r].y -= a.lr * x.v[r].y;
             x.w[r].z -= a.lr * x.v[r].z;
             x.w[r].w -= a.lr * x.v[r].w;
-            store_wm<WM>(at_byte(vs, woff[r]), 0, a.d_out, true, x.v[r]);
+            if (vs) store_wm<WM>(at_byte(vs, woff[r]), 0, a.d_out, true, x.v[r]);
             store_wm<WM>(at_byte(ws, woff[r]), 0, a.d_out, true, x.w[r]);
         }
         // Z_1' += A_0'[:, k0 .. k0+15] W_1[k0 .. k0+15, :] with the tile just updated
@@ -357,12 +368,17 @@ hipError_t launch_first_layer(lc_handle* h) {
     if (!first_layer_kernel_ok(h)) return hipErrorInvalidValue;
     if (S.cur_slot + 1 >= S.slots) return hipErrorInvalidValue;
     FirstArgs a;
-    a.X = h->X;
-    a.V = h->V;
+    const StepBufs sb = plan_step_buffers(h, 1);
+    a.X = sb.ox;
+    a.V = sb.ov;
     a.x_stride = h->Ps;
-    a.Xr = h->lazy_rows ? h->xbar : h->X;
-    a.xr_stride = h->lazy_rows ? 0 : h->Ps;
-    a.shared_w = (h->lazy_rows && shared_weight_order(h, g)) ? shared_set(h, S.G) : 0;
+    a.Xr = sb.xr;
+    a.xr_stride = sb.xr_stride;
+    a.Aux = sb.aux;
+    a.aux_stride = sb.aux_stride;
+    a.imp_in = sb.imp_in;
+    a.inv_lr = 1.f / h->md.lr;
+    a.shared_w = (sb.xr_stride == 0 && shared_weight_order(h, g)) ? shared_set(h, S.G) : 0;
     a.w_off = g.w_off;
     a.b_off = g.b_off;
     a.d_in = g.d_in;
@@ -385,6 +401,7 @@ hipError_t launch_first_layer(lc_handle* h) {
     const hipError_t e = bf16 ? launch_fl<bf16_t>(a, S.Bp / 16, h->stream_weights, grid, h->stream)
                               : launch_fl<float>(a, S.Bp / 16, h->stream_weights, grid, h->stream);
     timing_stop(h, kTimeBwd, 1, kBwdFirstLayer);
+    if (e == hipSuccess) h->imp[1] = sb.next;
     return e;
 }
 

@@ -31,6 +31,24 @@ enum TimedKernel { kTimeBwd = 0, kTimeFwd = 1, kTimeAvg = 2, kTimeUpd = 3, kTime
 // Kernels of the backward class, for lc_timing_select().
 enum BwdKernel { kBwdAny = 0, kBwdRowOwner = 1, kBwdFirstLayer = 2, kBwdTileOwner = 3, kBwdHead = 4, kBwdResident = 5 };
 
+// Implicit momentum: where a layer's parameters of the current and of the previous step are.
+enum ImpBuf { kBufX = 0, kBufV = 1, kBufXbar = 2 };
+struct ImpState {
+    bool active;   // false: parameters in X (or the averaged model while a broadcast is pending), momentum in V
+    int cur, prev; // active: x_k in `cur` (X or V rows), x_{k-1} in `prev` (the other rows, or the averaged model)
+};
+// Buffers of one backward-class launch of a layer, and the layer's form after it.
+struct StepBufs {
+    const float* xr;      // parameters are read here
+    int64_t xr_stride;
+    const float* aux;     // momentum rows, or (imp_in) the parameters of one step earlier
+    int64_t aux_stride;
+    int imp_in;
+    float* ox;            // new parameters
+    float* ov;            // new momentum, or null (implicit)
+    ImpState next;
+};
+
 // One layer of the per-replica MLP as the kernels see it.
 struct LayerGeom {
     int d_in, d_out;      // logical sizes
@@ -108,6 +126,9 @@ struct lc_handle {
     bool res_local_on;      // lc_set_xcd_local_exchange
     bool res_xcc_known;     // the probe found blocks dealt to the XCDs by id mod 8
     unsigned res_xcc_of;    // 4 bits per residue: the XCD it runs on
+    int imp_mode;           // lc_set_implicit_momentum: 0 off, 1 where it pays, 2 wherever the kernels allow
+    bool imp_out;           // the step being queued may leave its layers in implicit form (not the last of a period or call)
+    lc::ImpState imp[LC_MAX_LAYERS + 1];   // index 1..L
     bool fl_on;             // lc_set_first_layer_fusion
     bool a1_ready;          // A_1 of the step about to run was produced by the previous step's backward pass
     bool res_fuse_always;   // lc_set_resident(2): averaging steps inside the launch at every eligible shape
@@ -142,6 +163,9 @@ hipError_t launch_softmax(lc_handle* h, bool eval, int loss_offset);
 hipError_t launch_backward(lc_handle* h, int l, bool da_only = false);   // da_only: dZ_{l-1} only, no update
 bool first_layer_kernel_ok(const lc_handle* h);   // layer 1: backward kernel that also runs the next step's forward
 hipError_t launch_first_layer(lc_handle* h);
+bool implicit_layer_ok(const lc_handle* h, int l);   // layer l may keep its momentum implicitly inside a period
+void layer_weights(const lc_handle* h, int l, const float** base, int64_t* stride);   // where layer l's current parameters are read
+StepBufs plan_step_buffers(const lc_handle* h, int l);
 bool sync_layer_ok(const lc_handle* h, int l);    // layer l at tau = 1: dW, update of V and averaging of the layer by tile
 hipError_t launch_sync_layer(lc_handle* h, int l);
 bool shared_weight_order(const lc_handle* h, const LayerGeom& g);   // tile-major block order on steps that read one model

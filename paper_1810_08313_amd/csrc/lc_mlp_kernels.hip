@@ -571,11 +571,19 @@ __global__ __launch_bounds__(128) void softmax_kernel(SoftmaxArgs a) {
 // ------------------------------------------------------------------- backward
 
 struct BwdArgs {
-    float* X;
-    float* V;
+    float* X;            // where the new parameters are written (rows of stride x_stride)
+    float* V;            // where the new momentum is written, or null: implicit momentum (see Aux)
     int64_t x_stride;
     const float* Xr;     // where the weights are READ: X itself, or the single averaged model that all
-    int64_t xr_stride;   // replicas share right after a lazy averaging step (stride 0)
+    int64_t xr_stride;   // replicas share right after a lazy averaging step (stride 0), or the other row buffer
+    // Second operand of the update.  imp_in == 0: the momentum rows v.  imp_in != 0: the parameters of
+    // ONE STEP EARLIER, x_prev, from which the momentum is recovered as (x_prev - x) / lr -- the update
+    // x = x_prev - lr v read backwards.  Inside a period the buffer that held v then holds the newer of
+    // two consecutive models instead, and a step reads 8 and writes 4 bytes per parameter.
+    const float* Aux;
+    int64_t aux_stride;
+    int imp_in;
+    float inv_lr;
     int64_t w_off, b_off;
     int d_in, d_out, dp_in, dp_out;
     int B, Bp;
@@ -639,7 +647,8 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
 
     float* W = a.X + g * a.x_stride + a.w_off;
     const float* Wr = a.Xr + g * a.xr_stride + a.w_off;
-    float* Vw = a.V + g * a.x_stride + a.w_off;
+    float* Vw = a.V ? a.V + g * a.x_stride + a.w_off : nullptr;
+    const float* Va = DAO ? nullptr : a.Aux + g * a.aux_stride + a.w_off;
     const OT* AT = static_cast<const OT*>(a.a_fm) + static_cast<int64_t>(g) * a.dp_in * Bp;
     const OT* dZ = static_cast<const OT*>(a.dz_bm) + static_cast<int64_t>(g) * Bp * a.dp_out;
     const OT* dZT = static_cast<const OT*>(a.dz_fm) + static_cast<int64_t>(g) * a.dp_out * Bp;
@@ -693,7 +702,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
             const int row = k0 + 4 * q + r;
             if constexpr (WM == kWGeneric) {
                 ww[r] = load_w4_rows(Wr, row, a.d_in, c0 + 4 * j, a.d_out, vec, false);
-                vv[r] = load_w4_rows(Vw, row, a.d_in, c0 + 4 * j, a.d_out, vec, false);
+                vv[r] = load_w4_rows(Va, row, a.d_in, c0 + 4 * j, a.d_out, vec, false);
             } else {
                 // rows past d_in read the last row instead (no branch between the loads); their
                 // weights are zeroed when used and they are never stored
@@ -703,7 +712,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
                     ww[r] = load_wm<kWVector>(Wr + static_cast<int64_t>(rr) * a.d_out, c0 + 4 * j, a.d_out, vec);
                 else
                     ww[r] = load_wm<WM>(Wr + static_cast<int64_t>(rr) * a.d_out, c0 + 4 * j, a.d_out, vec);
-                if constexpr (!DAO) vv[r] = load_wm<WM>(Vw + static_cast<int64_t>(rr) * a.d_out, c0 + 4 * j, a.d_out, vec);
+                if constexpr (!DAO) vv[r] = load_wm<WM>(Va + static_cast<int64_t>(rr) * a.d_out, c0 + 4 * j, a.d_out, vec);
             }
         }
         if constexpr (!DAO) {
@@ -752,9 +761,9 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         // to them in turn, so that no workgroup carries it on all of its trips and finishes late.
         if (!DAO && rb == chunk_at(i) % a.n_row_blocks && tid < kColChunk && c0 + tid < a.d_out) {
             float* bx = a.X + g * a.x_stride + a.b_off + c0 + tid;
-            float* bv = a.V + g * a.x_stride + a.b_off + c0 + tid;
             const float x = a.Xr[g * a.xr_stride + a.b_off + c0 + tid];   // requested before the sum below
-            const float v0 = *bv;
+            float v0 = a.Aux[g * a.aux_stride + a.b_off + c0 + tid];
+            if (a.imp_in) v0 = (v0 - x) * a.inv_lr;
             const OT* zr = dzt_lds[(tid & 3) * 16 + (tid >> 2)];
             float sb = 0.f;   // (batch entries beyond B are zeros; the order of the sum is the batch order)
 #pragma unroll
@@ -764,7 +773,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
                 for (int e = 0; e < 8; ++e) sb += to_f32(f.v[e]);
             }
             const float vb = momentum_update(a.beta, v0, sb, a.wd, x);
-            *bv = vb;
+            if (a.V) a.V[g * a.x_stride + a.b_off + c0 + tid] = vb;
             if (!a.skip_x) *bx = weight_update(x, a.lr, vb);
         }
         // dW tile: sum over the batch of A^T[k][b] dZ^T[c][b]
@@ -795,6 +804,12 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
         for (int r = 0; r < 4 && !DAO; ++r) {
             const int row = k0 + 4 * q + r;
             const float4 gr = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
+            if (a.imp_in) {   // the tile holds the parameters of one step earlier: v = (x_prev - x) / lr
+                v[r].x = (v[r].x - w[r].x) * a.inv_lr;
+                v[r].y = (v[r].y - w[r].y) * a.inv_lr;
+                v[r].z = (v[r].z - w[r].z) * a.inv_lr;
+                v[r].w = (v[r].w - w[r].w) * a.inv_lr;
+            }
             v[r].x = momentum_update(a.beta, v[r].x, gr.x, a.wd, w[r].x);
             v[r].y = momentum_update(a.beta, v[r].y, gr.y, a.wd, w[r].y);
             v[r].z = momentum_update(a.beta, v[r].z, gr.z, a.wd, w[r].z);
@@ -804,7 +819,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
             w[r].z = weight_update(w[r].z, a.lr, v[r].z);
             w[r].w = weight_update(w[r].w, a.lr, v[r].w);
             if (row < a.d_in) {
-                store_wm<WM>(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, v[r]);
+                if (Vw) store_wm<WM>(Vw + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, v[r]);
                 if (!a.skip_x) store_wm<WM>(W + static_cast<int64_t>(row) * a.d_out, c0 + 4 * j, a.d_out, vec, w[r]);
             }
         }
@@ -1219,6 +1234,65 @@ hipError_t launch_gather(lc_handle* h, bool eval, int64_t k_or_base, int n_steps
     return hipGetLastError();
 }
 
+// ---- implicit momentum: which buffer holds what ---------------------------------------------------
+//
+// Inside a period (Sec. 2: tau local updates between two averaging steps) the update
+// x_{k+1} = x_k - lr v_{k+1} lets the momentum be read off two consecutive models,
+// v_k = (x_{k-1} - x_k) / lr.  A layer in implicit form keeps x_k in one of the two row buffers (X, V)
+// and x_{k-1} in the other (or in the one averaged model, right after an averaging step); a step
+// then reads both and writes x_{k+1} over x_{k-1}: 12 instead of 16 bytes per parameter.  The last
+// step of a period (of a call) writes x to X and v to V again.  The recovered momentum differs from
+// the stored one by the rounding of x_k, ulp(x) / (2 lr): relative to v that is 6e-8 divided by the
+// relative size of a step, 1e-4 .. 1e-3 in training -- invisible beside bf16 operands (bar 2e-2), not
+// beside fp32 operands (bar 1e-4), so it is taken for bf16 runs whose state streams from memory.
+bool implicit_layer_ok(const lc_handle* h, int l) {
+    if (h->imp_mode == 0 || h->md.kind != LC_KIND_MLP || l < 1 || l >= h->L) return false;   // the last layer is small: explicit
+    if (h->bm_on || !(h->md.lr > 0.f)) return false;
+    if (h->imp_mode == 2) return true;
+    const LayerGeom& g = h->layer[l];
+    return h->md.gemm == LC_GEMM_BF16 && h->stream_weights && 4.0 * g.d_in * g.d_out >= 1024.0 * 1024;
+}
+
+namespace {
+const float* buffer_of(const lc_handle* h, int b, int64_t* stride) {
+    *stride = b == kBufXbar ? 0 : h->Ps;
+    return b == kBufX ? h->X : (b == kBufV ? h->V : h->xbar);
+}
+}  // namespace
+
+void layer_weights(const lc_handle* h, int l, const float** base, int64_t* stride) {
+    const ImpState& s = h->imp[l];
+    *base = buffer_of(h, s.active ? s.cur : (h->lazy_rows ? kBufXbar : kBufX), stride);
+}
+
+StepBufs plan_step_buffers(const lc_handle* h, int l) {
+    StepBufs b;
+    const ImpState& s = h->imp[l];
+    const int cur = s.active ? s.cur : (h->lazy_rows ? kBufXbar : kBufX);
+    b.xr = buffer_of(h, cur, &b.xr_stride);
+    if (s.active) {
+        b.aux = buffer_of(h, s.prev, &b.aux_stride);
+        b.imp_in = 1;
+    } else {
+        b.aux = h->V;
+        b.aux_stride = h->Ps;
+        b.imp_in = 0;
+    }
+    if (h->imp_out && implicit_layer_ok(h, l)) {
+        // the new parameters go to the row buffer that does not hold the current ones: over the
+        // momentum or the older model, which the same thread has read by then
+        const int dst = cur == kBufV ? kBufX : kBufV;
+        b.ox = dst == kBufX ? h->X : h->V;
+        b.ov = nullptr;
+        b.next = ImpState{true, dst, cur};
+    } else {
+        b.ox = h->X;
+        b.ov = h->V;
+        b.next = ImpState{false, kBufX, kBufV};
+    }
+    return b;
+}
+
 // Replicas that read one model take the same weight tile in neighbouring blocks when the layer is
 // too large for an XCD's L2 to hold until the next replica comes by (measured: +14 % at m = 64 with
 // 16-25 MB layers; a few per cent slower for models that are cache-resident anyway, whose blocks
@@ -1239,9 +1313,14 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     const LayerGeom& g = h->layer[l];
     const bool bf16 = !eval && h->md.gemm == LC_GEMM_BF16;
     FwdArgs a;
-    const bool shared = eval || h->lazy_rows;   // one model for all groups
-    a.X = shared ? h->xbar : h->X;
-    a.x_stride = shared ? 0 : h->Ps;
+    // one model for all groups (the averaged one), or every replica's own rows -- which inside a
+    // period with implicit momentum may be the rows of the other buffer
+    const float* src = h->xbar;
+    int64_t src_stride = 0;
+    if (!eval) layer_weights(h, l, &src, &src_stride);
+    const bool shared = src_stride == 0;
+    a.X = src;
+    a.x_stride = src_stride;
     a.w_off = g.w_off;
     a.b_off = g.b_off;
     a.d_in = g.d_in;
@@ -1264,7 +1343,7 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     a.dz_fm = eval ? nullptr : S.dz_fm[h->L];
     a.loss = S.loss + static_cast<int64_t>(loss_offset) * kLossParts;
     a.eval = eval ? 1 : 0;
-    a.shared_w = (!eval && h->lazy_rows && shared_weight_order(h, g)) ? shared_set(h, S.G) : 0;
+    a.shared_w = (!eval && shared && shared_weight_order(h, g)) ? shared_set(h, S.G) : 0;
     // batch tiles per block: all of them, unless that leaves most of the chip idle
     int mt = mt_for(S.Bp);
     a.m_split = 1;
@@ -1369,11 +1448,17 @@ hipError_t launch_backward(lc_handle* h, int l, bool da_only) {
     const LayerGeom& g = h->layer[l];
     const bool bf16 = h->md.gemm == LC_GEMM_BF16;
     BwdArgs a;
-    a.X = h->X;
-    a.V = h->V;
+    const StepBufs sb = plan_step_buffers(h, l);
+    if (da_only && (sb.imp_in || !sb.ov)) return hipErrorInvalidValue;   // (the tau = 1 path: momentum is explicit there)
+    a.X = sb.ox;
+    a.V = sb.ov;
     a.x_stride = h->Ps;
-    a.Xr = h->lazy_rows ? h->xbar : h->X;
-    a.xr_stride = h->lazy_rows ? 0 : h->Ps;
+    a.Xr = sb.xr;
+    a.xr_stride = sb.xr_stride;
+    a.Aux = sb.aux;
+    a.aux_stride = sb.aux_stride;
+    a.imp_in = sb.imp_in;
+    a.inv_lr = h->md.lr > 0.f ? 1.f / h->md.lr : 0.f;
     a.w_off = g.w_off;
     a.b_off = g.b_off;
     a.d_in = g.d_in;
@@ -1396,7 +1481,7 @@ hipError_t launch_backward(lc_handle* h, int l, bool da_only) {
     a.n_row_blocks = g.dp_in / 64;
     a.col_split = 1;
     a.skip_x = h->defer_x ? 1 : 0;
-    a.shared_w = (h->lazy_rows && shared_weight_order(h, g)) ? shared_set(h, S.G) : 0;
+    a.shared_w = (sb.xr_stride == 0 && shared_weight_order(h, g)) ? shared_set(h, S.G) : 0;
     if (l == 1) {
         // no dA: the columns can be shared out, to fill the chip and to keep the walk of a
         // workgroup short (measured: walks of 2-4 trips stream faster than long ones, a single
@@ -1428,6 +1513,7 @@ hipError_t launch_backward(lc_handle* h, int l, bool da_only) {
                  : launch_bwd_wm<float>(a, S.Bp / 16, grid, h->stream);
     }
     timing_stop(h, kTimeBwd, l, kBwdRowOwner);
+    if (e == hipSuccess && !da_only) h->imp[l] = sb.next;
     return e;
 }
 

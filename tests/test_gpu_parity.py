@@ -1165,6 +1165,58 @@ def test_deferred_update_with_chunked_averaging(pkg, orc):
     assert np.isfinite(out[0][0])
 
 
+# ---------------------------------------------------------- implicit momentum
+
+IMPLICIT_CASES = [
+    # dims, m, B: row-owner backward kernel on three layers, ragged; the column-owner first-layer kernel
+    # with the next forward in it; unaligned rows
+    ([130, 70, 33, 7], 4, 48),
+    ([96, 256, 24, 10], 48, 30),
+    ([67, 129, 10], 3, 33),
+]
+
+
+@pytest.mark.parametrize("lazy", [False, True])
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("dims,m,B", IMPLICIT_CASES)
+def test_implicit_momentum_inside_periods(pkg, orc, dims, m, B, bf16, lazy):
+    """Inside a call the large layers may keep two consecutive models instead of model and momentum
+    (lc_set_implicit_momentum; forced on here at small shapes and for both operand types).  Calls of
+    2, 5, 1 and 7 steps -- two to seven of them without the momentum in memory, through both row
+    buffers in turn, from separate rows and from a pending broadcast -- against the oracle, each from
+    the oracle's state: model, momentum (explicit again at the end of every call) and losses at the
+    bar; then the averaging step."""
+    _say(f"implicit momentum dims={dims} m={m} B={B} bf16={bf16} lazy={lazy}")
+    tol = TOL16 if bf16 else TOL32
+    ref, run = _problem(pkg, orc, dims, m, B, wd=5e-4, bf16=bf16, lr=0.05, resident=False)
+    run.set_implicit_momentum(2)
+    run.set_lazy_broadcast(lazy)
+    for tau in (2, 5, 1, 7):
+        masks = UnitMasks()
+        _ref_steps(orc, ref, 11, tau, masks)
+        run.local_steps(tau)
+        _check_workers(run, ref, dims, tol, f"call of {tau}", masks, over="skip")
+        _check_losses(run, ref, tol, f"local losses, call of {tau}")
+        ref.average()
+        run.average()
+        X, _, _ = run.get_state()
+        _assert_close(X[0], ref.X[0], dims, tol, f"mean after {tau}", _xmask(ref, masks.union(range(m))), over="skip")
+        assert all(np.array_equal(X[i], X[0]) for i in range(1, m))
+        _force(run, ref)
+        if lazy:
+            run.average()   # identical rows: exact; leaves the broadcast pending, the next call starts from the one model
+    # the schedule driver: periods of 3, the last one shortened
+    masks = UnitMasks()
+    for j, tau in enumerate((3, 3, 2)):
+        _ref_steps(orc, ref, 11, tau, masks, fresh=j == 0)
+        ref.average()
+    run.run(8, 3)
+    X, V, k = run.get_state()
+    assert k == ref.k
+    _assert_close(X[0], ref.X[0], dims, tol, "after the driver", _xmask(ref, masks.union(range(m))), over="skip")
+    run.close()
+
+
 # -------------------------------------------------------------- random shapes
 
 def _random_case(seed):
