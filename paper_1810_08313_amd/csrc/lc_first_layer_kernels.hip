@@ -90,6 +90,19 @@ __device__ __forceinline__ f32x4 mma4(const Frag4<bf16_t>& a, const Frag4<bf16_t
                                                      0, 0, 0);
 }
 
+// Steps a wavefront requests ahead of the one it works on, and wavefronts per SIMD the register
+// budget is set for.  Up to 64 samples two workgroups share a CU (256 registers per lane) with one
+// step ahead: what the walk responds to is the number of wavefronts that can issue, not the depth
+// of a wavefront's queue (two steps ahead at one workgroup per CU: 1072 us on the 3072x2048 layer
+// of 64 replicas, one or two steps ahead at two per CU: 900 us, none ahead at three or four per
+// CU: 920 us).  At 128 samples the 32 accumulator tiles of the forward product leave room for one
+// workgroup per CU only.  (fp32 operands at 64 samples spill at 256 registers with a step ahead.)
+template <typename OT, int NT>
+struct FlBudget {
+    static constexpr int kWavesPerSimd = NT >= 8 ? 1 : 2;
+    static constexpr int kAhead = (NT == 4 && sizeof(OT) == 4) ? 0 : 1;
+};
+
 // One workgroup = one replica x 64 columns of W_1; its 4 wavefronts take the 16-row steps
 // wave, wave + 4, ... and never synchronise inside the walk: the dZ_1 slice is staged once, the
 // A_0 tiles go from memory straight into operand registers.  The loads of a wavefront's next PD
@@ -99,11 +112,11 @@ __device__ __forceinline__ f32x4 mma4(const Frag4<bf16_t>& a, const Frag4<bf16_t
 // Rows are 16-byte aligned and a multiple of 64 columns long and d_in is a multiple of 16 (the
 // launcher checks), so every weight access is one unconditional 16-byte instruction.
 template <typename OT, int NT, int WM>
-__global__ __launch_bounds__(256) void first_layer_kernel(FirstArgs a) {
+__global__ __launch_bounds__(256, (FlBudget<OT, NT>::kWavesPerSimd)) void first_layer_kernel(FirstArgs a) {
     constexpr int kPad = sizeof(OT) == 2 ? 8 : 4;
     constexpr int Bp = 16 * NT;
     constexpr int NS = Bp / 32;
-    constexpr int PD = NT >= 8 ? 1 : 2;
+    constexpr int PD = FlBudget<OT, NT>::kAhead;
     // the dZ^T slice during the walk; the wavefronts' partial Z_1' tiles after it
     constexpr size_t kSliceBytes = sizeof(OT) * kColChunk * (Bp + kPad);
     constexpr size_t kPartBytes = sizeof(float) * kFlWaves * Bp * (kColChunk + 4);
