@@ -111,7 +111,11 @@ struct FlBudget {
 // steps in flight stay below the 64 outstanding memory instructions a wavefront can have.
 // Rows are 16-byte aligned and a multiple of 64 columns long and d_in is a multiple of 16 (the
 // launcher checks), so every weight access is one unconditional 16-byte instruction.
-template <typename OT, int NT, int WM>
+// WM is the access mode of the state that streams (momentum or older model, all stores), WMR that of
+// the weights read: cached where all replicas read one model, which the neighbouring blocks want in
+// the L2.  (A template parameter, not a run-time flag: with the choice made per load the compiler
+// waited for each load before it issued the next.)
+template <typename OT, int NT, int WM, int WMR>
 __global__ __launch_bounds__(256, (FlBudget<OT, NT>::kWavesPerSimd)) void first_layer_kernel(FirstArgs a) {
     constexpr int kPad = sizeof(OT) == 2 ? 8 : 4;
     constexpr int Bp = 16 * NT;
@@ -172,9 +176,7 @@ __global__ __launch_bounds__(256, (FlBudget<OT, NT>::kWavesPerSimd)) void first_
         const float* vb = Va + static_cast<int64_t>(k0) * a.d_out;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            // (weights that all replicas share are wanted in the L2 by the neighbouring blocks)
-            if (WM == kWVectorStream && a.shared_w) x.w[r] = load_wm<kWVector>(at_byte(wb, woff[r]), 0, a.d_out, true);
-            else x.w[r] = load_wm<WM>(at_byte(wb, woff[r]), 0, a.d_out, true);
+            x.w[r] = load_wm<WMR>(at_byte(wb, woff[r]), 0, a.d_out, true);
             x.v[r] = load_wm<WM>(at_byte(vb, woff[r]), 0, a.d_out, true);
         }
         const OT* ab = AT + static_cast<int64_t>(k0) * Bp;
@@ -337,14 +339,256 @@ __global__ __launch_bounds__(256, (FlBudget<OT, NT>::kWavesPerSimd)) void first_
     }
 }
 
+
+// The same step at 128 samples.  Sharing out the rows alone leaves each wavefront with the whole
+// 128 x 64 tile of Z_1' (128 accumulator registers per lane), so four wavefronts fill a CU's register
+// file with two steps in flight each, and the walk waits for memory.  Here a workgroup has 8
+// wavefronts that share out BOTH: wavefront w updates the 16-row steps 8 r + w (r = 0, 1, ... :
+// "rounds") as above, publishes each updated tile in LDS in operand precision, and after one
+// barrier per round multiplies all 8 tiles of the round with ITS 16 samples of A_0' -- 4
+// accumulator tiles per wavefront, complete at the end of the walk, nothing to add up across
+// wavefronts.  Two sets of loads per wavefront, twice the wavefronts (3072x1024, 16 replicas: 161 ->
+// 148 us; a third set changes nothing, nor does leaving out either product: what remains is the
+// memory system's rate for 256 column walks).
+// The tiles are double-buffered: a wavefront can only write round r + 1's buffer (that of round
+// r - 1) after the barrier of round r, which every reader of round r - 1 has passed.
+constexpr int kWideWaves = 8;
+
+template <typename OT, int WM, int WMR, int PD = 1>
+__global__ __launch_bounds__(64 * kWideWaves) void first_layer_wide_kernel(FirstArgs a) {
+    static_assert(sizeof(OT) == 2, "operand fragments of fp32 do not fit the register budget here");
+    constexpr int kPad = 8;
+    constexpr int Bp = 128, NS = Bp / 32, NTH = 64 * kWideWaves;
+    constexpr size_t kSliceBytes = sizeof(OT) * kColChunk * (Bp + kPad);
+    constexpr size_t kTileBytes = 2 * kWideWaves * 2 * 64 * sizeof(bf16x8);
+    constexpr size_t kPartBytes = sizeof(float) * Bp * (kColChunk + 4);
+    constexpr size_t kWalkBytes = kSliceBytes + kTileBytes;
+    __shared__ __attribute__((aligned(16))) char smem[kWalkBytes > kPartBytes ? kWalkBytes : kPartBytes];
+    __shared__ float bias_s[kColChunk];
+    OT (*dzt)[Bp + kPad] = reinterpret_cast<OT (*)[Bp + kPad]>(smem);
+    // [buffer][wavefront][half][lane]: a lane's 4 x 4 block of the tile as 4 operand fragments
+    // (columns 4 j + t, rows 4 q ..), 16 bytes per lane and half: consecutive lanes, no bank conflicts
+    bf16x8 (*wt)[kWideWaves][2][64] = reinterpret_cast<bf16x8 (*)[kWideWaves][2][64]>(smem + kSliceBytes);
+
+    const int64_t logical = xcd_logical_block(a.total_blocks);
+    if (logical < 0) return;
+    int g, chunk;
+    shared_order(logical, a.n_chunks, a.shared_w, g, chunk);
+    const int c0 = chunk * kColChunk;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j = lane & 15, q = lane >> 4;
+
+    float* W = a.X + g * a.x_stride + a.w_off;
+    const float* Wr = a.Xr + g * a.xr_stride + a.w_off;
+    float* Vw = a.V ? a.V + g * a.x_stride + a.w_off : nullptr;
+    const float* Va = a.Aux + g * a.aux_stride + a.w_off;
+    const OT* AT = static_cast<const OT*>(a.a_fm) + static_cast<int64_t>(g) * a.dp_in * Bp;
+    // this wavefront's 16 samples of the next step's input
+    const OT* AN = static_cast<const OT*>(a.an_bm) + (static_cast<int64_t>(g) * Bp + 16 * wave) * a.dp_in;
+    const int n_rounds = a.d_in / (16 * kWideWaves);   // the launcher checks that this divides
+
+    struct Set {
+        float4 w[4], v[4];            // rows k0 + 4 q + r, columns c0 + 4 j ..
+        Frag<OT> af[NS];              // A_0^T tile of this wavefront's 16 rows
+        Frag4<OT> an[kWideWaves];     // A_0' of this wavefront's samples, 4 entries for each tile of the round
+    };
+    Set set[PD + 1];
+
+    unsigned woff[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) woff[r] = 4u * static_cast<unsigned>((4 * q + r) * a.d_out + c0 + 4 * j);
+    const unsigned atoff = static_cast<unsigned>(sizeof(OT)) * static_cast<unsigned>(j * Bp + 8 * q);
+    const unsigned anoff = static_cast<unsigned>(sizeof(OT)) * static_cast<unsigned>(j * a.dp_in + 4 * q);
+    auto at_byte = [](auto* base, unsigned off) {
+        using T = std::remove_pointer_t<decltype(base)>;
+        using C = std::conditional_t<std::is_const_v<T>, const char, char>;
+        return reinterpret_cast<T*>(reinterpret_cast<C*>(base) + off);
+    };
+
+    auto load_round = [&](int r, Set& x) {
+        // rounds past the end are never used: the last one is read for them (no branch between the loads)
+        const int rr = r < n_rounds ? r : n_rounds - 1;
+        const int k0 = 16 * (kWideWaves * rr + wave);
+        const float* wb = Wr + static_cast<int64_t>(k0) * a.d_out;
+        const float* vb = Va + static_cast<int64_t>(k0) * a.d_out;
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            x.w[r4] = load_wm<WMR>(at_byte(wb, woff[r4]), 0, a.d_out, true);
+            x.v[r4] = load_wm<WM>(at_byte(vb, woff[r4]), 0, a.d_out, true);
+        }
+        const OT* ab = AT + static_cast<int64_t>(k0) * Bp;
+#pragma unroll
+        for (int st = 0; st < NS; ++st) x.af[st] = load8(at_byte(ab + 32 * st, atoff));
+        const OT* nb = AN + 16 * kWideWaves * rr;
+#pragma unroll
+        for (int u = 0; u < kWideWaves; ++u) x.an[u] = load4(at_byte(nb + 16 * u, anoff));
+    };
+
+#pragma unroll
+    for (int p = 0; p < PD; ++p) load_round(p, set[p]);
+    {
+        const OT* ZT = static_cast<const OT*>(a.dz_fm) + (static_cast<int64_t>(g) * a.dp_out + c0) * Bp;
+        for (int p = tid; p < kColChunk * (Bp / 8); p += NTH) {
+            const int c = p / (Bp / 8), seg = p % (Bp / 8);
+            *reinterpret_cast<Frag<OT>*>(&dzt[(c & 3) * 16 + (c >> 2)][seg * 8]) = load8(ZT + static_cast<int64_t>(p) * 8);
+        }
+    }
+    __syncthreads();
+    if (tid < kColChunk) {
+        float* bx = a.X + g * a.x_stride + a.b_off + c0 + tid;
+        const float x = a.Xr[g * a.xr_stride + a.b_off + c0 + tid];
+        float vb0 = a.Aux[g * a.aux_stride + a.b_off + c0 + tid];
+        if (a.imp_in) vb0 = (vb0 - x) * a.inv_lr;
+        const OT* zr = dzt[(tid & 3) * 16 + (tid >> 2)];
+        float sb = 0.f;
+        for (int b = 0; b < a.B; ++b) sb += to_f32(zr[b]);
+        const float vb = a.beta * vb0 + (sb + a.wd * x);
+        if (a.V) a.V[g * a.x_stride + a.b_off + c0 + tid] = vb;
+        *bx = x - a.lr * vb;
+        bias_s[tid] = x - a.lr * vb;
+    }
+
+    f32x4 facc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) facc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto process = [&](int r, Set& x) {
+        const int64_t row0 = static_cast<int64_t>(16 * (kWideWaves * r + wave)) * a.d_out;
+        float* ws = W + row0;
+        float* vs = Vw ? Vw + row0 : nullptr;
+        f32x4 acc[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int st = 0; st < NS; ++st)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const Frag<OT> zf = *reinterpret_cast<const Frag<OT>*>(&dzt[t * 16 + j][32 * st + 8 * q]);
+                acc[t] = mma8(x.af[st], zf, acc[t]);
+            }
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            consume_here(x.w[r4]);
+            consume_here(x.v[r4]);
+            if (a.imp_in) {   // the tile holds the parameters of one step earlier: v = (x_prev - x) / lr
+                x.v[r4].x = (x.v[r4].x - x.w[r4].x) * a.inv_lr;
+                x.v[r4].y = (x.v[r4].y - x.w[r4].y) * a.inv_lr;
+                x.v[r4].z = (x.v[r4].z - x.w[r4].z) * a.inv_lr;
+                x.v[r4].w = (x.v[r4].w - x.w[r4].w) * a.inv_lr;
+            }
+            x.v[r4].x = a.beta * x.v[r4].x + (acc[0][r4] + a.wd * x.w[r4].x);
+            x.v[r4].y = a.beta * x.v[r4].y + (acc[1][r4] + a.wd * x.w[r4].y);
+            x.v[r4].z = a.beta * x.v[r4].z + (acc[2][r4] + a.wd * x.w[r4].z);
+            x.v[r4].w = a.beta * x.v[r4].w + (acc[3][r4] + a.wd * x.w[r4].w);
+            x.w[r4].x -= a.lr * x.v[r4].x;
+            x.w[r4].y -= a.lr * x.v[r4].y;
+            x.w[r4].z -= a.lr * x.v[r4].z;
+            x.w[r4].w -= a.lr * x.v[r4].w;
+            if (vs) store_wm<WM>(at_byte(vs, woff[r4]), 0, a.d_out, true, x.v[r4]);
+            store_wm<WM>(at_byte(ws, woff[r4]), 0, a.d_out, true, x.w[r4]);
+        }
+        // the updated tile, as the 4 operand fragments of this lane
+        Frag4<OT> b0, b1, b2, b3;
+        pack4(b0, x.w[0].x, x.w[1].x, x.w[2].x, x.w[3].x);
+        pack4(b1, x.w[0].y, x.w[1].y, x.w[2].y, x.w[3].y);
+        pack4(b2, x.w[0].z, x.w[1].z, x.w[2].z, x.w[3].z);
+        pack4(b3, x.w[0].w, x.w[1].w, x.w[2].w, x.w[3].w);
+        bf16x8 lo, hi;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            lo[e] = b0.v[e]; lo[4 + e] = b1.v[e];
+            hi[e] = b2.v[e]; hi[4 + e] = b3.v[e];
+        }
+        wt[r & 1][wave][0][lane] = lo;
+        wt[r & 1][wave][1][lane] = hi;
+        __syncthreads();
+        // Z_1'[these 16 samples] += A_0'[.., the round's 128 rows] W_1[the round's 128 rows, :]
+#pragma unroll
+        for (int u = 0; u < kWideWaves; ++u) {
+            const bf16x8 l2 = wt[r & 1][u][0][lane], h2 = wt[r & 1][u][1][lane];
+            Frag4<OT> f0, f1, f2, f3;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                f0.v[e] = l2[e]; f1.v[e] = l2[4 + e];
+                f2.v[e] = h2[e]; f3.v[e] = h2[4 + e];
+            }
+            facc[0] = mma4(x.an[u], f0, facc[0]);
+            facc[1] = mma4(x.an[u], f1, facc[1]);
+            facc[2] = mma4(x.an[u], f2, facc[2]);
+            facc[3] = mma4(x.an[u], f3, facc[3]);
+        }
+    };
+
+    // groups of PD + 1 rounds without control flow in between, then the rounds whose loads are under way
+    int r0 = 0;
+    for (; r0 + PD < n_rounds; r0 += PD + 1) {
+#pragma unroll
+        for (int u = 0; u <= PD; ++u) {
+            load_round(r0 + u + PD, set[(u + PD) % (PD + 1)]);
+            process(r0 + u, set[u]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < PD; ++u)
+        if (r0 + u < n_rounds) process(r0 + u, set[u]);   // uniform over the workgroup
+
+    // A_1' = ReLU(Z_1' + b_1), through LDS for the two layouts of the stores
+    __syncthreads();   // every wavefront is done with the slice and the tiles that share this memory
+    float (*part)[kColChunk + 4] = reinterpret_cast<float (*)[kColChunk + 4]>(smem);
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+        float4 z = make_float4(facc[0][r4] + bias_s[4 * j], facc[1][r4] + bias_s[4 * j + 1], facc[2][r4] + bias_s[4 * j + 2],
+                               facc[3][r4] + bias_s[4 * j + 3]);
+        z = make_float4(z.x > 0.f ? z.x : 0.f, z.y > 0.f ? z.y : 0.f, z.z > 0.f ? z.z : 0.f, z.w > 0.f ? z.w : 0.f);
+        *reinterpret_cast<float4*>(&part[16 * wave + 4 * q + r4][4 * j]) = z;
+    }
+    __syncthreads();
+    OT* obm = static_cast<OT*>(a.out_bm) + static_cast<int64_t>(g) * Bp * a.dp_out;
+    OT* ofm = static_cast<OT*>(a.out_fm) + static_cast<int64_t>(g) * a.dp_out * Bp;
+    for (int e = tid; e < Bp * (kColChunk / 8); e += NTH) {
+        const int b = e / (kColChunk / 8), cl = (e % (kColChunk / 8)) * 8;
+        if (b >= a.B) continue;
+        float y[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) y[i] = part[b][cl + i];
+        store8(obm + static_cast<int64_t>(b) * a.dp_out + c0 + cl, y);
+    }
+    for (int e = tid; e < kColChunk * (Bp / 8); e += NTH) {
+        const int c = e / (Bp / 8), bl = (e % (Bp / 8)) * 8;
+        if (bl >= a.B) continue;
+        float y[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) y[i] = bl + i < a.B ? part[bl + i][c] : 0.f;
+        if (bl + 8 <= a.B) {
+            store8(ofm + static_cast<int64_t>(c0 + c) * Bp + bl, y);
+        } else {
+            for (int i = 0; bl + i < a.B; ++i) ofm[static_cast<int64_t>(c0 + c) * Bp + bl + i] = static_cast<OT>(y[i]);
+        }
+    }
+}
+
 template <typename OT, int NT>
 void launch_fl_wm(const FirstArgs& a, bool stream_w, unsigned grid, hipStream_t st) {
-    if (stream_w) hipLaunchKernelGGL((first_layer_kernel<OT, NT, kWVectorStream>), dim3(grid), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((first_layer_kernel<OT, NT, kWVector>), dim3(grid), dim3(256), 0, st, a);
+    if (stream_w && !a.shared_w)
+        hipLaunchKernelGGL((first_layer_kernel<OT, NT, kWVectorStream, kWVectorStream>), dim3(grid), dim3(256), 0, st, a);
+    else if (stream_w) hipLaunchKernelGGL((first_layer_kernel<OT, NT, kWVectorStream, kWVector>), dim3(grid), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((first_layer_kernel<OT, NT, kWVector, kWVector>), dim3(grid), dim3(256), 0, st, a);
 }
 
 template <typename OT>
 hipError_t launch_fl(const FirstArgs& a, int nt, bool stream_w, unsigned grid, hipStream_t st) {
+    if constexpr (sizeof(OT) == 2) {
+        if (nt == 8 && a.d_in % (16 * kWideWaves) == 0) {
+            const dim3 block(64 * kWideWaves);
+            if (stream_w && !a.shared_w)
+                hipLaunchKernelGGL((first_layer_wide_kernel<OT, kWVectorStream, kWVectorStream>), dim3(grid), block, 0, st, a);
+            else if (stream_w) hipLaunchKernelGGL((first_layer_wide_kernel<OT, kWVectorStream, kWVector>), dim3(grid), block, 0, st, a);
+            else hipLaunchKernelGGL((first_layer_wide_kernel<OT, kWVector, kWVector>), dim3(grid), block, 0, st, a);
+            return hipGetLastError();
+        }
+    }
     if (nt == 2) launch_fl_wm<OT, 2>(a, stream_w, grid, st);
     else if (nt == 4) launch_fl_wm<OT, 4>(a, stream_w, grid, st);
     else launch_fl_wm<OT, 8>(a, stream_w, grid, st);

@@ -529,10 +529,14 @@ def test_resident_repeatable_and_barrier_timeout_reported(pkg, orc):
 
 FIRST_LAYER_CASES = [
     # dims, m, B: shapes the column-owner first-layer kernel takes (m * d1 / 64 >= 192, d0 a
-    # multiple of 16): 2, 4 and 8 batch tiles; 6, 5 and 7 sixteen-row steps over 4 wavefronts
+    # multiple of 16): 2, 4 and 8 batch tiles; 6, 5 and 7 sixteen-row steps over 4 wavefronts; then
+    # the 8-wavefront kernel of bf16 operands at 65..128 samples (d0 a multiple of 128): three rounds
+    # (a pair and a single one) and one round
     ([96, 256, 24, 10], 48, 30),
     ([80, 192, 10], 64, 64),
     ([112, 512, 24, 10], 32, 120),
+    ([384, 512, 24, 10], 32, 100),
+    ([128, 256, 10], 48, 128),
 ]
 
 
@@ -1169,10 +1173,11 @@ def test_deferred_update_with_chunked_averaging(pkg, orc):
 
 IMPLICIT_CASES = [
     # dims, m, B: row-owner backward kernel on three layers, ragged; the column-owner first-layer kernel
-    # with the next forward in it; unaligned rows
+    # with the next forward in it; unaligned rows; the 8-wavefront first-layer kernel (bf16 operands)
     ([130, 70, 33, 7], 4, 48),
     ([96, 256, 24, 10], 48, 30),
     ([67, 129, 10], 3, 33),
+    ([256, 512, 24, 10], 32, 100),
 ]
 
 
