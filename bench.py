@@ -197,7 +197,7 @@ def bench_mlp(args, pkg, synth, name, cache, headline=True):
            "deferred_broadcast": not args.eager, "resident_step_kernel": resident,
            "first_layer_fusion": not args.no_first_layer_fusion,
            "deferred_update_at_tau_1": not args.no_deferred_update and not args.eager,
-           "implicit_momentum_inside_periods": not args.no_implicit_momentum and w.bf16 and 8.0 * w.m * w.P > 256 * 2**20}
+           "implicit_momentum_inside_periods": run.implicit_momentum_layers() > 0}
     if name == "cfg3":
         cfg["note"] = ("at this configuration's own learning rate and momentum the averaged model stays near ln 10 "
                        "with periods of 20, so the rule keeps tau near tau0: an adapting tau is not exercised here")

@@ -253,10 +253,16 @@ int lc_set_deferred_update(lc_handle* h, int on);
  * in training).  That is far below the rounding of bf16 operands and above that of fp32 operands.
  *   mode 1 (default): layers of at least 1 MB, the last layer excepted, of LC_KIND_MLP runs with
  *           LC_GEMM_BF16 whose state exceeds the caches (X and V above 256 MB), on the
- *           launch-per-layer path, while block momentum is off and lr > 0;
+ *           launch-per-layer path, while block momentum is off and lr >= 1e-4 (the absolute
+ *           error of the recovered momentum grows as 1 / lr);
  *   mode 2: every layer but the last, with either operand type and at any size;
  *   mode 0: off -- x in X and v in V after every step. */
 int lc_set_implicit_momentum(lc_handle* h, int mode);
+
+/* Number of layers of this (attached) handle whose steps inside a period take the implicit form
+ * under the current mode, operand type, sizes, learning rate and block-momentum setting (0 where
+ * the resident step kernel runs the steps); negative on error. */
+int lc_implicit_momentum_layers(const lc_handle* h);
 
 /* 1 if lc_local_steps() of this (attached) handle takes the resident step kernel, else 0. */
 int lc_resident_active(const lc_handle* h);

@@ -91,6 +91,8 @@ def lib() -> C.CDLL:
     L.lc_set_implicit_momentum.argtypes = [vp, C.c_int]
     L.lc_set_resident.restype = C.c_int
     L.lc_set_resident.argtypes = [vp, C.c_int]
+    L.lc_implicit_momentum_layers.restype = C.c_int
+    L.lc_implicit_momentum_layers.argtypes = [vp]
     L.lc_resident_active.restype = C.c_int
     L.lc_resident_active.argtypes = [vp]
     L.lc_set_barrier_polls.restype = C.c_int
@@ -323,6 +325,12 @@ class LocalSGD:
         """False/0: launch-per-layer kernels; True/1: resident step kernel where it applies; 2: and
         in-kernel averaging steps at every shape it handles (see lc_local_periods)."""
         self._check(self._L.lc_set_resident(self._h, int(on)), "lc_set_resident")
+
+    def implicit_momentum_layers(self) -> int:
+        """Layers whose steps inside a period keep two consecutive models instead of model and momentum."""
+        rc = self._L.lc_implicit_momentum_layers(self._h)
+        self._check(min(rc, 0), "lc_implicit_momentum_layers")
+        return rc
 
     def resident_active(self) -> bool:
         rc = self._L.lc_resident_active(self._h)

@@ -578,6 +578,15 @@ int lc_set_implicit_momentum(lc_handle* h, int mode) {
     return LC_OK;
 }
 
+int lc_implicit_momentum_layers(const lc_handle* h) {
+    if (!h) return LC_ERR_ARG;
+    if (!h->attached) return LC_ERR_STATE;
+    if (h->res_on && h->res_a1x) return 0;
+    int n = 0;
+    for (int l = 1; l <= h->L; ++l) n += implicit_layer_ok(h, l) ? 1 : 0;
+    return n;
+}
+
 int lc_set_deferred_update(lc_handle* h, int on) {
     if (!h) return LC_ERR_ARG;
     h->defer_x_on = on != 0;

@@ -1250,7 +1250,8 @@ bool implicit_layer_ok(const lc_handle* h, int l) {
     if (h->bm_on || !(h->md.lr > 0.f)) return false;
     if (h->imp_mode == 2) return true;
     const LayerGeom& g = h->layer[l];
-    return h->md.gemm == LC_GEMM_BF16 && h->stream_weights && 4.0 * g.d_in * g.d_out >= 1024.0 * 1024;
+    // (the recovered momentum is off by up to ulp(x) / (2 lr) per element: not with very small rates)
+    return h->md.gemm == LC_GEMM_BF16 && h->stream_weights && h->md.lr >= 1e-4f && 4.0 * g.d_in * g.d_out >= 1024.0 * 1024;
 }
 
 namespace {

@@ -1452,12 +1452,14 @@ def test_full_size_period_sampled_replicas(pkg, orc, name, replicas):
     the units whose gate some step of the period leaves undecided -- at 32 samples per batch and
     three hidden layers of bf16 activations that is most of the upper layers after ten steps, so
     the count is printed, and a layer of which less than a tenth is left is not compared.  Then
-    the averaging step: sampled columns bit for bit against the mean of the rows the GPU held."""
+    the averaging step: sampled columns bit for bit against the mean of the rows the GPU held.
+    (The momentum of the large layers is implicit inside the period, as in the benchmark.)"""
     _say(f"full-size period {name}")
     w, omd, gmd = _full_size(pkg, orc, name, LR_SCALE_FULL)
     tau = w.tau0
     run = pkg.LocalSGD(w.m, gmd, w.seed, w.x1, w.data, w.labels)
     run.set_lazy_broadcast(True)
+    assert run.implicit_momentum_layers() == len(w.dims) - 2   # every layer but the last
     run.local_steps(tau)
     X, V, k = run.get_state()
     ll = run.local_losses()
