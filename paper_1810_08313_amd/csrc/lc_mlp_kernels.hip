@@ -447,16 +447,16 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
                     const float* z = red[t];
                     float zmax = z[0];
                     for (int c = 1; c < a.d_out; ++c) zmax = fmaxf(zmax, z[c]);
-                    float sum = 0.f;
-                    for (int c = 0; c < a.d_out; ++c) sum += expf(z[c] - zmax);
-                    nll = -(z[y] - zmax - logf(sum));
+                    float s_other = 0.f;
+                    for (int c = 0; c < a.d_out; ++c) s_other += c == y ? 0.f : expf(z[c] - zmax);
+                    const float e_y = expf(z[y] - zmax);
+                    nll = xent_loss(s_other, e_y, z[y] - zmax);
                     if (a.dz_bm) {
                         OT* dbm = static_cast<OT*>(a.dz_bm) + (static_cast<int64_t>(g) * a.Bp + b) * a.dp_out;
                         OT* dfm = static_cast<OT*>(a.dz_fm) + static_cast<int64_t>(g) * a.dp_out * a.Bp + b;
-                        const float inv = 1.f / sum, invB = 1.f / static_cast<float>(a.B);
+                        const float inv = 1.f / (s_other + e_y), invB = 1.f / static_cast<float>(a.B);
                         for (int c = 0; c < a.d_out; ++c) {
-                            const float pr = expf(z[c] - zmax) * inv;
-                            const OT d = static_cast<OT>((pr - (c == y ? 1.f : 0.f)) * invB);
+                            const OT d = static_cast<OT>(xent_delta(expf(z[c] - zmax), c == y, s_other, inv) * invB);
                             dbm[c] = d;
                             dfm[static_cast<int64_t>(c) * a.Bp] = d;
                         }
@@ -543,16 +543,16 @@ __global__ __launch_bounds__(128) void softmax_kernel(SoftmaxArgs a) {
             const float* z = a.logits + (static_cast<int64_t>(g) * a.Bp + b) * a.dpL;
             float zmax = z[0];
             for (int c = 1; c < a.C; ++c) zmax = fmaxf(zmax, z[c]);
-            float sum = 0.f;
-            for (int c = 0; c < a.C; ++c) sum += expf(z[c] - zmax);
-            nll = -(z[y] - zmax - logf(sum));
+            float s_other = 0.f;
+            for (int c = 0; c < a.C; ++c) s_other += c == y ? 0.f : expf(z[c] - zmax);
+            const float e_y = expf(z[y] - zmax);
+            nll = xent_loss(s_other, e_y, z[y] - zmax);
             if (a.dz_bm) {
                 OT* dbm = static_cast<OT*>(a.dz_bm) + (static_cast<int64_t>(g) * a.Bp + b) * a.dpL;
                 OT* dfm = static_cast<OT*>(a.dz_fm) + static_cast<int64_t>(g) * a.dpL * a.Bp + b;
-                const float inv = 1.f / sum, invB = 1.f / static_cast<float>(a.B);
+                const float inv = 1.f / (s_other + e_y), invB = 1.f / static_cast<float>(a.B);
                 for (int c = 0; c < a.C; ++c) {
-                    const float p = expf(z[c] - zmax) * inv;
-                    const OT d = static_cast<OT>((p - (c == y ? 1.f : 0.f)) * invB);
+                    const OT d = static_cast<OT>(xent_delta(expf(z[c] - zmax), c == y, s_other, inv) * invB);
                     dbm[c] = d;
                     dfm[static_cast<int64_t>(c) * a.Bp] = d;
                 }
@@ -1005,13 +1005,13 @@ __global__ __launch_bounds__(512) void head_kernel(HeadArgs a) {
                     const float* z = red[b];
                     float zmax = z[0];
                     for (int c = 1; c < a.d_out; ++c) zmax = fmaxf(zmax, z[c]);
-                    float sum = 0.f;
-                    for (int c = 0; c < a.d_out; ++c) sum += expf(z[c] - zmax);
-                    nll = -(z[y] - zmax - logf(sum));
-                    const float inv = 1.f / sum, invB = 1.f / static_cast<float>(a.B);
+                    float s_other = 0.f;
+                    for (int c = 0; c < a.d_out; ++c) s_other += c == y ? 0.f : expf(z[c] - zmax);
+                    const float e_y = expf(z[y] - zmax);
+                    nll = xent_loss(s_other, e_y, z[y] - zmax);
+                    const float inv = 1.f / (s_other + e_y), invB = 1.f / static_cast<float>(a.B);
                     for (int c = 0; c < a.d_out; ++c) {
-                        const float pr = expf(z[c] - zmax) * inv;
-                        const OT d = static_cast<OT>((pr - (c == y ? 1.f : 0.f)) * invB);
+                        const OT d = static_cast<OT>(xent_delta(expf(z[c] - zmax), c == y, s_other, inv) * invB);
                         dz_lds[b][c] = d;
                         dzt_lds[(c & 3) * 16 + (c >> 2)][b] = d;
                     }

@@ -170,6 +170,18 @@ __device__ __forceinline__ void store_wm(float* row, int c, int d_out, bool vec,
 // w' = fma(-lr, v', w).  Kernels whose results are compared bit for bit (the backward kernel, the
 // tau = 1 first-layer kernel, the averaging kernels that form x_bar - lr v themselves) must not
 // leave the choice of which products are fused to the compiler's contraction pass.
+// Softmax cross-entropy of one sample from e_c = exp(z_c - max z), without the cancellation of
+// "p_y - 1" and "log(sum)" when the label's class holds almost all of the mass (a well-fitted
+// sample: p_y = 1 - 1e-5 in fp32 leaves three digits of p_y - 1).  With s the sum of e_c over the
+// classes OTHER than the label y:
+//     p_y - 1 = -s / (s + e_y),      -log p_y = log1p(s / e_y)   (while s < e_y; else the plain form).
+__device__ __forceinline__ float xent_loss(float s_other, float e_y, float zy_minus_max) {
+    return s_other < e_y ? log1pf(s_other / e_y) : logf(s_other + e_y) - zy_minus_max;
+}
+__device__ __forceinline__ float xent_delta(float e_c, bool is_label, float s_other, float inv_sum) {
+    return (is_label ? -s_other : e_c) * inv_sum;
+}
+
 __device__ __forceinline__ float momentum_update(float beta, float v, float g, float wd, float w) {
     return __builtin_fmaf(beta, v, __builtin_fmaf(wd, w, g));
 }

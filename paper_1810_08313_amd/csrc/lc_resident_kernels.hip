@@ -409,14 +409,15 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(ResArgs a) {
 #pragma unroll
             for (int o = 8; o > 0; o >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o, 16));
             const float ex = valid ? expf(z - zmax) : 0.f;
-            float sum = ex;
+            float s_other = c == y ? 0.f : ex;   // over the classes other than the label (see xent_loss)
 #pragma unroll
-            for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 16);
-            const float zy = __shfl(z, y >= 0 ? y : 0, 16);
+            for (int o = 8; o > 0; o >>= 1) s_other += __shfl_xor(s_other, o, 16);
+            const float zy = __shfl(z, y >= 0 ? y : 0, 16), sum = s_other + __shfl(ex, y >= 0 ? y : 0, 16);
             float dz = 0.f;
             if (y >= 0 && valid)
-                dz = round_operand((ex * (1.f / sum) - (c == y ? 1.f : 0.f)) * (1.f / static_cast<float>(a.B)), OT());
+                dz = round_operand(xent_delta(ex, c == y, s_other, 1.f / sum) * (1.f / static_cast<float>(a.B)), OT());
             z2s[b][c] = dz;
+            // (the step's own loss is a by-product here: the plain form, without the log1p of xent_loss)
             if (c == 0) lred[b] = y >= 0 ? -(zy - zmax - logf(sum)) : 0.f;
         }
         __syncthreads();
@@ -638,13 +639,13 @@ __global__ __launch_bounds__(kResThreads) void resident1_kernel(Res1Args a) {
 #pragma unroll
             for (int o = 8; o > 0; o >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o, 16));
             const float ex = valid ? expf(z - zmax) : 0.f;
-            float sum = ex;
+            float s_other = c == y ? 0.f : ex;   // over the classes other than the label (see xent_loss)
 #pragma unroll
-            for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 16);
-            const float zy = __shfl(z, y >= 0 ? y : 0, 16);
+            for (int o = 8; o > 0; o >>= 1) s_other += __shfl_xor(s_other, o, 16);
+            const float zy = __shfl(z, y >= 0 ? y : 0, 16), sum = s_other + __shfl(ex, y >= 0 ? y : 0, 16);
             float dz = 0.f;
             if (y >= 0 && valid)
-                dz = round_operand((ex * (1.f / sum) - (c == y ? 1.f : 0.f)) * (1.f / static_cast<float>(a.B)), OT());
+                dz = round_operand(xent_delta(ex, c == y, s_other, 1.f / sum) * (1.f / static_cast<float>(a.B)), OT());
             zs[b][c] = dz;
             dzt[c][b] = static_cast<OT>(dz);
             if (c == 0) lred[b] = y >= 0 ? -(zy - zmax - logf(sum)) : 0.f;
