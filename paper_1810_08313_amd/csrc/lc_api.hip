@@ -125,9 +125,12 @@ size_t carve(lc_handle* h, char* base) {
             size_t n = (static_cast<size_t>(128) << 20) / slot_bytes;
             S.slots = n < kGatherSlots ? kGatherSlots : (n > 4 * kGatherSlots ? 4 * kGatherSlots : static_cast<int>(n));
             // the first-layer kernel folds a step's first forward pass into the step before it, which
-            // needs that step's inputs gathered by the same launch: fewer, longer runs (400 MB at the
-            // two large configurations)
-            if (first_layer_kernel_ok(h) && S.slots < 2 * kGatherSlots) S.slots = 2 * kGatherSlots;
+            // needs that step's inputs gathered by the same launch: fewer, longer runs -- 32 steps
+            // where that stays within 1 GB (800 MB at the two large configurations: a period of 20
+            // is then gathered whole), else 16
+            if (first_layer_kernel_ok(h) && S.slots < 4 * kGatherSlots)
+                S.slots = 4 * kGatherSlots * slot_bytes <= (static_cast<size_t>(1) << 30) ? 4 * kGatherSlots
+                          : (S.slots < 2 * kGatherSlots ? 2 * kGatherSlots : S.slots);
         }
         S.cur_slot = 0;
         for (int l = 0; l <= L; ++l) {
@@ -286,8 +289,9 @@ int run_periods(lc_handle* h, int tau, int n_periods, bool average) {
                 h->defer_x = defer;
                 for (int u = 0; u < in_period; ++u, ++t) {
                     h->train.cur_slot = t;
-                    // (the last step of a period, and of what this chunk holds of it, leaves x in X and v in V)
-                    const int r = one_local_step(h, u + 1 < in_period, !defer && u + 1 < in_period);
+                    // (the last step of a period -- of a call -- leaves x in X and v in V; a period
+                    // longer than one gather launch stays implicit across the launches)
+                    const int r = one_local_step(h, u + 1 < in_period, !defer && pos + u + 1 < tau);
                     if (r != LC_OK) {
                         h->defer_x = false;
                         h->sync_done = 0;
