@@ -9,7 +9,8 @@
 //     dW_1 = A_0^T dZ_1,   v <- beta v + dW_1 + wd w,   w <- w - lr v        (step k)
 // the updated tile is used at once as the operand of
 //     Z_1' = A_0' W_1 + b_1                                                  (step k+1)
-// and W_1 crosses the memory system 16 instead of 20 bytes per parameter and step.
+// and W_1 crosses the memory system 16 instead of 20 bytes per parameter and step (12 instead of
+// 16 where the momentum is implicit, see FirstArgs::Aux).
 //
 // This needs no exchange between lanes: the dW tile comes out of the matrix cores in accumulator
 // layout (lane (j, q) holds rows 4q..4q+3 of a 16-row block, column j), and a matrix instruction
@@ -95,7 +96,8 @@ __device__ __forceinline__ f32x4 mma4(const Frag4<bf16_t>& a, const Frag4<bf16_t
 // step ahead: what the walk responds to is the number of wavefronts that can issue, not the depth
 // of a wavefront's queue (two steps ahead at one workgroup per CU: 1072 us on the 3072x2048 layer
 // of 64 replicas, one or two steps ahead at two per CU: 900 us, none ahead at three or four per
-// CU: 920 us).  At 128 samples the 32 accumulator tiles of the forward product leave room for one
+// CU: 920 us -- measured while the weight-read mode was still a per-load choice, see WMR below;
+// 887 us since).  At 128 samples the 32 accumulator tiles of the forward product leave room for one
 // workgroup per CU only.  (fp32 operands at 64 samples spill at 256 registers with a step ahead.)
 template <typename OT, int NT>
 struct FlBudget {
