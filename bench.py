@@ -61,6 +61,8 @@ def parse():
                     help="resident kernel: exchange through device scope (see lc_set_xcd_local_exchange)")
     ap.add_argument("--no-deferred-update", action="store_true",
                     help="at tau = 1 write every replica's weights in the step (lc_set_deferred_update(0))")
+    ap.add_argument("--fused-averaging", type=int, default=None, choices=[0, 1, 2],
+                    help="lc_set_fused_averaging: 0 off, 1 first layer, 2 large hidden layers too (library default)")
     ap.add_argument("--no-implicit-momentum", action="store_true",
                     help="momentum rows read and written in every step (lc_set_implicit_momentum(0))")
     ap.add_argument("--no-first-layer-fusion", action="store_true",
@@ -110,6 +112,8 @@ def make_run(args, pkg, synth, name, cache):
     run.set_first_layer_fusion(not args.no_first_layer_fusion)
     run.set_deferred_update(not args.no_deferred_update)
     run.set_implicit_momentum(0 if args.no_implicit_momentum else 1)
+    if args.fused_averaging is not None:
+        run.set_fused_averaging(args.fused_averaging)
     run.set_xcd_local_exchange(not args.agent_scope_exchange)
     return w, run
 
@@ -159,6 +163,10 @@ def layer_bytes(w, rec, tau0, args, implicit_tau=0):
     the others (priced at 16 B)."""
     l = rec["layer"]
     n = w.dims[l - 1] * w.dims[l] + w.dims[l]
+    if rec["kernel_id"] == 3 and tau0 != 1:
+        # last step of a longer period, the layer's averaging in the same launch: every replica's
+        # weights and momentum (or older model) read, its momentum written, one averaged tile written
+        return (12.0 * w.m + 4.0) * w.dims[l - 1] * w.dims[l]
     if rec["kernel_id"] == 3:
         return (8.0 * w.m + 8.0) * w.dims[l - 1] * w.dims[l]
     if tau0 == 1 and not args.eager:
@@ -197,7 +205,8 @@ def bench_mlp(args, pkg, synth, name, cache, headline=True):
            "deferred_broadcast": not args.eager, "resident_step_kernel": resident,
            "first_layer_fusion": not args.no_first_layer_fusion,
            "deferred_update_at_tau_1": not args.no_deferred_update and not args.eager,
-           "implicit_momentum_inside_periods": run.implicit_momentum_layers() > 0}
+           "implicit_momentum_inside_periods": run.implicit_momentum_layers() > 0,
+           "fused_averaging_mode": 2 if args.fused_averaging is None else args.fused_averaging}
     if name == "cfg3":
         cfg["note"] = ("at this configuration's own learning rate and momentum the averaged model stays near ln 10 "
                        "with periods of 20, so the rule keeps tau near tau0: an adapting tau is not exercised here")

@@ -259,6 +259,23 @@ int lc_set_deferred_update(lc_handle* h, int on);
  *   mode 0: off -- x in X and v in V after every step. */
 int lc_set_implicit_momentum(lc_handle* h, int mode);
 
+/* The averaging step of large layers folded into the last local step of a period (Sec. 2: the
+ * k mod tau = 0 branch follows that step at once).  Inside lc_local_periods() and the schedule
+ * drivers, with tau > 1, the deferred broadcast on and block momentum off, the last step of a
+ * period does not write the rows of X for such a layer: one kernel owns the layer's weights by
+ * tile, walks over the workers, updates each worker's momentum tile from that worker's own weights
+ * and adds the worker's new weights to a sum kept in double; after the last worker the tile of the
+ * averaged model is written, and the averaging kernels skip the layer's weights (its biases are
+ * written to X and averaged as before).  Bit-identical to the step followed by the averaging
+ * step; 12 instead of 20-24 bytes per parameter and replica for the two together.  Layers as for
+ * the tile-owner kernel of tau = 1 (lc_set_deferred_update): 8 MB or more, rows of a multiple of
+ * 64 columns, not the last layer.
+ *   mode 1: the first layer (it needs no deltas for a layer below);
+ *   mode 2 (default): the hidden layers too (after a pass over the old weights that forms the
+ *           deltas of the layer below);
+ *   mode 0: off. */
+int lc_set_fused_averaging(lc_handle* h, int mode);
+
 /* Number of layers of this (attached) handle whose steps inside a period take the implicit form
  * under the current mode, operand type, sizes, learning rate and block-momentum setting (0 where
  * the resident step kernel runs the steps); negative on error. */

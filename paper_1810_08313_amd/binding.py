@@ -91,6 +91,8 @@ def lib() -> C.CDLL:
     L.lc_set_implicit_momentum.argtypes = [vp, C.c_int]
     L.lc_set_resident.restype = C.c_int
     L.lc_set_resident.argtypes = [vp, C.c_int]
+    L.lc_set_fused_averaging.restype = C.c_int
+    L.lc_set_fused_averaging.argtypes = [vp, C.c_int]
     L.lc_implicit_momentum_layers.restype = C.c_int
     L.lc_implicit_momentum_layers.argtypes = [vp]
     L.lc_resident_active.restype = C.c_int
@@ -325,6 +327,10 @@ class LocalSGD:
         """False/0: launch-per-layer kernels; True/1: resident step kernel where it applies; 2: and
         in-kernel averaging steps at every shape it handles (see lc_local_periods)."""
         self._check(self._L.lc_set_resident(self._h, int(on)), "lc_set_resident")
+
+    def set_fused_averaging(self, mode: int) -> None:
+        """0 off, 1 the first layer, 2 large hidden layers too (default) (see lc_set_fused_averaging)."""
+        self._check(self._L.lc_set_fused_averaging(self._h, int(mode)), "lc_set_fused_averaging")
 
     def implicit_momentum_layers(self) -> int:
         """Layers whose steps inside a period keep two consecutive models instead of model and momentum."""

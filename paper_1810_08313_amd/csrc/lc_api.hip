@@ -213,7 +213,7 @@ int one_local_step(lc_handle* h, bool next_gathered, bool implicit_out = false) 
         for (int l = head_is_fused(h) ? h->L - 1 : h->L; l >= 1; --l) {
             if (l == 1 && first_fused) {
                 LC_HIP(h, launch_first_layer(h));
-            } else if (h->defer_x && sync_layer_ok(h, l)) {
+            } else if ((h->defer_x || (h->fuse_avg && (l == 1 || h->fuse_avg_on > 1))) && sync_layer_ok(h, l)) {
                 if (l > 1) LC_HIP(h, launch_backward(h, l, true));   // dZ_{l-1} from the weights of before the update
                 LC_HIP(h, launch_sync_layer(h, l));   // dW_l, V, and the layer's part of the averaging step
                 h->sync_done |= 1u << l;
@@ -265,6 +265,8 @@ int run_periods(lc_handle* h, int tau, int n_periods, bool average) {
     const bool resident = mlp && h->res_on && h->res_a1x;
     const bool defer_ok = mlp && !resident && average && tau == 1 && h->defer_x_on && h->lazy_enabled &&
                           !h->bm_on && !head_is_fused(h);
+    const bool fuse_ok = mlp && !resident && average && tau > 1 && h->fuse_avg_on && h->lazy_enabled && !h->bm_on &&
+                         h->m >= 2 && !head_is_fused(h);
     int64_t left = static_cast<int64_t>(tau) * n_periods;
     int pos = 0;   // steps of the current period already taken
     while (left > 0) {
@@ -289,11 +291,14 @@ int run_periods(lc_handle* h, int tau, int n_periods, bool average) {
                 h->defer_x = defer;
                 for (int u = 0; u < in_period; ++u, ++t) {
                     h->train.cur_slot = t;
+                    // the last step of a longer period, the averaging step next: the large layers take
+                    // the step and their average together
+                    h->fuse_avg = fuse_ok && pos + u + 1 == tau;
                     // (the last step of a period -- of a call -- leaves x in X and v in V; a period
                     // longer than one gather launch stays implicit across the launches)
                     const int r = one_local_step(h, u + 1 < in_period, !defer && pos + u + 1 < tau);
                     if (r != LC_OK) {
-                        h->defer_x = false;
+                        h->defer_x = h->fuse_avg = false;
                         h->sync_done = 0;
                         return r;
                     }
@@ -304,7 +309,7 @@ int run_periods(lc_handle* h, int tau, int n_periods, bool average) {
                 pos = 0;
                 if (average) {
                     const int r = lc_average(h);   // (reads V instead of X while defer_x is set)
-                    h->defer_x = false;
+                    h->defer_x = h->fuse_avg = false;
                     h->sync_done = 0;
                     if (r != LC_OK) return r;
                 }
@@ -432,6 +437,8 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     h->defer_x_on = true;
     h->defer_x = false;
     h->sync1_on = h->sync_all_on = true;
+    h->fuse_avg_on = 2;
+    h->fuse_avg = false;
     if (const char* e = getenv("LC_SYNC_FIRST_LAYER")) {   // tuning knob for measurement runs: 0 off, 1 layer 1 only
         h->sync1_on = atoi(e) != 0;
         h->sync_all_on = atoi(e) > 1;
@@ -579,6 +586,12 @@ int lc_set_first_layer_fusion(lc_handle* h, int on) {
 int lc_set_implicit_momentum(lc_handle* h, int mode) {
     if (!h || mode < 0 || mode > 2) return LC_ERR_ARG;
     h->imp_mode = mode;
+    return LC_OK;
+}
+
+int lc_set_fused_averaging(lc_handle* h, int mode) {
+    if (!h || mode < 0 || mode > 2) return LC_ERR_ARG;
+    h->fuse_avg_on = mode;
     return LC_OK;
 }
 

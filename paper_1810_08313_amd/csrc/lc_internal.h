@@ -114,6 +114,11 @@ struct lc_handle {
     // is set while the averaging step of the iteration still has to skip the layer
     bool sync1_on, sync_all_on;   // layer 1 / the layers above it as well
     unsigned sync_done;           // bit l: the iteration in progress has averaged layer l's weights already
+    // Last step of a period of tau > 1 whose averaging step follows with the broadcast deferred: the
+    // large layers' tile-owner kernel forms the step and the layer's average together (the rows of X
+    // stay unwritten).  fuse_avg is set only while run_periods takes such a step and its averaging step.
+    int fuse_avg_on;              // 0 off, 1 the first layer, 2 the large hidden layers as well
+    bool fuse_avg;
     bool share_w_on;          // block order of the steps that read one model for all replicas (see FwdArgs)
     int share_w_set;          // ... replicas per set
     // resident local steps (small two-layer models): exchange buffer, barrier counters, switches

@@ -1450,7 +1450,7 @@ hipError_t launch_backward(lc_handle* h, int l, bool da_only) {
     const bool bf16 = h->md.gemm == LC_GEMM_BF16;
     BwdArgs a;
     const StepBufs sb = plan_step_buffers(h, l);
-    if (da_only && (sb.imp_in || !sb.ov)) return hipErrorInvalidValue;   // (the tau = 1 path: momentum is explicit there)
+    if (da_only && !sb.ov) return hipErrorInvalidValue;   // (only before a step that leaves v in V; the pass reads the weights alone)
     a.X = sb.ox;
     a.V = sb.ov;
     a.x_stride = h->Ps;

@@ -286,7 +286,7 @@ hipError_t launch_average(lc_handle* h, const float* X, float* out_rows, float* 
     int n_r = 0;
     {
         int64_t lo = 0;
-        for (int l = 1; l <= h->L && h->defer_x; ++l) {
+        for (int l = 1; l <= h->L && (h->defer_x || h->fuse_avg); ++l) {
             if (!(h->sync_done >> l & 1u)) continue;
             const int64_t w_lo = h->layer[l].w_off, w_hi = h->layer[l].b_off;
             if (w_lo > lo) { r_lo[n_r] = lo; r_hi[n_r] = w_lo; ++n_r; }

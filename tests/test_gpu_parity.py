@@ -1074,6 +1074,49 @@ def test_deferred_update_at_tau_1_is_bit_identical(pkg, orc, dims, m, B, bf16):
     defer.close()
 
 
+@pytest.mark.parametrize("bf16,m,d0,d1,mode,implicit", [
+    (True, 16, 2048, 1152, 1, 1),              # first layer; momentum implicit inside the period (the default at this size)
+    (False, 12, 2000, 1152, 1, 0),             # fp32 operands, a last row block that is partly padding
+    (False, 12, 2048, 1152, 1, 2),             # ... with the implicit form forced on
+    (True, 8, 2048, (1152, 1856), 2, 1),       # a hidden layer above 8 MB as well (after the dA-only pass)
+    (False, 16, 2048, (1152, 1856), 2, 0),
+])
+def test_fused_averaging_is_bit_identical(pkg, orc, bf16, m, d0, d1, mode, implicit):
+    """The last step of a period and the averaging of the large layers in one kernel
+    (lc_set_fused_averaging) against the same periods with the step and the averaging step apart:
+    periods of 3, 2 and 4 through the schedule driver and lc_local_periods, a learning-rate change
+    in between; model, buffers, losses bit for bit.  (Against the oracle these periods are held
+    by the other tests of this file, which run with the fusion on wherever it applies.)"""
+    dims, B = [d0, *(d1 if isinstance(d1, tuple) else (d1,)), 10], 24
+    _say(f"fused averaging bf16={bf16} m={m} dims={dims} mode={mode} implicit={implicit}")
+    runs = []
+    for fused in (mode, 0):
+        _, r = _problem(pkg, orc, dims, m, B, N=300, lr=0.05, wd=1e-4, bf16=bf16, mean_sd=0.03)
+        assert not r.resident_active()
+        r.set_lazy_broadcast(True)
+        r.set_implicit_momentum(implicit)
+        r.set_fused_averaging(fused)
+        runs.append(r)
+    for step, (tau, n) in enumerate([(3, 2), (2, 1), (4, 1)]):
+        outs = []
+        for r in runs:
+            if step == 0:
+                r.run(tau * n, tau)
+            else:
+                r.local_periods(tau, n)
+            outs.append((r.loss(), r.local_losses(), *r.get_state()))
+            if step == 1:
+                r.set_lr(0.02)
+        (la, lla, Xa, Va, ka), (lb, llb, Xb, Vb, kb) = outs
+        assert ka == kb
+        assert la == lb and np.array_equal(lla, llb), (tau, n)
+        assert np.array_equal(Xa.view(np.uint32), Xb.view(np.uint32)), (tau, n)
+        assert np.array_equal(Va.view(np.uint32), Vb.view(np.uint32)), (tau, n)
+        assert bool((Xa[1:] == Xa[0:1]).all())
+    for r in runs:
+        r.close()
+
+
 @pytest.mark.parametrize("bf16,m,d0,d1,tau,K", [
     (True, 16, 2048, 1100, 1, 3), (False, 16, 2048, 1100, 1, 3),   # two sets of 8 replicas
     (False, 12, 2048, 1100, 1, 3),                                 # one set of 12
