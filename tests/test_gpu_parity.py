@@ -1608,6 +1608,18 @@ def test_full_size_period_sampled_replicas(pkg, orc, name, replicas):
     assert np.array_equal(Xa[0, cols].view(np.uint32), want.view(np.uint32))
     assert all(np.array_equal(Xa[i], Xa[0]) for i in range(1, w.m))
     run.close()
+    # the same period as the benchmark takes it: one lc_local_periods call, in which the last step and
+    # the averaging of the large layers are one kernel per layer -- bit for bit the same model and buffers
+    del X, ref
+    again = pkg.LocalSGD(w.m, gmd, w.seed, w.x1, w.data, w.labels)
+    again.set_lazy_broadcast(True)
+    again.local_periods(tau, 1)
+    Xb, Vb, kb = again.get_state()
+    again.close()
+    assert kb == tau
+    assert np.array_equal(Xb[0].view(np.uint32), Xa[0].view(np.uint32))
+    assert all(np.array_equal(Xb[i], Xb[0]) for i in range(1, w.m))
+    assert np.array_equal(Vb.view(np.uint32), V.view(np.uint32))
 
 
 def test_cfg2_full_configuration_periods(pkg, orc):
