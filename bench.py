@@ -36,8 +36,10 @@ HBM_PEAK_GBS = 8000.0
 MFMA_FP32_PEAK_TFLOPS = 157.3
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
-DEFAULT_STEPS = {"cfg1": 2000, "cfg2": 2000, "cfg3": 200, "cfg4": 40, "cfg5a": 50, "cfg5b": 20}
-DEFAULT_WARMUP = {"cfg1": 100, "cfg2": 100, "cfg3": 20, "cfg4": 5, "cfg5a": 5, "cfg5b": 3}
+# (cfg3, cfg4: twice the configuration's loss-evaluation interval, so that the timed steps hold the
+# evaluations and decisions of the schedule at their own spacing)
+DEFAULT_STEPS = {"cfg1": 2000, "cfg2": 2000, "cfg3": 1000, "cfg4": 400, "cfg5a": 50, "cfg5b": 20}
+DEFAULT_WARMUP = {"cfg1": 100, "cfg2": 100, "cfg3": 20, "cfg4": 10, "cfg5a": 5, "cfg5b": 3}
 FLAT = {"cfg5a": (16, 25_600_000), "cfg5b": (8, 138_000_000)}
 MIN_TIMED_S = 0.5          # the K-step schedule is repeated until this much has been timed
 KERNEL_NAMES = {1: "backward_kernel", 2: "first_layer_kernel", 3: "sync_first_layer_kernel", 4: "head_kernel",
@@ -215,7 +217,7 @@ def bench_mlp(args, pkg, synth, name, cache, headline=True):
         return out
 
     # roofline of the dominant kernel: further passes over K2 steps with HIP events around its launches
-    K2 = min(K, 200)
+    K2 = min(K, 100)
     kernels, n_all, ms_all = dominant_kernel(run, w, K2, tau0)
     dom = kernels[0]
     if resident:
