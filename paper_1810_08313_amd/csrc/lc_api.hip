@@ -397,6 +397,8 @@ int lc_init(int m, int64_t P, const lc_model* md, uint64_t seed, lc_handle** out
     }
     if (const char* e = getenv("LC_AVG_TWO_PHASE")) h->avg_two_phase = atoi(e) != 0;
     h->share_w_on = true;
+    h->group_shared_on = true;
+    if (const char* e = getenv("LC_GROUP_SHARED")) h->group_shared_on = atoi(e) != 0;   // tuning knob for measurement runs
     h->share_w_set = 8;
     if (const char* e = getenv("LC_SHARED_W_ORDER")) {   // 0: replica-major everywhere; n: sets of n replicas
         h->share_w_on = atoi(e) != 0;

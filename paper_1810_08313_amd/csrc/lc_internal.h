@@ -120,6 +120,7 @@ struct lc_handle {
     int fuse_avg_on;              // 0 off, 1 the first layer, 2 the large hidden layers as well
     bool fuse_avg;
     bool share_w_on;          // block order of the steps that read one model for all replicas (see FwdArgs)
+    bool group_shared_on;     // ... and several replicas' batches per block in them (see FwdArgs::fm_Bp)
     int share_w_set;          // ... replicas per set
     // resident local steps (small two-layer models): exchange buffer, barrier counters, switches
     float* res_a1x;         // [2 parities][m][dp1/16][Bp][16] exchange buffer of the resident kernel, null when the shape does not qualify

@@ -192,6 +192,12 @@ struct FwdArgs {
     float* loss;            // [G]
     int eval;               // 1: loss[g] = sum over valid samples; 0: mean over B
     const void* a_in_fm;    // [G][dp_in][Bp] of OT: the same activations feature-major (AFM instances)
+    // Steps in which all replicas read one model may hand several replicas' batches to one block as
+    // one batch of Bp rows (their batch-major activations lie one after the other): the weight tile
+    // then crosses the L2 once per set of replicas instead of once per replica.  Bp is the batch of
+    // such a set, fm_Bp the padded batch of ONE replica, by which the feature-major copies are laid
+    // out (equal when nothing is grouped).
+    int fm_Bp;
     int shared_w;           // > 0: every group reads the same weights from memory (x_stride 0, training step
                             // right after an averaging step) and neighbouring blocks take the same tile of W
                             // for different replicas, in sets of this many replicas (see shared_order), so
@@ -502,6 +508,18 @@ __global__ __launch_bounds__(NW * 64) void forward_kernel(FwdArgs a) {
                 const int cl = e / (MT * 2), bl = (e % (MT * 2)) * 8;
                 const int b = row0 + bl, c = c0 + cl;
                 if (b >= a.B || c >= a.d_out) continue;
+                if (a.fm_Bp != a.Bp) {
+                    // several replicas' batches in this block (all rows valid, see launch_forward): the
+                    // 8 entries belong to replica b / fm_Bp of the set, whose copy has rows of fm_Bp
+                    float y[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const float z = red[tile_row(bl + i)][cl] + bias_s[cl];
+                        y[i] = z > 0.f ? z : 0.f;
+                    }
+                    store8(ofm + (static_cast<int64_t>(b / a.fm_Bp) * a.dp_out + c) * a.fm_Bp + b % a.fm_Bp, y);
+                    continue;
+                }
                 float y[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
@@ -600,6 +618,8 @@ struct BwdArgs {
     int col_split;       // workgroups sharing one row block's columns (1 when dA is needed)
     int shared_w;        // > 0: all replicas read the same weights (xr_stride 0) and neighbouring blocks take
                          // the same rows of W for different replicas, in sets of this many (see FwdArgs)
+    int fm_Bp;           // DAO instances: padded batch of ONE replica when a block takes the batches of several
+                         // (see FwdArgs::fm_Bp); the feature-major buffers are laid out by it.  Else = Bp
     int skip_x;          // V is updated, X is left unwritten: the averaging step that follows forms
                          // every replica's new weights from Xr and V itself (tau = 1, deferred update)
     int64_t total_blocks;
@@ -683,13 +703,19 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
     }
 
     // ReLU gates of this lane's dA entries, fetched now (one bit each) instead of after the walk
+    // (DAO instances may hold several replicas' batches: entry b of the block is entry b % fm_Bp of
+    // replica b / fm_Bp of the set, and every replica's feature-major copy has rows of fm_Bp)
+    auto fm_at = [&](int row, int b, int dp) {
+        if constexpr (DAO) return (static_cast<int64_t>(b / a.fm_Bp) * dp + row) * a.fm_Bp + b % a.fm_Bp;
+        else return static_cast<int64_t>(row) * Bp + b;
+    };
     uint32_t gate = 0;
     if (need_da) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                if (to_f32(AT[static_cast<int64_t>(k0 + 4 * q + r) * Bp + 16 * nt + j]) > 0.f) gate |= 1u << (nt * 4 + r);
+                if (to_f32(AT[fm_at(k0 + 4 * q + r, 16 * nt + j, a.dp_in)]) > 0.f) gate |= 1u << (nt * 4 + r);
     }
 
     float4 w[4], v[4], wn[4], vn[4];
@@ -862,7 +888,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdArgs a) {
             for (int r = 0; r < 4; ++r) {
                 const int row = k0 + 4 * q + r;
                 d[r] = ((gate >> (nt * 4 + r)) & 1u) ? dacc[nt][r] : 0.f;
-                pfm[static_cast<int64_t>(row) * Bp + b] = static_cast<OT>(d[r]);
+                pfm[fm_at(row, b, a.dp_in)] = static_cast<OT>(d[r]);
             }
             store4<OT>(pbm + static_cast<int64_t>(b) * a.dp_in + k0 + 4 * q, d[0], d[1], d[2], d[3]);
         }
@@ -1330,6 +1356,21 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     a.dp_out = g.dp_out;
     a.B = S.B;
     a.Bp = S.Bp;
+    a.fm_Bp = S.Bp;
+    // one model for all replicas, every batch row valid, not the last layer (whose epilogue works
+    // per replica): sets of replicas as one batch of up to 128 rows
+    int n_groups = S.G;
+    if (!eval && shared && h->group_shared_on && l < h->L && S.B == S.Bp && S.Bp < 128) {
+        int gr = 128 / S.Bp;
+        while (gr > 1 && S.G % gr != 0) gr /= 2;
+        // (not when that leaves most of the chip idle)
+        while (gr > 1 && static_cast<int64_t>(S.G / gr) * (g.dp_out / kColChunk) < 256) gr /= 2;
+        if (gr > 1) {
+            a.B = a.Bp = S.Bp * gr;
+            n_groups = S.G / gr;
+        }
+    }
+    const bool grouped = n_groups != S.G;
     a.a_in = l == 1 ? a0_ptr(h, S, S.a_bm[0], eval) : S.a_bm[l - 1];
     a.out_bm = S.a_bm[l];
     a.out_fm = S.a_fm[l];
@@ -1344,16 +1385,16 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     a.dz_fm = eval ? nullptr : S.dz_fm[h->L];
     a.loss = S.loss + static_cast<int64_t>(loss_offset) * kLossParts;
     a.eval = eval ? 1 : 0;
-    a.shared_w = (!eval && shared && shared_weight_order(h, g)) ? shared_set(h, S.G) : 0;
+    a.shared_w = (!eval && shared && shared_weight_order(h, g)) ? shared_set(h, n_groups) : 0;
     // batch tiles per block: all of them, unless that leaves most of the chip idle
-    int mt = mt_for(S.Bp);
+    int mt = mt_for(a.Bp);
     a.m_split = 1;
-    while (mt > 1 && static_cast<int64_t>(S.G) * a.n_chunks * a.m_split < 256) {
+    while (!grouped && mt > 1 && static_cast<int64_t>(S.G) * a.n_chunks * a.m_split < 256) {
         mt /= 2;
         a.m_split *= 2;
     }
     if (a.fuse_softmax) (eval ? h->loss_parts_eval : h->loss_parts_train) = a.m_split;
-    a.total_blocks = static_cast<int64_t>(S.G) * a.n_chunks * a.m_split;
+    a.total_blocks = static_cast<int64_t>(n_groups) * a.n_chunks * a.m_split;
     const unsigned grid = xcd_grid(a.total_blocks);
     // few blocks: split the reduction over more wavefronts per block
     const bool wide = a.total_blocks * 4 < 2048 && g.dp_in >= 512;
@@ -1361,7 +1402,7 @@ hipError_t launch_forward(lc_handle* h, bool eval, int l, int loss_offset) {
     hipError_t e;
     // whole padded batch in one block and a feature-major copy of the input at hand
     const void* in_fm = eval ? nullptr : (l == 1 ? a0_ptr(h, S, S.a_fm[0], false) : S.a_fm[l - 1]);
-    const bool afm = in_fm != nullptr && a.m_split == 1 && mt * 16 == S.Bp && mt == 8;
+    const bool afm = in_fm != nullptr && !grouped && a.m_split == 1 && mt * 16 == S.Bp && mt == 8;
     a.a_in_fm = in_fm;
     if (bf16) e = launch_fwd_wm<bf16_t>(a, mt, wide, afm, grid, h->stream);
     else e = launch_fwd_wm<float>(a, mt, wide, afm, grid, h->stream);
@@ -1482,7 +1523,20 @@ hipError_t launch_backward(lc_handle* h, int l, bool da_only) {
     a.n_row_blocks = g.dp_in / 64;
     a.col_split = 1;
     a.skip_x = h->defer_x ? 1 : 0;
-    a.shared_w = (sb.xr_stride == 0 && shared_weight_order(h, g)) ? shared_set(h, S.G) : 0;
+    a.fm_Bp = S.Bp;
+    // the dA-only pass over one model that all replicas share: sets of replicas as one batch of up
+    // to 128 rows (see launch_forward)
+    int n_groups = S.G;
+    if (da_only && sb.xr_stride == 0 && h->group_shared_on && S.B == S.Bp && S.Bp < 128) {
+        int gr = 128 / S.Bp;
+        while (gr > 1 && S.G % gr != 0) gr /= 2;
+        while (gr > 1 && static_cast<int64_t>(S.G / gr) * (g.dp_in / 64) < 256) gr /= 2;
+        if (gr > 1) {
+            a.B = a.Bp = S.Bp * gr;
+            n_groups = S.G / gr;
+        }
+    }
+    a.shared_w = (sb.xr_stride == 0 && shared_weight_order(h, g)) ? shared_set(h, n_groups) : 0;
     if (l == 1) {
         // no dA: the columns can be shared out, to fill the chip and to keep the walk of a
         // workgroup short (measured: walks of 2-4 trips stream faster than long ones, a single
@@ -1500,15 +1554,15 @@ hipError_t launch_backward(lc_handle* h, int l, bool da_only) {
         // 155 us with 4 or 8 per row block, 191 us with 16)
         if (h->stream_weights && a.col_split < n_cc * 32 / S.Bp) a.col_split = n_cc * 32 / S.Bp;
     }
-    a.total_blocks = static_cast<int64_t>(S.G) * a.n_row_blocks * a.col_split;
+    a.total_blocks = static_cast<int64_t>(n_groups) * a.n_row_blocks * a.col_split;
     const unsigned grid = xcd_grid(a.total_blocks);
     // (same conditions as the tile-owner kernel that follows; the columns are not shared out here)
     if (da_only && (l < 2 || !a.vec || g.d_out % kColChunk != 0 || !a.stream)) return hipErrorInvalidValue;
     timing_start(h, kTimeBwd, l, kBwdRowOwner);
     hipError_t e;
     if (da_only) {
-        e = bf16 ? launch_bwd_da_only<bf16_t>(a, S.Bp / 16, grid, h->stream)
-                 : launch_bwd_da_only<float>(a, S.Bp / 16, grid, h->stream);
+        e = bf16 ? launch_bwd_da_only<bf16_t>(a, a.Bp / 16, grid, h->stream)
+                 : launch_bwd_da_only<float>(a, a.Bp / 16, grid, h->stream);
     } else {
         e = bf16 ? launch_bwd_wm<bf16_t>(a, S.Bp / 16, grid, h->stream)
                  : launch_bwd_wm<float>(a, S.Bp / 16, grid, h->stream);
