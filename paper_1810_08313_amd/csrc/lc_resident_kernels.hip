@@ -729,6 +729,20 @@ size_t resident_exchange_floats(const lc_handle* h) {
     return 2 * static_cast<size_t>(h->m) * h->train.Bp * h->layer[1].dp_out;
 }
 
+// Workgroups of the resident kernel that can be on the chip at the same time: one per compute unit
+// (16 wavefronts and 66 KB and more of LDS each) of the current device -- 256 on the MI355X this is
+// written for, fewer on a partition of it.  Without a device (host-only use of the library) the
+// full chip is assumed; the kernel's bounded barrier wait remains the last line of defence.
+static int resident_workgroup_budget() {
+    static const int budget = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return 256;
+        return cus < 256 ? cus : 256;   // (the exchange buffers and counters are sized for 256)
+    }();
+    return budget;
+}
+
 // Two layers, at most 16 classes and 64 samples, widths within the LDS budget, and few enough
 // workgroups that all of them are on the chip at the same time (one per compute unit); or one
 // layer of at most 256 (padded) inputs and 16 classes.
@@ -738,7 +752,7 @@ bool resident_shape_ok(const lc_handle* h) {
     if (h->L != 2) return false;
     if (h->layer[2].d_out > 16) return false;
     if (h->layer[1].dp_in > kResMaxD0 || h->layer[1].dp_out > kResMaxD1) return false;
-    return h->m <= 64 && static_cast<int64_t>(h->m) * (h->layer[1].dp_out / 16) <= 256;
+    return h->m <= 64 && static_cast<int64_t>(h->m) * (h->layer[1].dp_out / 16) <= resident_workgroup_budget();
 }
 
 namespace {
@@ -777,7 +791,7 @@ hipError_t launch_resident1(lc_handle* h, int slot0, int n_steps, int period) {
     a.err = h->res_ctr + 64;
     a.spin_limit = h->res_spin_limit;
     if (slot0 < 0 || n_steps < 1 || slot0 + n_steps > S.slots) return hipErrorInvalidValue;
-    if (period < 0 || (period > 0 && (n_steps % period != 0 || !h->res_avx || S.G > 256))) return hipErrorInvalidValue;
+    if (period < 0 || (period > 0 && (n_steps % period != 0 || !h->res_avx || S.G > resident_workgroup_budget()))) return hipErrorInvalidValue;
     if (S.Bp != 32 && S.Bp != 64) return hipErrorInvalidValue;
     if (a.dp0 > kResMaxD1 || a.d1 > 16) return hipErrorInvalidValue;
     timing_start(h, kTimeBwd, 0, kBwdResident);
@@ -850,7 +864,7 @@ hipError_t launch_resident(lc_handle* h, int slot0, int n_steps, int period) {
     if (slot0 < 0 || n_steps < 1 || slot0 + n_steps > S.slots) return hipErrorInvalidValue;
     if (period < 0 || (period > 0 && (n_steps % period != 0 || !h->res_avx))) return hipErrorInvalidValue;
     const int64_t total = static_cast<int64_t>(a.G) * a.NB;
-    if (total > 256 || a.G > 64 || !h->res_a1x) return hipErrorInvalidValue;
+    if (total > resident_workgroup_budget() || a.G > 64 || !h->res_a1x) return hipErrorInvalidValue;
     const unsigned grid = static_cast<unsigned>((total + kXcds - 1) / kXcds * kXcds);
     if (S.Bp != 32 && S.Bp != 64) return hipErrorInvalidValue;
     timing_start(h, kTimeBwd, 0, kBwdResident);
